@@ -1,0 +1,201 @@
+/*
+ * CPU oracle for the verify-step MoE layer of MoE-SpAc.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP kernels are checked against.  It shares no code with them and nothing
+ * in the product path may link or call it; only the tests, the smoke check
+ * and the bench's cpu_baseline leg do.
+ *
+ * Everything is the defining formula written out, in fp64, on bf16-rounded
+ * inputs, with no blocking, fusion or reordering:
+ *   - routing, gating, expert mixture: Sec. 2.2, the four-line MoE equation
+ *     (s = W_g h; Top-k; g_i = exp(s_i)/sum_{j in Top-k} exp(s_j);
+ *      y = sum_{i in Top-k} g_i E_i(h));
+ *   - activation frequency f_{i,t}: Sec. 2.3 "Activation Frequency";
+ *   - resident / missed split with a sentinel id: App. D (the ids rewrite,
+ *     skipped experts, and the join of the two partial results);
+ *   - the expert is the gate/up/down FFN named in App. D; the activation is
+ *     SiLU on the gate branch (SwiGLU), biases absent.
+ *
+ * Readings where the paper is silent: ties in Top-k go to the lower expert
+ * id; the k ids of a token are listed by descending logit; the sentinel is
+ * -1; gates are normalised over the full Top-k set even when some of those
+ * experts are not resident (the device result is a partial sum that the
+ * host's share completes); shared experts are added with weight 1 for every
+ * token and are outside routing, histogram and miss list.
+ *
+ * Pinned by tests/test_oracle_pins.py (brute-force dense evaluation in
+ * numpy, textbook SwiGLU through torch's own linear/silu, closed forms,
+ * the worked example of App. C.1, invariants).  No function here is
+ * "parity unpinned".
+ *
+ * Optional threading: a bare "omp parallel for" over output rows; the
+ * per-element summation order does not depend on the thread count.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double bf16_to_f64(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* s[t,e] = sum_h W_g[e,h] * h_t[h] (+ bias[e])      -- Sec. 2.2, first line */
+void oracle_router_logits(const uint16_t *hidden, const float *router_w, const float *bias,
+                          int T, int H, int E, double *logits)
+{
+    for (int t = 0; t < T; ++t)
+        for (int e = 0; e < E; ++e) {
+            double s = 0.0;
+            for (int h = 0; h < H; ++h)
+                s += (double)router_w[(size_t)e * H + h] * bf16_to_f64(hidden[(size_t)t * H + h]);
+            if (bias) s += (double)bias[e];
+            logits[(size_t)t * E + e] = s;
+        }
+}
+
+/* Top-k by k passes of arg-max (larger logit first, lower id on equality) and
+ * the gate restricted to the selected set      -- Sec. 2.2, lines two and three */
+void oracle_topk_gate(const double *logits, int T, int E, int k, int32_t *topk_idx, double *gate)
+{
+    char *taken = (char *)malloc((size_t)E);
+    for (int t = 0; t < T; ++t) {
+        const double *s = logits + (size_t)t * E;
+        memset(taken, 0, (size_t)E);
+        for (int j = 0; j < k; ++j) {
+            int best = -1;
+            for (int e = 0; e < E; ++e) {
+                if (taken[e]) continue;
+                if (best < 0 || s[e] > s[best]) best = e;
+            }
+            taken[best] = 1;
+            topk_idx[(size_t)t * k + j] = best;
+        }
+        double smax = s[topk_idx[(size_t)t * k]];
+        double den = 0.0;
+        for (int j = 0; j < k; ++j) den += exp(s[topk_idx[(size_t)t * k + j]] - smax);
+        for (int j = 0; j < k; ++j)
+            gate[(size_t)t * k + j] = exp(s[topk_idx[(size_t)t * k + j]] - smax) / den;
+    }
+    free(taken);
+}
+
+/* f_i = number of (token, rank) pairs that selected expert i  -- Sec. 2.3 */
+void oracle_expert_histogram(const int32_t *topk_idx, int T, int k, int E, int32_t *hist)
+{
+    for (int e = 0; e < E; ++e) hist[e] = 0;
+    for (int a = 0; a < T * k; ++a) hist[topk_idx[a]] += 1;
+}
+
+/* ids rewrite: expert id -> cache slot, -1 when not resident; the missed
+ * assignments (flat id a = t*k + j) in ascending order      -- App. D */
+void oracle_slot_resolve(const int32_t *topk_idx, const int32_t *slot_table, int T, int k,
+                         int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count)
+{
+    int n = 0;
+    for (int a = 0; a < T * k; ++a) {
+        int32_t c = slot_table[topk_idx[a]];
+        slot_idx[a] = c;
+        if (c < 0) miss_list[n++] = a;
+    }
+    *miss_count = n;
+}
+
+/* One expert on one token: o = W_down ( silu(W_gate x) * (W_up x) ), added
+ * into y with weight g.  w_gate/w_up are [F,H], w_down is [H,F] (row = output). */
+static void expert_ffn_add(const uint16_t *x_bits, const uint16_t *w_gate, const uint16_t *w_up,
+                           const uint16_t *w_down, int H, int F, double g, double *y)
+{
+    double *x = (double *)malloc(sizeof(double) * (size_t)H);
+    double *m = (double *)malloc(sizeof(double) * (size_t)F);
+    for (int h = 0; h < H; ++h) x[h] = bf16_to_f64(x_bits[h]);
+#pragma omp parallel for schedule(static)
+    for (int f = 0; f < F; ++f) {
+        double a = 0.0, u = 0.0;
+        for (int h = 0; h < H; ++h) a += bf16_to_f64(w_gate[(size_t)f * H + h]) * x[h];
+        for (int h = 0; h < H; ++h) u += bf16_to_f64(w_up[(size_t)f * H + h]) * x[h];
+        m[f] = (a / (1.0 + exp(-a))) * u;
+    }
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < H; ++h) {
+        double o = 0.0;
+        for (int f = 0; f < F; ++f) o += bf16_to_f64(w_down[(size_t)h * F + f]) * m[f];
+        y[h] += g * o;
+    }
+    free(x);
+    free(m);
+}
+
+/* y_t = sum over the token's RESIDENT selected experts of g * E_i(h_t)
+ *                                     -- Sec. 2.2 last line, restricted per App. D.
+ * Weights are indexed by EXPERT id in the full [E,...] set.  slot_table only
+ * decides residency.  y is [T,H] fp64 and is overwritten. */
+void oracle_routed_ffn(const uint16_t *hidden, const int32_t *topk_idx, const double *gate,
+                       const int32_t *slot_table, const uint16_t *w_gate, const uint16_t *w_up,
+                       const uint16_t *w_down, int T, int H, int F, int k, double *y)
+{
+    for (size_t i = 0; i < (size_t)T * H; ++i) y[i] = 0.0;
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < k; ++j) {
+            int e = topk_idx[(size_t)t * k + j];
+            if (slot_table[e] < 0) continue;
+            size_t off = (size_t)e * F * H;
+            expert_ffn_add(hidden + (size_t)t * H, w_gate + off, w_up + off, w_down + off, H, F,
+                           gate[(size_t)t * k + j], y + (size_t)t * H);
+        }
+}
+
+/* always-on experts: y_t += E_s(h_t) for every token and every shared expert */
+void oracle_shared_ffn_add(const uint16_t *hidden, const uint16_t *sh_gate, const uint16_t *sh_up,
+                           const uint16_t *sh_down, int T, int H, int Fs, int n_shared, double *y)
+{
+    for (int t = 0; t < T; ++t)
+        for (int s = 0; s < n_shared; ++s) {
+            size_t off = (size_t)s * Fs * H;
+            expert_ffn_add(hidden + (size_t)t * H, sh_gate + off, sh_up + off, sh_down + off, H, Fs,
+                           1.0, y + (size_t)t * H);
+        }
+}
+
+/* The whole layer for one verification batch, in the order of the steps. */
+void oracle_verify_layer(const uint16_t *hidden, const float *router_w, const float *router_bias,
+                         const int32_t *slot_table, const uint16_t *w_gate, const uint16_t *w_up,
+                         const uint16_t *w_down, const uint16_t *sh_gate, const uint16_t *sh_up,
+                         const uint16_t *sh_down, int T, int H, int E, int k, int F, int n_shared,
+                         int Fs, double *logits, int32_t *topk_idx, double *gate, int32_t *hist,
+                         int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, double *y)
+{
+    oracle_router_logits(hidden, router_w, router_bias, T, H, E, logits);
+    oracle_topk_gate(logits, T, E, k, topk_idx, gate);
+    oracle_expert_histogram(topk_idx, T, k, E, hist);
+    oracle_slot_resolve(topk_idx, slot_table, T, k, slot_idx, miss_list, miss_count);
+    oracle_routed_ffn(hidden, topk_idx, gate, slot_table, w_gate, w_up, w_down, T, H, F, k, y);
+    if (n_shared > 0)
+        oracle_shared_ffn_add(hidden, sh_gate, sh_up, sh_down, T, H, Fs, n_shared, y);
+}

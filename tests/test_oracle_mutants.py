@@ -1,0 +1,50 @@
+"""Plant plausible mistakes in the oracle (on the CPU, in a temporary copy of its
+source) and require that the pins catch every one of them."""
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import oracle_pins
+
+SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "moe_oracle.c")
+
+MUTANTS = {
+    "silu_on_up_branch": ("m[f] = (a / (1.0 + exp(-a))) * u;", "m[f] = (u / (1.0 + exp(-u))) * a;"),
+    "silu_sign": ("exp(-a)", "exp(a)"),
+    "down_transposed": ("w_down[(size_t)h * F + f]", "w_down[(size_t)f * H + h]"),
+    "gate_transposed": ("w_gate[(size_t)f * H + h]", "w_gate[(size_t)h * F + f]"),
+    "up_reads_gate": ("bf16_to_f64(w_up[", "bf16_to_f64(w_gate["),
+    "tie_break_high_id": ("s[e] > s[best]", "s[e] >= s[best]"),
+    "slot_zero_is_miss": ("if (slot_table[e] < 0) continue;", "if (slot_table[e] <= 0) continue;"),
+    "gate_weight_dropped": ("y[h] += g * o;", "y[h] += o;"),
+    "hist_saturates": ("hist[topk_idx[a]] += 1;", "hist[topk_idx[a]] = 1;"),
+    "miss_list_holds_expert": ("miss_list[n++] = a;", "miss_list[n++] = topk_idx[a];"),
+    "bias_dropped": ("if (bias) s += (double)bias[e];", ""),
+    "router_transposed": ("router_w[(size_t)e * H + h]", "router_w[(size_t)h * E + e]"),
+    "shared_weight_half": ("1.0, y + (size_t)t * H);", "0.5, y + (size_t)t * H);"),
+    "weights_by_slot": ("size_t off = (size_t)e * F * H;", "size_t off = (size_t)slot_table[e] * F * H;"),
+    "gate_not_normalised": ("- smax) / den;", "- smax);"),
+    "descending_order_lost": ("topk_idx[(size_t)t * k + j] = best;", "topk_idx[(size_t)t * k + (k - 1 - j)] = best;"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_mutant_is_caught(name, tmp_path):
+    old, new = MUTANTS[name]
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found"
+    mutated = text.replace(old, new)
+    c = tmp_path / "mutant.c"
+    so = tmp_path / "mutant.so"
+    c.write_text(mutated)
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-shared", "-fPIC", "-o", str(so), str(c), "-lm"])
+    O = oracle.Oracle(str(so))
+    caught = []
+    for pin in oracle_pins.ALL_PINS:
+        try:
+            pin(O)
+        except AssertionError:
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"

@@ -1,0 +1,123 @@
+/*
+ * moe_spac.h -- C-ABI of the MI355X (gfx950) verify-step MoE layer.
+ *
+ * One call of moe_verify_layer is the MoE layer forward for one speculative-
+ * decoding verification batch of T = gamma + 1 tokens (Sec. 2.1): routing and
+ * gating (Sec. 2.2), the activation-frequency histogram that the Speculative
+ * Utility Estimator consumes (Sec. 2.3, Alg. 1 "observe activation
+ * frequencies"), the rewrite of expert ids into cache slots with non-resident
+ * experts marked by a sentinel and listed for the host (App. D), and the
+ * gate/up/down expert FFN over the resident experts with the weighted
+ * combine back into token order (Sec. 2.2 last line; App. D).
+ *
+ * Conventions for every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller, unless the
+ *     comment says "host".  The library never allocates, frees or keeps a
+ *     pointer.  Scratch comes from the caller's `workspace`.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; no call synchronises.  Outputs (miss_count
+ *     included) are valid once the caller has synchronised the stream.
+ *   - Layouts are row-major, innermost index last.  bf16 tensors are raw
+ *     16-bit patterns (void*).  Notation: T tokens, H hidden size, E routed
+ *     experts, k experts per token, F expert FFN width, C cache capacity in
+ *     slots, A = T*k assignments (flat id a = t*k + j).
+ *   - Return value: MOE_OK, or a negative code; on a negative code nothing
+ *     was launched.  No exceptions, no abort, nothing printed.
+ *   - Supported sizes: 1 <= k <= min(E, 64); E <= 512; C <= 1024; H and F
+ *     multiples of 32; H <= 4992; bf16 tensors and `out` 16-byte aligned.
+ *   - Two calls that share a workspace must not overlap in time.
+ */
+#ifndef MOE_SPAC_H
+#define MOE_SPAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MOE_OK = 0,
+    MOE_ERR_NULL = -1,      /* a required pointer is NULL                              */
+    MOE_ERR_SHAPE = -2,     /* a size is out of the supported range                    */
+    MOE_ERR_ALIGN = -3,     /* H or F not a multiple of 32, or a misaligned pointer     */
+    MOE_ERR_WORKSPACE = -4, /* workspace_bytes is smaller than the call needs          */
+    MOE_ERR_LAUNCH = -5     /* the HIP runtime refused a launch or an attribute        */
+};
+
+/* Problem sizes of one layer call.  n_shared always-on experts of width
+ * F_shared each (0 = none); they are not routed, not cached and not counted. */
+typedef struct moe_shape {
+    int T, H, E, k, F, C;
+    int n_shared, F_shared;
+} moe_shape_t;
+
+/* Host-only, pure.  Static text for a status code (never NULL). */
+const char *moe_status_string(int status);
+
+/* Host-only, pure.  Bytes of workspace that any entry point needs for `shape`
+ * (an upper bound for the single-step entry points).  shape: host pointer. */
+int moe_workspace_bytes(const moe_shape_t *shape, size_t *bytes_out);
+
+/* Clears the control block at the start of a freshly allocated workspace.
+ * Call once per workspace before its first use; every entry point leaves the
+ * control block cleared again when its kernels finish. */
+int moe_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* Step 1 -- Sec. 2.2, lines one to three of the MoE equation.
+ *   s = W_g h (+ bias), the k largest logits per token (listed by descending
+ *   logit, ties to the lower expert id), g = softmax restricted to those k.
+ * hidden [T,H] bf16; router_w [E,H] fp32; router_bias [E] fp32 or NULL (NULL
+ * is the paper's equation); topk_idx [T,k] int32 out; topk_w [T,k] fp32 out;
+ * logits_opt [T,E] fp32 out or NULL. */
+int moe_route_topk(const void *hidden, const float *router_w, const float *router_bias, int T, int H,
+                   int E, int k, int32_t *topk_idx, float *topk_w, float *logits_opt, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
+/* Step 2 -- Sec. 2.3 "Activation Frequency": hist[e] = number of assignments
+ * that selected expert e over the T tokens of this step (the f_{e,t} that
+ * Alg. 1 observes).  topk_idx [T,k] int32 with values in [0,E); hist [E] int32
+ * out (overwritten).  Ids outside [0,E) are ignored. */
+int moe_expert_histogram(const int32_t *topk_idx, int T, int k, int E, int32_t *hist, void *stream);
+
+/* Step 3 -- App. D: the ids rewrite.  slot_idx[a] = slot_table[topk_idx[a]],
+ * -1 when the expert is not resident; miss_list = the flat ids a of the
+ * missed assignments in ascending order (the host's share of the layer);
+ * miss_count [1].  slot_table [E] int32: -1 or a slot in [0,C), distinct
+ * experts in distinct slots; a value outside [0,C) is treated as -1.
+ * miss_list must hold T*k entries.  The per-slot token lists (the
+ * expert-sorted permutation that step 4 consumes) are left in `workspace`. */
+int moe_slot_resolve(const int32_t *topk_idx, const int32_t *slot_table, int T, int k, int E, int C,
+                     int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/* Step 4 -- Sec. 2.2 last line, restricted to resident experts (App. D):
+ *   out[t,:] (+)= sum over j with slot_idx[t,j] >= 0 of
+ *        topk_w[t,j] * W_down[c] ( silu(W_gate[c] x_t) * (W_up[c] x_t) ),  c = slot_idx[t,j].
+ * Pools are slot-major: w_gate, w_up [C,F,H] bf16, w_down [C,H,F] bf16 (each
+ * matrix [out,in]).  bf16 products, fp32 accumulation; the activation is
+ * rounded to bf16 before the down projection.  Missed assignments add
+ * nothing.  out [T,H] fp32, or bf16 when out_bf16 != 0; accumulate != 0 adds
+ * to what `out` holds (the join with the host's partial result), else `out`
+ * is overwritten.  Slots outside [0,C) in slot_idx are treated as -1. */
+int moe_grouped_ffn(const void *hidden, const float *topk_w, const int32_t *slot_idx, const void *w_gate,
+                    const void *w_up, const void *w_down, int T, int H, int F, int k, int C, void *out,
+                    int out_bf16, int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Steps 1-4 for one verification batch in three launches on `stream`.
+ * shape: host pointer.  shared_gate/up [n_shared,F_shared,H] and shared_down
+ * [n_shared,H,F_shared] bf16 (NULL when n_shared = 0) are added with weight 1
+ * for every token.  All step outputs are produced: topk_idx, topk_w [T,k];
+ * hist [E]; slot_idx [T,k]; miss_list [T*k]; miss_count [1]; out [T,H]. */
+int moe_verify_layer(const moe_shape_t *shape, const void *hidden, const float *router_w,
+                     const float *router_bias, const int32_t *slot_table, const void *w_gate,
+                     const void *w_up, const void *w_down, const void *shared_gate, const void *shared_up,
+                     const void *shared_down, int32_t *topk_idx, float *topk_w, int32_t *hist,
+                     int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, void *out, int out_bf16,
+                     int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_SPAC_H */

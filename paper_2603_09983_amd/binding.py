@@ -1,0 +1,172 @@
+"""Thin Python binding of libmoe_spac.so: argument marshalling only.
+
+Every function has the name and argument meaning of its C entry point in
+include/moe_spac.h.  Tensors are torch CUDA(HIP) tensors used as typed device
+pointers; the stream is torch's current stream unless one is given.  There is
+no fallback: if the library is not built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_spac.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+        "(hipcc, gfx950). There is no CPU or PyTorch fallback for the MoE layer.")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4, -5
+
+
+class MoeShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "E", "k", "F", "C", "n_shared", "F_shared")]
+
+
+_vp, _sz, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+_lib.moe_status_string.restype = ctypes.c_char_p
+_lib.moe_status_string.argtypes = [_i]
+_lib.moe_workspace_bytes.argtypes = [ctypes.POINTER(MoeShape), ctypes.POINTER(_sz)]
+_lib.moe_workspace_init.argtypes = [_vp, _sz, _vp]
+_lib.moe_route_topk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moe_expert_histogram.argtypes = [_vp, _i, _i, _i, _vp, _vp]
+_lib.moe_slot_resolve.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moe_grouped_ffn.argtypes = [_vp] * 6 + [_i] * 5 + [_vp, _i, _i, _vp, _sz, _vp]
+_lib.moe_verify_layer.argtypes = [ctypes.POINTER(MoeShape)] + [_vp] * 17 + [_i, _i, _vp, _sz, _vp]
+for _f in ("moe_workspace_bytes", "moe_workspace_init", "moe_route_topk", "moe_expert_histogram",
+           "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer"):
+    getattr(_lib, _f).restype = _i
+
+EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
+           "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
+
+
+class MoeError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: status {code}: {moe_status_string(code)}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("device-resident contiguous tensors only")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(rc: int, where: str, check: bool) -> int:
+    if check and rc != OK:
+        raise MoeError(rc, where)
+    return rc
+
+
+def moe_status_string(status: int) -> str:
+    return _lib.moe_status_string(status).decode()
+
+
+def make_shape(T, H, E, k, F, C, n_shared=0, F_shared=0) -> MoeShape:
+    return MoeShape(T, H, E, k, F, C, n_shared, F_shared)
+
+
+def moe_workspace_bytes(shape: MoeShape) -> int:
+    out = _sz(0)
+    rc = _lib.moe_workspace_bytes(ctypes.byref(shape), ctypes.byref(out))
+    _check(rc, "moe_workspace_bytes", True)
+    return int(out.value)
+
+
+def moe_workspace_init(workspace: torch.Tensor, stream=None, check=True) -> int:
+    return _check(_lib.moe_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                          _stream(stream)), "moe_workspace_init", check)
+
+
+def new_workspace(shape: MoeShape, device="cuda") -> torch.Tensor:
+    """Device buffer of moe_workspace_bytes(shape) bytes with a cleared control block."""
+    ws = torch.empty(moe_workspace_bytes(shape), dtype=torch.uint8, device=device)
+    moe_workspace_init(ws)
+    return ws
+
+
+def moe_route_topk(hidden, router_w, router_bias, T, H, E, k, topk_idx, topk_w, logits_opt, workspace,
+                   stream=None, check=True) -> int:
+    rc = _lib.moe_route_topk(_ptr(hidden), _ptr(router_w), _ptr(router_bias), T, H, E, k, _ptr(topk_idx),
+                             _ptr(topk_w), _ptr(logits_opt), _ptr(workspace),
+                             0 if workspace is None else workspace.numel(), _stream(stream))
+    return _check(rc, "moe_route_topk", check)
+
+
+def moe_expert_histogram(topk_idx, T, k, E, hist, stream=None, check=True) -> int:
+    return _check(_lib.moe_expert_histogram(_ptr(topk_idx), T, k, E, _ptr(hist), _stream(stream)),
+                  "moe_expert_histogram", check)
+
+
+def moe_slot_resolve(topk_idx, slot_table, T, k, E, C, slot_idx, miss_list, miss_count, workspace,
+                     stream=None, check=True) -> int:
+    rc = _lib.moe_slot_resolve(_ptr(topk_idx), _ptr(slot_table), T, k, E, C, _ptr(slot_idx), _ptr(miss_list),
+                               _ptr(miss_count), _ptr(workspace),
+                               0 if workspace is None else workspace.numel(), _stream(stream))
+    return _check(rc, "moe_slot_resolve", check)
+
+
+def moe_grouped_ffn(hidden, topk_w, slot_idx, w_gate, w_up, w_down, T, H, F, k, C, out, out_bf16, accumulate,
+                    workspace, stream=None, check=True) -> int:
+    rc = _lib.moe_grouped_ffn(_ptr(hidden), _ptr(topk_w), _ptr(slot_idx), _ptr(w_gate), _ptr(w_up),
+                              _ptr(w_down), T, H, F, k, C, _ptr(out), int(out_bf16), int(accumulate),
+                              _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream))
+    return _check(rc, "moe_grouped_ffn", check)
+
+
+def moe_verify_layer(shape: MoeShape, hidden, router_w, router_bias, slot_table, w_gate, w_up, w_down,
+                     shared_gate, shared_up, shared_down, topk_idx, topk_w, hist, slot_idx, miss_list,
+                     miss_count, out, out_bf16, accumulate, workspace, stream=None, check=True) -> int:
+    rc = _lib.moe_verify_layer(ctypes.byref(shape), _ptr(hidden), _ptr(router_w), _ptr(router_bias),
+                               _ptr(slot_table), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(shared_gate),
+                               _ptr(shared_up), _ptr(shared_down), _ptr(topk_idx), _ptr(topk_w), _ptr(hist),
+                               _ptr(slot_idx), _ptr(miss_list), _ptr(miss_count), _ptr(out), int(out_bf16),
+                               int(accumulate), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                               _stream(stream))
+    return _check(rc, "moe_verify_layer", check)
+
+
+# ---------------------------------------------------------------------------
+# Convenience holder: device buffers for one layer (allocation and marshalling
+# only; every step of the layer runs in the library's kernels).
+# ---------------------------------------------------------------------------
+@dataclass
+class LayerBuffers:
+    shape: MoeShape
+    topk_idx: torch.Tensor
+    topk_w: torch.Tensor
+    hist: torch.Tensor
+    slot_idx: torch.Tensor
+    miss_list: torch.Tensor
+    miss_count: torch.Tensor
+    out: torch.Tensor
+    workspace: torch.Tensor
+
+    @staticmethod
+    def allocate(shape: MoeShape, out_bf16: bool = False, device="cuda") -> "LayerBuffers":
+        T, k, E, H = shape.T, shape.k, shape.E, shape.H
+        i32 = dict(dtype=torch.int32, device=device)
+        return LayerBuffers(
+            shape,
+            torch.empty((T, k), **i32), torch.empty((T, k), dtype=torch.float32, device=device),
+            torch.empty(E, **i32), torch.empty((T, k), **i32), torch.empty(T * k, **i32),
+            torch.empty(1, **i32),
+            torch.empty((T, H), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=device),
+            new_workspace(shape, device))

@@ -1,0 +1,207 @@
+// C-ABI of libmoe_spac.so: argument checks and launch sequencing only.
+#include "../../include/moe_spac.h"
+#include "moe_internal.h"
+
+using namespace moe;
+
+namespace {
+
+thread_local char g_launch_msg[160] = "HIP launch error";
+
+int launch_failed(hipError_t e)
+{
+    snprintf(g_launch_msg, sizeof g_launch_msg, "HIP launch error: %s", hipGetErrorString(e));
+    return MOE_ERR_LAUNCH;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_route_shape(int T, int H, int E, int k)
+{
+    if (T < 1 || H < 1 || E < 1 || k < 1 || k > E || E > kMaxE || k > kMaxK) return MOE_ERR_SHAPE;
+    if ((size_t)T * k > (size_t)1 << 30) return MOE_ERR_SHAPE;
+    if (H % 8 != 0) return MOE_ERR_ALIGN;
+    return MOE_OK;
+}
+
+int check_ffn_shape(int T, int H, int F, int k, int C)
+{
+    if (T < 1 || H < 1 || F < 1 || k < 1 || C < 0 || C > kMaxC || T > 65535) return MOE_ERR_SHAPE;
+    if (H % 32 != 0 || F % 32 != 0) return MOE_ERR_ALIGN;
+    if (ffn_token_tiles(T, H) == 0) return MOE_ERR_SHAPE;
+    return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" const char *moe_status_string(int status)
+{
+    switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_NULL: return "a required pointer is NULL";
+    case MOE_ERR_SHAPE: return "a size is outside the supported range";
+    case MOE_ERR_ALIGN: return "H or F is not a multiple of 32 (8 for routing), or a pointer is not 16-byte aligned";
+    case MOE_ERR_WORKSPACE: return "workspace is smaller than moe_workspace_bytes() asks for";
+    case MOE_ERR_LAUNCH: return g_launch_msg;
+    default: return "unknown status";
+    }
+}
+
+extern "C" int moe_workspace_bytes(const moe_shape_t *sh, size_t *bytes_out)
+{
+    if (!sh || !bytes_out) return MOE_ERR_NULL;
+    if (sh->T < 1 || sh->H < 1 || sh->E < 1 || sh->k < 1 || sh->k > sh->E || sh->F < 1 || sh->C < 0 ||
+        sh->n_shared < 0 || (sh->n_shared > 0 && sh->F_shared < 1))
+        return MOE_ERR_SHAPE;
+    *bytes_out = ws_layout(sh->T, sh->E, sh->k, sh->C, sh->H, sh->F, sh->n_shared, sh->F_shared).total;
+    return MOE_OK;
+}
+
+extern "C" int moe_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return MOE_ERR_NULL;
+    if (workspace_bytes < (size_t)kCtrlBytes) return MOE_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return MOE_ERR_ALIGN;
+    hipError_t e = launch_clear_ctrl(workspace, (hipStream_t)stream);
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
+}
+
+extern "C" int moe_route_topk(const void *hidden, const float *router_w, const float *router_bias, int T,
+                              int H, int E, int k, int32_t *topk_idx, float *topk_w, float *logits_opt,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!hidden || !router_w || !topk_idx || !topk_w || !workspace) return MOE_ERR_NULL;
+    int rc = check_route_shape(T, H, E, k);
+    if (rc) return rc;
+    if (!aligned16(hidden) || !aligned16(router_w) || !aligned16(workspace)) return MOE_ERR_ALIGN;
+    WsLayout w = ws_layout(T, E, k, 0, 0, 0, 0, 0);
+    if (workspace_bytes < w.perm) return MOE_ERR_WORKSPACE;   // control block + logits
+    char *ws = (char *)workspace;
+    RouteArgs a = {};
+    a.hidden = hidden; a.router_w = router_w; a.router_bias = router_bias;
+    a.T = T; a.H = H; a.E = E; a.k = k;
+    a.logits_ws = (float *)(ws + w.logits);
+    a.ticket = (unsigned *)(ws + w.ctrl);
+    a.topk_idx = topk_idx; a.topk_w = topk_w; a.logits_opt = logits_opt;
+    hipError_t e = launch_route(a, (hipStream_t)stream);
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
+}
+
+extern "C" int moe_expert_histogram(const int32_t *topk_idx, int T, int k, int E, int32_t *hist, void *stream)
+{
+    if (!topk_idx || !hist) return MOE_ERR_NULL;
+    if (T < 1 || k < 1 || E < 1 || E > 8192 || (size_t)T * k > (size_t)1 << 30) return MOE_ERR_SHAPE;
+    hipError_t e = launch_histogram(topk_idx, T * k, E, hist, (hipStream_t)stream);
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
+}
+
+extern "C" int moe_slot_resolve(const int32_t *topk_idx, const int32_t *slot_table, int T, int k, int E, int C,
+                                int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    if (!topk_idx || !slot_table || !slot_idx || !miss_list || !miss_count || !workspace) return MOE_ERR_NULL;
+    if (T < 1 || k < 1 || E < 1 || C < 0 || C > kMaxC || (size_t)T * k > (size_t)1 << 30) return MOE_ERR_SHAPE;
+    if (!aligned16(workspace)) return MOE_ERR_ALIGN;
+    WsLayout w = ws_layout(T, E, k, C, 0, 0, 0, 0);
+    if (workspace_bytes < w.part) return MOE_ERR_WORKSPACE;
+    char *ws = (char *)workspace;
+    hipError_t e = launch_resolve(topk_idx, slot_table, T * k, E, C, slot_idx, miss_list, miss_count,
+                                  (int32_t *)(ws + w.slot_count), (int32_t *)(ws + w.slot_offset),
+                                  (int32_t *)(ws + w.perm), (int32_t *)(ws + w.pos), (hipStream_t)stream);
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
+}
+
+extern "C" int moe_grouped_ffn(const void *hidden, const float *topk_w, const int32_t *slot_idx,
+                               const void *w_gate, const void *w_up, const void *w_down, int T, int H, int F,
+                               int k, int C, void *out, int out_bf16, int accumulate, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    if (!hidden || !topk_w || !slot_idx || !out || !workspace) return MOE_ERR_NULL;
+    if (C > 0 && (!w_gate || !w_up || !w_down)) return MOE_ERR_NULL;
+    int rc = check_ffn_shape(T, H, F, k, C);
+    if (rc) return rc;
+    if (!aligned16(hidden) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) ||
+        !aligned16(out) || !aligned16(workspace))
+        return MOE_ERR_ALIGN;
+    // the single-step call has no routing scratch: lay the workspace out with E = 0
+    WsLayout w = ws_layout(T, 0, k, C, H, F, 0, 0);
+    if (workspace_bytes < w.total) return MOE_ERR_WORKSPACE;
+    char *ws = (char *)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *slot_count = (int32_t *)(ws + w.slot_count), *slot_offset = (int32_t *)(ws + w.slot_offset);
+    int32_t *perm = (int32_t *)(ws + w.perm), *pos = (int32_t *)(ws + w.pos);
+    hipError_t e = launch_lists_from_slots(slot_idx, T * k, C, slot_count, slot_offset, perm, pos, s);
+    if (e != hipSuccess) return launch_failed(e);
+    FfnArgs f = {};
+    f.hidden = hidden; f.w_gate = w_gate; f.w_up = w_up; f.w_down = w_down;
+    f.slot_count = slot_count; f.slot_offset = slot_offset; f.perm = perm;
+    f.part = (float *)(ws + w.part); f.part_sh = nullptr;
+    f.T = T; f.H = H; f.F = F; f.k = k; f.C = C; f.n_shared = 0; f.F_shared = 0;
+    e = launch_ffn(f, s);
+    if (e != hipSuccess) return launch_failed(e);
+    CombineArgs c = {};
+    c.topk_w = topk_w; c.pos = pos; c.part = f.part; c.part_sh = nullptr; c.out = out;
+    c.T = T; c.H = H; c.F = F; c.k = k; c.n_shared = 0; c.F_shared = 0;
+    c.out_bf16 = out_bf16; c.accumulate = accumulate;
+    e = launch_combine(c, s);
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
+}
+
+extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const float *router_w,
+                                const float *router_bias, const int32_t *slot_table, const void *w_gate,
+                                const void *w_up, const void *w_down, const void *shared_gate,
+                                const void *shared_up, const void *shared_down, int32_t *topk_idx,
+                                float *topk_w, int32_t *hist, int32_t *slot_idx, int32_t *miss_list,
+                                int32_t *miss_count, void *out, int out_bf16, int accumulate, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    if (!sh || !hidden || !router_w || !slot_table || !topk_idx || !topk_w || !hist || !slot_idx ||
+        !miss_list || !miss_count || !out || !workspace)
+        return MOE_ERR_NULL;
+    if (sh->C > 0 && (!w_gate || !w_up || !w_down)) return MOE_ERR_NULL;
+    if (sh->n_shared < 0 || (sh->n_shared > 0 && sh->F_shared < 1)) return MOE_ERR_SHAPE;
+    if (sh->n_shared > 0 && (!shared_gate || !shared_up || !shared_down)) return MOE_ERR_NULL;
+    int rc = check_route_shape(sh->T, sh->H, sh->E, sh->k);
+    if (rc) return rc;
+    rc = check_ffn_shape(sh->T, sh->H, sh->F, sh->k, sh->C);
+    if (rc) return rc;
+    if (sh->n_shared > 0 && sh->F_shared % 32 != 0) return MOE_ERR_ALIGN;
+    if (!aligned16(hidden) || !aligned16(router_w) || !aligned16(w_gate) || !aligned16(w_up) ||
+        !aligned16(w_down) || !aligned16(shared_gate) || !aligned16(shared_up) || !aligned16(shared_down) ||
+        !aligned16(out) || !aligned16(workspace))
+        return MOE_ERR_ALIGN;
+    WsLayout w = ws_layout(sh->T, sh->E, sh->k, sh->C, sh->H, sh->F, sh->n_shared, sh->F_shared);
+    if (workspace_bytes < w.total) return MOE_ERR_WORKSPACE;
+    char *ws = (char *)workspace;
+    hipStream_t s = (hipStream_t)stream;
+
+    RouteArgs r = {};
+    r.hidden = hidden; r.router_w = router_w; r.router_bias = router_bias;
+    r.T = sh->T; r.H = sh->H; r.E = sh->E; r.k = sh->k;
+    r.logits_ws = (float *)(ws + w.logits);
+    r.ticket = (unsigned *)(ws + w.ctrl);
+    r.topk_idx = topk_idx; r.topk_w = topk_w; r.logits_opt = nullptr; r.hist = hist;
+    r.slot_table = slot_table; r.C = sh->C;
+    r.slot_idx = slot_idx; r.miss_list = miss_list; r.miss_count = miss_count;
+    r.slot_count = (int32_t *)(ws + w.slot_count); r.slot_offset = (int32_t *)(ws + w.slot_offset);
+    r.perm = (int32_t *)(ws + w.perm); r.pos = (int32_t *)(ws + w.pos);
+    hipError_t e = launch_route(r, s);
+    if (e != hipSuccess) return launch_failed(e);
+
+    FfnArgs f = {};
+    f.hidden = hidden; f.w_gate = w_gate; f.w_up = w_up; f.w_down = w_down;
+    f.sh_gate = shared_gate; f.sh_up = shared_up; f.sh_down = shared_down;
+    f.slot_count = r.slot_count; f.slot_offset = r.slot_offset; f.perm = r.perm;
+    f.part = (float *)(ws + w.part); f.part_sh = (float *)(ws + w.part_sh);
+    f.T = sh->T; f.H = sh->H; f.F = sh->F; f.k = sh->k; f.C = sh->C;
+    f.n_shared = sh->n_shared; f.F_shared = sh->n_shared ? sh->F_shared : 0;
+    e = launch_ffn(f, s);
+    if (e != hipSuccess) return launch_failed(e);
+
+    CombineArgs c = {};
+    c.topk_w = topk_w; c.pos = r.pos; c.part = f.part; c.part_sh = f.part_sh; c.out = out;
+    c.T = sh->T; c.H = sh->H; c.F = sh->F; c.k = sh->k; c.n_shared = f.n_shared; c.F_shared = f.F_shared;
+    c.out_bf16 = out_bf16; c.accumulate = accumulate;
+    e = launch_combine(c, s);
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
+}

@@ -1,0 +1,100 @@
+// Internal declarations shared by the translation units of libmoe_spac.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace moe {
+
+constexpr int kWave = 64;
+constexpr int kMaxE = 512;        // logits of one token live in one wavefront: E <= 64 * kMaxEPL
+constexpr int kMaxEPL = kMaxE / kWave;
+constexpr int kMaxK = 64;
+constexpr int kMaxC = 1024;
+constexpr int kSliceF = 128;      // FFN rows (gate/up outputs) owned by one workgroup
+constexpr int kFfnThreads = 512;  // 8 wavefronts, 16 FFN rows each
+constexpr int kLdsBytes = 160 * 1024;
+constexpr int kCtrlBytes = 256;
+
+static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+// Byte offsets of the scratch arrays inside the caller's workspace.
+struct WsLayout {
+    size_t ctrl, logits, perm, pos, slot_count, slot_offset, part, part_sh, total;
+};
+
+static inline int n_slices(int F) { return (F + kSliceF - 1) / kSliceF; }
+
+static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n_shared, int F_shared)
+{
+    WsLayout w;
+    size_t A = (size_t)T * k;
+    size_t o = 0;
+    w.ctrl = o;        o += kCtrlBytes;
+    w.logits = o;      o += align256((size_t)T * E * 4);
+    w.perm = o;        o += align256(A * 4);
+    w.pos = o;         o += align256(A * 4);
+    w.slot_count = o;  o += align256((size_t)(C > 0 ? C : 1) * 4);
+    w.slot_offset = o; o += align256((size_t)(C + 1) * 4);
+    w.part = o;        o += align256((size_t)n_slices(F) * A * H * 4);
+    w.part_sh = o;     o += align256((size_t)n_shared * n_slices(F_shared) * T * H * 4);
+    w.total = o;
+    return w;
+}
+
+// What the routing kernel should do after the logits are complete.
+struct RouteArgs {
+    const void *hidden;        // [T,H] bf16
+    const float *router_w;     // [E,H]
+    const float *router_bias;  // [E] or null
+    int T, H, E, k;
+    float *logits_ws;          // [T,E] scratch
+    unsigned *ticket;          // control word, zero on entry, zero on exit
+    int32_t *topk_idx;         // [T,k]
+    float *topk_w;             // [T,k]
+    float *logits_opt;         // [T,E] or null
+    int32_t *hist;             // [E] or null (skip)
+    // slot resolve (skipped when slot_table is null)
+    const int32_t *slot_table; // [E]
+    int C;
+    int32_t *slot_idx;         // [T,k]
+    int32_t *miss_list;        // [T*k]
+    int32_t *miss_count;       // [1]
+    int32_t *slot_count;       // [C]
+    int32_t *slot_offset;      // [C+1]
+    int32_t *perm;             // [T*k]
+    int32_t *pos;              // [T*k]
+};
+
+struct FfnArgs {
+    const void *hidden;        // [T,H] bf16
+    const void *w_gate, *w_up, *w_down;        // slot-major pools
+    const void *sh_gate, *sh_up, *sh_down;     // shared experts or null
+    const int32_t *slot_count, *slot_offset, *perm;
+    float *part;               // [n_slices(F)][A][H]
+    float *part_sh;            // [n_shared][n_slices(F_shared)][T][H]
+    int T, H, F, k, C, n_shared, F_shared;
+};
+
+struct CombineArgs {
+    const float *topk_w;       // [T,k]
+    const int32_t *pos;        // [T*k] row of `part` or -1
+    const float *part, *part_sh;
+    void *out;
+    int T, H, F, k, n_shared, F_shared, out_bf16, accumulate;
+};
+
+hipError_t launch_route(const RouteArgs &a, hipStream_t s);
+hipError_t launch_histogram(const int32_t *topk_idx, int A, int E, int32_t *hist, hipStream_t s);
+hipError_t launch_resolve(const int32_t *topk_idx, const int32_t *slot_table, int A, int E, int C,
+                          int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, int32_t *slot_count,
+                          int32_t *slot_offset, int32_t *perm, int32_t *pos, hipStream_t s);
+hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_t *slot_count,
+                                   int32_t *slot_offset, int32_t *perm, int32_t *pos, hipStream_t s);
+hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
+hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
+hipError_t launch_clear_ctrl(void *ctrl, hipStream_t s);
+size_t ffn_lds_bytes(int H, int nt);
+int ffn_token_tiles(int T, int H);   // 0 when H does not fit the LDS
+
+}  // namespace moe

@@ -1,0 +1,219 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU
+oracle on the same seeded inputs.  Integer outputs must be bit-exact, gate
+weights within 1e-5, FFN outputs within 2e-2 x RMS of the oracle output."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_09983_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def layer(seed, **kw):
+    fs = kw.pop("Fs", 0)
+    return synth.make_layer(synth.small_recipe(f"t{seed}", seed, F_shared=fs, **kw))
+
+
+SMALL_CASES = {
+    # several FFN slices, a ragged last slice (160 = 128 + 32), half cache, one shared expert
+    "ragged_F": dict(T=9, H=256, E=16, k=3, F=160, C=7, n_shared=1, Fs=96),
+    # H not a multiple of the 128-wide pipeline step (ragged contraction tail)
+    "ragged_H": dict(T=5, H=160, E=8, k=2, F=256, C=5),
+    # a single token, a single expert per token
+    "T1_k1": dict(T=1, H=128, E=4, k=1, F=128, C=2),
+    # k = E: every expert selected by every token, all resident
+    "k_eq_E": dict(T=7, H=128, E=6, k=6, F=128, C=6, residency="all"),
+    # two token tiles in one pass (T > 16)
+    "two_tiles": dict(T=24, H=256, E=8, k=2, F=128, C=4, n_shared=1, Fs=128),
+    # more routed tokens per slot than one pass holds (several token groups), shared over T=70
+    "token_groups": dict(T=70, H=128, E=4, k=2, F=128, C=3, n_shared=1, Fs=64),
+    # E = 60 (lanes beyond E idle in the wavefront arg-max), Zipf-biased router
+    "zipf_E60": dict(T=6, H=256, E=60, k=4, F=128, C=20, residency="zipf", zipf_s=1.1, n_shared=1, Fs=256,
+                     hidden="unit"),
+    # more experts than one lane each (E > 64)
+    "E130": dict(T=5, H=128, E=130, k=7, F=64, C=40, hidden="unit"),
+    # nothing resident: output is the shared expert alone, every assignment missed
+    "cache_empty": dict(T=4, H=128, E=8, k=2, F=128, C=0, n_shared=1, Fs=128),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SMALL_CASES))
+def test_verify_layer_small(G, name):
+    li = layer(100 + sorted(SMALL_CASES).index(name), **dict(SMALL_CASES[name]))
+    print(f"[case] {name} shape={li.shape}", flush=True)
+    d = G.upload(li)
+    buf = G.run_layer(d)
+    G.check_against_oracle(li, buf, tag=name)
+
+
+def test_verify_layer_cfg1_tiny(G):
+    li = synth.make_layer(synth.RECIPES["cfg1"])
+    print(f"[case] cfg1 shape={li.shape}", flush=True)
+    buf = G.run_layer(G.upload(li))
+    G.check_against_oracle(li, buf, tag="cfg1")
+    assert int(buf.miss_count.item()) == 0
+
+
+def test_all_miss_without_shared_is_exact_zero(G):
+    li = layer(7, T=5, H=128, E=8, k=2, F=128, C=4)
+    li.slot_table[:] = -1
+    buf = G.run_layer(G.upload(li))
+    assert torch.count_nonzero(buf.out).item() == 0
+    assert int(buf.miss_count.item()) == 10
+    assert buf.miss_list.cpu().tolist() == list(range(10))
+    G.check_against_oracle(li, buf, tag="all_miss")
+
+
+def test_two_runs_are_bit_identical_and_workspace_is_reusable(G):
+    li = layer(8, T=9, H=256, E=16, k=4, F=256, C=8, n_shared=1, Fs=128)
+    d = G.upload(li)
+    buf = G.run_layer(d)
+    first = buf.out.clone()
+    idx = buf.topk_idx.clone()
+    for _ in range(3):
+        buf.out.fill_(float("nan"))
+        G.run_layer(d, buf)
+        assert torch.equal(buf.out, first) and torch.equal(buf.topk_idx, idx)
+
+
+def test_device_part_plus_host_part_is_the_whole(G):
+    """App. D: the device result over resident experts plus the result over the missed ones
+    equals the all-resident layer; here the 'host part' is pre-loaded and accumulate=1 joins it."""
+    li = layer(9, T=6, H=128, E=10, k=3, F=128, C=4)
+    ref_all = None
+    full = li.slot_table.copy()
+    comp = np.full_like(full, -1)
+    comp[full < 0] = np.arange((full < 0).sum())
+    d_a = G.upload(li)
+    buf = G.run_layer(d_a)
+    li_b = layer(9, T=6, H=128, E=10, k=3, F=128, C=6)
+    li_b.slot_table = comp
+    host_part = oracle.layer_from_inputs(li_b).y
+    buf.out.copy_(torch.from_numpy(host_part.astype(np.float32)).cuda())
+    G.run_layer(d_a, buf, accumulate=True)
+    li.slot_table = np.arange(10, dtype=np.int32)
+    ref_all = oracle.layer_from_inputs(li)
+    y = buf.out.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(y - ref_all.y)) <= G.RTOL_RMS * G.rms(ref_all.y)
+
+
+def test_bf16_output(G):
+    li = layer(10, T=5, H=128, E=8, k=2, F=128, C=8, residency="all")
+    buf = G.run_layer(G.upload(li), out_bf16=True)
+    ref = oracle.layer_from_inputs(li)
+    y = buf.out.float().cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(y - ref.y)) <= G.RTOL_RMS * G.rms(ref.y)
+
+
+# ---------------------------------------------------------------------------
+# single-step entry points
+# ---------------------------------------------------------------------------
+def test_route_topk_entry_point(G):
+    from paper_2603_09983_amd import binding as B
+    li = layer(11, T=19, H=256, E=64, k=6, F=32, C=8, residency="zipf", zipf_s=1.1)
+    s = li.shape
+    hid, rw, bias = G.dev_bf16(li.hidden), G.dev(li.router_w), G.dev(li.router_bias)
+    ws = B.new_workspace(B.make_shape(s.T, s.H, s.E, s.k, s.F, s.C))
+    idx = torch.empty((s.T, s.k), dtype=torch.int32, device="cuda")
+    w = torch.empty((s.T, s.k), dtype=torch.float32, device="cuda")
+    logits = torch.empty((s.T, s.E), dtype=torch.float32, device="cuda")
+    for b in (bias, None):
+        B.moe_route_topk(hid, rw, b, s.T, s.H, s.E, s.k, idx, w, logits, ws)
+        torch.cuda.synchronize()
+        ref_logits = oracle.router_logits(li.hidden, li.router_w, None if b is None else li.router_bias)
+        ridx, rg = oracle.topk_gate(ref_logits, s.k)
+        assert np.max(np.abs(logits.cpu().numpy() - ref_logits)) < 1e-5
+        if b is not None:   # the margin was enforced with the bias in place
+            assert np.array_equal(idx.cpu().numpy(), ridx)
+            assert np.max(np.abs(w.cpu().numpy() - rg)) <= G.GATE_ATOL
+
+
+def test_route_topk_ties_go_to_the_lower_expert(G):
+    from paper_2603_09983_amd import binding as B
+    T, H, E, k = 3, 64, 12, 5
+    hid = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")     # all logits equal (0)
+    rw = torch.randn((E, H), dtype=torch.float32, device="cuda")
+    ws = B.new_workspace(B.make_shape(T, H, E, k, 32, 0))
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    B.moe_route_topk(hid, rw, None, T, H, E, k, idx, w, None, ws)
+    torch.cuda.synchronize()
+    assert idx.cpu().tolist() == [list(range(k))] * T
+    assert torch.all(w == 1.0 / k).item()
+
+
+def test_histogram_entry_point_small_and_large(G):
+    from paper_2603_09983_amd import binding as B
+    rng = np.random.default_rng(3)
+    for T, k, E in [(9, 6, 64), (1, 6, 64), (40000, 4, 60)]:    # the last one takes the multi-workgroup path
+        idx = rng.integers(0, E, size=(T, k), dtype=np.int32)
+        hist = torch.full((E,), -7, dtype=torch.int32, device="cuda")
+        B.moe_expert_histogram(G.dev(idx), T, k, E, hist)
+        torch.cuda.synchronize()
+        assert np.array_equal(hist.cpu().numpy(), oracle.expert_histogram(idx, E))
+        assert int(hist.sum().item()) == T * k
+
+
+def test_slot_resolve_entry_point(G):
+    from paper_2603_09983_amd import binding as B
+    rng = np.random.default_rng(4)
+    for T, k, E, C in [(9, 6, 64, 32), (128, 6, 64, 48), (2000, 3, 16, 5), (4, 2, 8, 0)]:
+        idx = np.stack([rng.choice(E, k, replace=False) for _ in range(T)]).astype(np.int32)
+        table = np.full(E, -1, dtype=np.int32)
+        if C:
+            ch = rng.choice(E, min(C, E), replace=False)
+            table[ch] = rng.permutation(C)[: len(ch)]
+        sh = B.make_shape(T, 32, E, k, 32, C)
+        ws = B.new_workspace(sh)
+        slot_idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+        miss = torch.full((T * k,), -5, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+        B.moe_slot_resolve(G.dev(idx), G.dev(table), T, k, E, C, slot_idx, miss, cnt, ws)
+        torch.cuda.synchronize()
+        rs, rm, rn = oracle.slot_resolve(idx, table)
+        assert np.array_equal(slot_idx.cpu().numpy(), rs)
+        assert int(cnt.item()) == rn
+        assert np.array_equal(miss.cpu().numpy()[:rn], rm)
+
+
+def test_grouped_ffn_entry_point(G):
+    from paper_2603_09983_amd import binding as B
+    li = layer(12, T=11, H=256, E=12, k=3, F=256, C=6)
+    s = li.shape
+    ref = oracle.layer_from_inputs(li)
+    pg, pu, pd = li.pools()
+    ws = B.new_workspace(B.make_shape(s.T, s.H, s.E, s.k, s.F, s.C))
+    out = torch.empty((s.T, s.H), dtype=torch.float32, device="cuda")
+    B.moe_grouped_ffn(G.dev_bf16(li.hidden), G.dev(ref.gate.astype(np.float32)), G.dev(ref.slot_idx),
+                      G.dev_bf16(pg), G.dev_bf16(pu), G.dev_bf16(pd), s.T, s.H, s.F, s.k, s.C, out, 0, 0, ws)
+    torch.cuda.synchronize()
+    y = out.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(y - ref.y)) <= G.RTOL_RMS * G.rms(ref.y)
+    # shared experts through the same entry point: slots = shared experts, weight 1, accumulate
+    li2 = layer(13, T=5, H=128, E=4, k=2, F=128, C=4, n_shared=2, Fs=128, residency="all")
+    r2 = oracle.layer_from_inputs(li2)
+    d2 = G.upload(li2)
+    buf = G.run_layer(d2)
+    G.check_against_oracle(li2, buf, r2, tag="shared")
+
+
+def test_runtime_errors_leave_outputs_untouched(G):
+    from paper_2603_09983_amd import binding as B
+    out = torch.zeros((4, 128), dtype=torch.float32, device="cuda")
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    x = torch.zeros((4, 128), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((4, 2), dtype=torch.float32, device="cuda")
+    si = torch.zeros((4, 2), dtype=torch.int32, device="cuda")
+    pool = torch.zeros((2, 128, 128), dtype=torch.bfloat16, device="cuda")
+    rc = B.moe_grouped_ffn(x, w, si, pool, pool, pool, 4, 128, 100, 2, 2, out, 0, 0, ws, check=False)
+    assert rc == B.ERR_ALIGN
+    with pytest.raises(B.MoeError):
+        B.moe_grouped_ffn(x, w, si, pool, pool, pool, 4, 128, 128, 2, 2, out, 0, 0, ws[:64])

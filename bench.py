@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify-step MoE layer on one MI355X.
+
+A step = one pass of the whole hot path (moe_verify_layer: routing, histogram,
+slot resolve, grouped SwiGLU FFN, combine) over one verification batch.  The
+default workload is the small-MoE verify step (T=9, H=2048, 64 experts, top-6,
+2 shared experts, cache capacity 32).  Consecutive steps run DIFFERENT layers
+(independent seeded weights, router and hidden states), rotating over enough
+weight copies that the streamed bytes exceed the 256 MB last-level cache many
+times over, so every step reads its expert weights from HBM.
+
+Prints ONE JSON line: whole-job expert-weight GB/s (value), ms per step, the
+HBM roofline of the dominant kernel measured with HIP events inside this run,
+and the CPU oracle timed on this machine's host cores (a reported baseline only).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=240)
+    p.add_argument("--warmup", type=int, default=48)
+    p.add_argument("--workload", default="cfg2",
+                   help="cfg2 | cfg3 | cfg4_c8 | cfg4_c4 | cfg5_T<n> (24-layer sweep at T=n)")
+    p.add_argument("--copies", type=int, default=0, help="distinct layers to rotate over (0 = auto)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--cpu-seconds", type=float, default=10.0)
+    return p.parse_args()
+
+
+def build_layers(workload: str, copies: int):
+    """List of synth.LayerInputs (resident experts only) for the chosen workload."""
+    import dataclasses
+    from paper_2603_09983_amd import synth
+    layers = []
+    if workload.startswith("cfg5_T"):
+        T = int(workload[len("cfg5_T"):])
+        n = copies or synth.SWEEP_LAYERS
+        for l in range(n):
+            layers.append(synth.make_layer(synth.sweep_recipe(T, l), hidden_seed=synth.sweep_hidden_seed(T),
+                                           experts="resident"))
+        desc = f"cfg5 sweep: T={T} H=2048 E=64 k=6 F=1408 C=48, {n} independent layers back to back"
+    else:
+        base = synth.RECIPES[workload]
+        s = base.shape
+        per_copy = s.C * 6 * s.H * s.F + s.n_shared * 6 * s.H * s.F_shared
+        n = copies or max(2, min(16, int(6e9 // per_copy)))
+        for i in range(n):
+            layers.append(synth.make_layer(dataclasses.replace(base, seed=base.seed + 1000 * i),
+                                           experts="resident"))
+        desc = (f"{workload}: T={s.T} H={s.H} E={s.E} k={s.k} F={s.F} C={s.C} "
+                f"shared={s.n_shared}x{s.F_shared}, rotating over {n} independent layers")
+    return layers, desc
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the verify-step MoE layer is a single-device kernel path; "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2603_09983_amd import binding as B
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import gpu_util as G
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    t_gen = time.time()
+    layers, desc = build_layers(args.workload, args.copies)
+    dev_layers = [G.upload(li) for li in layers]
+    shape = layers[0].shape
+    buf = B.LayerBuffers.allocate(dev_layers[0].shape)
+    print(f"[bench] {desc}; inputs built and uploaded in {time.time() - t_gen:.1f}s", file=sys.stderr, flush=True)
+
+    def step(i):
+        d = dev_layers[i % len(dev_layers)]
+        B.moe_verify_layer(d.shape, d.hidden, d.router_w, d.router_bias, d.slot_table, d.w_gate, d.w_up,
+                           d.w_down, d.sh_gate, d.sh_up, d.sh_down, buf.topk_idx, buf.topk_w, buf.hist,
+                           buf.slot_idx, buf.miss_list, buf.miss_count, buf.out, False, False, buf.workspace)
+
+    # algorithmic expert-weight bytes of each layer, from its actual routing (one untimed pass)
+    per_expert = 6 * shape.H * shape.F
+    shared_bytes = shape.n_shared * 6 * shape.H * shape.F_shared
+    layer_bytes = []
+    for i, li in enumerate(layers):
+        step(i)
+        torch.cuda.synchronize()
+        hist = buf.hist.cpu().numpy()
+        u_res = int(((hist > 0) & (li.slot_table >= 0)).sum())
+        layer_bytes.append(u_res * per_expert + shared_bytes)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # timed region 1: K steps, wall clock between synchronisations -> value
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    bytes_total = sum(layer_bytes[i % len(layers)] for i in range(args.steps))
+    gbs = bytes_total / (t1 - t0) / 1e9
+
+    # timed region 2: the same K steps with HIP events around every kernel (on the launch stream)
+    B.moe_profile_enable(True)
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    B.moe_profile_enable(False)
+    kernels = {}
+    for kind in range(B.KERNEL_KINDS):
+        ms, n = B.moe_profile_read(kind)
+        if n:
+            kernels[B.moe_profile_kernel_name(kind)] = {"launches": n, "avg_us": ms * 1e3 / n}
+    ffn_ms, ffn_n = B.moe_profile_read(B.KERNEL_FFN)
+    ffn_avg_s = ffn_ms * 1e-3 / ffn_n
+    bytes_per_launch = bytes_total / args.steps
+    achieved = bytes_per_launch / ffn_avg_s / 1e9
+    roofline = {"bound": "hbm", "kernel": "ffn_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_kernel_us": round(ffn_avg_s * 1e6, 2),
+                "algorithmic_bytes_per_launch": int(bytes_per_launch), "kernels": kernels}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        li = layers[0]
+        threads = oracle.max_threads()
+        oracle.layer_from_inputs(li)  # warm-up
+        n, t_cpu0 = 0, time.perf_counter()
+        while True:
+            oracle.layer_from_inputs(li)
+            n += 1
+            el = time.perf_counter() - t_cpu0
+            if el >= args.cpu_seconds or n >= 200:
+                break
+        cpu_s = el / n
+        cpu = {"value": round(layer_bytes[0] / cpu_s / 1e9, 3), "unit": "GB/s", "cores": threads,
+               "kind": "oracle", "us_per_layer": round(cpu_s * 1e6, 1),
+               "sample": f"{n} runs of the whole layer 0 of this workload ({el:.1f}s), fp64 scalar C, "
+                         f"OpenMP over output rows"}
+
+    out = {
+        "metric": "verify-step MoE layer: expert-weight HBM GB/s (us per layer = 1000*ms_per_step), 1xMI355X",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "us_per_layer": round(ms_per_step * 1e3, 2),
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic", "config": {"workload": desc, "layers": len(layers),
+                                        "mean_weight_bytes_per_layer": int(np.mean(layer_bytes))},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

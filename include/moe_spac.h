@@ -117,6 +117,19 @@ int moe_verify_layer(const moe_shape_t *shape, const void *hidden, const float *
                      int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, void *out, int out_bf16,
                      int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Measurement aid (host-side state only; not part of the layer's arithmetic).
+ * While enabled, every kernel the library launches is bracketed by a pair of
+ * HIP events recorded on the caller's stream.  kind: MOE_KERNEL_*.
+ * moe_profile_enable(1) creates the event pool (hipEventCreate, no device
+ * memory) and clears the records; moe_profile_enable(0) stops recording.
+ * moe_profile_read sums hipEventElapsedTime over the records of one kind; the
+ * caller must have synchronised the stream.  total_ms, launches: host. */
+enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2, MOE_KERNEL_COMBINE = 3,
+       MOE_KERNEL_KINDS = 4 };
+int moe_profile_enable(int on);
+int moe_profile_read(int kind, double *total_ms, int *launches);
+const char *moe_profile_kernel_name(int kind);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,7 +45,15 @@ for _f in ("moe_workspace_bytes", "moe_workspace_init", "moe_route_topk", "moe_e
            "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer"):
     getattr(_lib, _f).restype = _i
 
-EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
+_lib.moe_profile_enable.argtypes = [_i]
+_lib.moe_profile_enable.restype = _i
+_lib.moe_profile_read.argtypes = [_i, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i)]
+_lib.moe_profile_read.restype = _i
+_lib.moe_profile_kernel_name.argtypes = [_i]
+_lib.moe_profile_kernel_name.restype = ctypes.c_char_p
+KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_KINDS = 0, 1, 2, 3, 4
+
+EXPORTS = ("moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
 
 
@@ -77,6 +85,21 @@ def _check(rc: int, where: str, check: bool) -> int:
 
 def moe_status_string(status: int) -> str:
     return _lib.moe_status_string(status).decode()
+
+
+def moe_profile_enable(on: bool) -> int:
+    return _check(_lib.moe_profile_enable(int(on)), "moe_profile_enable", True)
+
+
+def moe_profile_read(kind: int):
+    """(total_ms, launches) of one kernel kind since moe_profile_enable(True); sync first."""
+    ms, n = ctypes.c_double(0.0), _i(0)
+    _check(_lib.moe_profile_read(kind, ctypes.byref(ms), ctypes.byref(n)), "moe_profile_read", True)
+    return float(ms.value), int(n.value)
+
+
+def moe_profile_kernel_name(kind: int) -> str:
+    return _lib.moe_profile_kernel_name(kind).decode()
 
 
 def make_shape(T, H, E, k, F, C, n_shared=0, F_shared=0) -> MoeShape:

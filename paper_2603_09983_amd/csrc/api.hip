@@ -14,6 +14,15 @@ int launch_failed(hipError_t e)
     return MOE_ERR_LAUNCH;
 }
 
+// ---- measurement aid: event pairs around each launch ----
+constexpr int kProfMax = 8192;
+struct ProfState {
+    bool on = false;
+    hipEvent_t ev[MOE_KERNEL_KINDS][kProfMax][2];
+    int created = 0;   // pairs created per kind
+    int used[MOE_KERNEL_KINDS] = {0, 0, 0, 0};
+} g_prof;
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int check_route_shape(int T, int H, int E, int k)
@@ -33,6 +42,61 @@ int check_ffn_shape(int T, int H, int F, int k, int C)
 }
 
 }  // namespace
+
+void moe::prof_begin(int kind, hipStream_t s)
+{
+    if (g_prof.on && g_prof.used[kind] < g_prof.created) (void)hipEventRecord(g_prof.ev[kind][g_prof.used[kind]][0], s);
+}
+
+void moe::prof_end(int kind, hipStream_t s)
+{
+    if (g_prof.on && g_prof.used[kind] < g_prof.created) {
+        (void)hipEventRecord(g_prof.ev[kind][g_prof.used[kind]][1], s);
+        ++g_prof.used[kind];
+    }
+}
+
+extern "C" int moe_profile_enable(int on)
+{
+    if (on && g_prof.created == 0) {
+        for (int k = 0; k < MOE_KERNEL_KINDS; ++k)
+            for (int i = 0; i < kProfMax; ++i)
+                for (int j = 0; j < 2; ++j)
+                    if (hipEventCreate(&g_prof.ev[k][i][j]) != hipSuccess) return MOE_ERR_LAUNCH;
+        g_prof.created = kProfMax;
+    }
+    if (on)
+        for (int k = 0; k < MOE_KERNEL_KINDS; ++k) g_prof.used[k] = 0;
+    g_prof.on = on != 0;
+    return MOE_OK;
+}
+
+extern "C" int moe_profile_read(int kind, double *total_ms, int *launches)
+{
+    if (!total_ms || !launches) return MOE_ERR_NULL;
+    if (kind < 0 || kind >= MOE_KERNEL_KINDS) return MOE_ERR_SHAPE;
+    double sum = 0.0;
+    for (int i = 0; i < g_prof.used[kind]; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_prof.ev[kind][i][0], g_prof.ev[kind][i][1]) != hipSuccess)
+            return MOE_ERR_LAUNCH;
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = g_prof.used[kind];
+    return MOE_OK;
+}
+
+extern "C" const char *moe_profile_kernel_name(int kind)
+{
+    switch (kind) {
+    case MOE_KERNEL_ROUTE: return "route_kernel";
+    case MOE_KERNEL_LISTS: return "resolve_kernel";
+    case MOE_KERNEL_FFN: return "ffn_kernel";
+    case MOE_KERNEL_COMBINE: return "combine_kernel";
+    default: return "?";
+    }
+}
 
 extern "C" const char *moe_status_string(int status)
 {

@@ -307,10 +307,12 @@ hipError_t launch_ffn(const FfnArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_done[nt] = true;
     }
+    prof_begin(2, s);
     if (nt == 2)
         hipLaunchKernelGGL(ffn_kernel<2>, dim3(blocks), dim3(kFfnThreads), lds, s, a, nsl, nsl_sh, xs);
     else
         hipLaunchKernelGGL(ffn_kernel<1>, dim3(blocks), dim3(kFfnThreads), lds, s, a, nsl, nsl_sh, xs);
+    prof_end(2, s);
     return hipGetLastError();
 }
 
@@ -318,7 +320,9 @@ hipError_t launch_combine(const CombineArgs &a, hipStream_t s)
 {
     const int nsl = n_slices(a.F), nsl_sh = a.n_shared ? n_slices(a.F_shared) : 0;
     dim3 grid((a.H / 4 + 255) / 256, a.T);
+    prof_begin(3, s);
     hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, s, a, nsl, nsl_sh);
+    prof_end(3, s);
     return hipGetLastError();
 }
 

@@ -94,6 +94,9 @@ hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_
 hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
 hipError_t launch_clear_ctrl(void *ctrl, hipStream_t s);
+// event bracketing for the measurement aid (no-ops unless enabled)
+void prof_begin(int kind, hipStream_t s);
+void prof_end(int kind, hipStream_t s);
 size_t ffn_lds_bytes(int H, int nt);
 int ffn_token_tiles(int T, int H);   // 0 when H does not fit the LDS
 

@@ -298,7 +298,9 @@ size_t post_lds_bytes(int E, int C, int A)
 hipError_t launch_route(const RouteArgs &a, hipStream_t s)
 {
     size_t lds = post_lds_bytes(a.E, a.slot_table ? a.C : 0, a.T * a.k);
+    prof_begin(0, s);
     hipLaunchKernelGGL(route_kernel, dim3(a.E), dim3(kRouteThreads), lds, s, a);
+    prof_end(0, s);
     return hipGetLastError();
 }
 
@@ -331,9 +333,11 @@ hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_
                                    int32_t *slot_offset, int32_t *perm, int32_t *pos, hipStream_t s)
 {
     size_t lds = post_lds_bytes(0, C, A);
+    prof_begin(1, s);
     hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(kRouteThreads), lds, s, (const int32_t *)nullptr,
                        (const int32_t *)nullptr, A, 0, C, const_cast<int32_t *>(slot_idx),
                        (int32_t *)nullptr, (int32_t *)nullptr, slot_count, slot_offset, perm, pos);
+    prof_end(1, s);
     return hipGetLastError();
 }
 

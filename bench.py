@@ -129,14 +129,23 @@ def main():
         ms, n = B.moe_profile_read(kind)
         if n:
             kernels[B.moe_profile_kernel_name(kind)] = {"launches": n, "avg_us": ms * 1e3 / n}
+    # dominant kernel: the gate/up stream (2/3 of the expert-weight bytes); when the batch is large
+    # enough for the fused kernel it carries gate, up and down (all of them)
     ffn_ms, ffn_n = B.moe_profile_read(B.KERNEL_FFN)
+    down_ms, down_n = B.moe_profile_read(B.KERNEL_DOWN)
     ffn_avg_s = ffn_ms * 1e-3 / ffn_n
-    bytes_per_launch = bytes_total / args.steps
+    share = 2.0 / 3.0 if down_n else 1.0
+    bytes_per_launch = share * bytes_total / args.steps
     achieved = bytes_per_launch / ffn_avg_s / 1e9
-    roofline = {"bound": "hbm", "kernel": "ffn_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+    roofline = {"bound": "hbm", "kernel": "stream_kernel<gate/up>" if down_n else "ffn_kernel (gate/up/down fused)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "avg_kernel_us": round(ffn_avg_s * 1e6, 2),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch), "kernels": kernels}
+    if down_n:
+        d_s = down_ms * 1e-3 / down_n
+        roofline["down_kernel"] = {"achieved": round((bytes_total / args.steps / 3.0) / d_s / 1e9, 1),
+                                   "avg_kernel_us": round(d_s * 1e6, 2)}
 
     cpu = None
     if not args.no_cpu_baseline:

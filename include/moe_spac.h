@@ -124,8 +124,8 @@ int moe_verify_layer(const moe_shape_t *shape, const void *hidden, const float *
  * memory) and clears the records; moe_profile_enable(0) stops recording.
  * moe_profile_read sums hipEventElapsedTime over the records of one kind; the
  * caller must have synchronised the stream.  total_ms, launches: host. */
-enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2, MOE_KERNEL_COMBINE = 3,
-       MOE_KERNEL_KINDS = 4 };
+enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2 /* gate/up (and down when fused) */,
+       MOE_KERNEL_COMBINE = 3, MOE_KERNEL_DOWN = 4, MOE_KERNEL_KINDS = 5 };
 int moe_profile_enable(int on);
 int moe_profile_read(int kind, double *total_ms, int *launches);
 const char *moe_profile_kernel_name(int kind);

@@ -51,7 +51,7 @@ _lib.moe_profile_read.argtypes = [_i, ctypes.POINTER(ctypes.c_double), ctypes.PO
 _lib.moe_profile_read.restype = _i
 _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
-KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_KINDS = 0, 1, 2, 3, 4
+KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_KINDS = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")

@@ -20,7 +20,7 @@ struct ProfState {
     bool on = false;
     hipEvent_t ev[MOE_KERNEL_KINDS][kProfMax][2];
     int created = 0;   // pairs created per kind
-    int used[MOE_KERNEL_KINDS] = {0, 0, 0, 0};
+    int used[MOE_KERNEL_KINDS] = {};
 } g_prof;
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -92,8 +92,9 @@ extern "C" const char *moe_profile_kernel_name(int kind)
     switch (kind) {
     case MOE_KERNEL_ROUTE: return "route_kernel";
     case MOE_KERNEL_LISTS: return "resolve_kernel";
-    case MOE_KERNEL_FFN: return "ffn_kernel";
+    case MOE_KERNEL_FFN: return "ffn_gate_up";
     case MOE_KERNEL_COMBINE: return "combine_kernel";
+    case MOE_KERNEL_DOWN: return "ffn_down";
     default: return "?";
     }
 }
@@ -145,7 +146,7 @@ extern "C" int moe_route_topk(const void *hidden, const float *router_w, const f
     a.hidden = hidden; a.router_w = router_w; a.router_bias = router_bias;
     a.T = T; a.H = H; a.E = E; a.k = k;
     a.logits_ws = (float *)(ws + w.logits);
-    a.ticket = (unsigned *)(ws + w.ctrl);
+    a.ticket = (unsigned *)(ws + w.ctrl) + kCtrlTicket;
     a.topk_idx = topk_idx; a.topk_w = topk_w; a.logits_opt = logits_opt;
     hipError_t e = launch_route(a, (hipStream_t)stream);
     return e == hipSuccess ? MOE_OK : launch_failed(e);
@@ -171,9 +172,69 @@ extern "C" int moe_slot_resolve(const int32_t *topk_idx, const int32_t *slot_tab
     char *ws = (char *)workspace;
     hipError_t e = launch_resolve(topk_idx, slot_table, T * k, E, C, slot_idx, miss_list, miss_count,
                                   (int32_t *)(ws + w.slot_count), (int32_t *)(ws + w.slot_offset),
-                                  (int32_t *)(ws + w.perm), (int32_t *)(ws + w.pos), (hipStream_t)stream);
+                                  (int32_t *)(ws + w.perm), (int32_t *)(ws + w.pos),
+                                  (int32_t *)(ws + w.active), (unsigned *)(ws + w.ctrl) + kCtrlNActive,
+                                  (hipStream_t)stream);
     return e == hipSuccess ? MOE_OK : launch_failed(e);
 }
+
+namespace {
+
+// The expert FFN and the combine, given the per-slot lists in the workspace.
+// Batches of up to 16 tokens stream the weights with the LDS-staged kernels
+// (gate/up, down, combine); larger batches take the fused per-slice kernel.
+int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const void *w_up, const void *w_down,
+            const void *sh_gate, const void *sh_up, const void *sh_down, int T, int H, int F, int k, int C,
+            int n_shared, int F_shared, const WsLayout &w, char *ws, void *out, int out_bf16, int accumulate,
+            hipStream_t s)
+{
+    int32_t *slot_count = (int32_t *)(ws + w.slot_count), *slot_offset = (int32_t *)(ws + w.slot_offset);
+    int32_t *perm = (int32_t *)(ws + w.perm), *pos = (int32_t *)(ws + w.pos);
+    CombineArgs c = {};
+    c.topk_w = topk_w; c.pos = pos; c.out = out;
+    c.T = T; c.H = H; c.F = F; c.k = k; c.n_shared = n_shared; c.F_shared = F_shared;
+    c.out_bf16 = out_bf16; c.accumulate = accumulate;
+    hipError_t e;
+    if (T <= kStreamMaxT) {
+        StreamArgs g = {};
+        g.w0 = (const uint16_t *)w_gate; g.w1 = (const uint16_t *)w_up;
+        g.s0 = (const uint16_t *)sh_gate; g.s1 = (const uint16_t *)sh_up;
+        g.bsrc = (const uint16_t *)hidden; g.bsrc_sh = nullptr;
+        g.out = ws + w.act; g.out_sh = ws + w.act_sh;
+        g.slot_count = slot_count; g.slot_offset = slot_offset; g.perm = perm;
+        g.active_slots = (const int32_t *)(ws + w.active);
+        g.n_active = (const unsigned *)(ws + w.ctrl) + kCtrlNActive;
+        g.T = T; g.k = k; g.C = C;
+        g.R = F; g.K = H; g.R_sh = F_shared; g.K_sh = H; g.n_shared = n_shared;
+        g.KP = g.KP_sh = stream_panel_width(H);
+        e = launch_stream(g, true, s);
+        if (e != hipSuccess) return launch_failed(e);
+        StreamArgs d = g;
+        d.w0 = (const uint16_t *)w_down; d.w1 = nullptr;
+        d.s0 = (const uint16_t *)sh_down; d.s1 = nullptr;
+        d.bsrc = (const uint16_t *)(ws + w.act); d.bsrc_sh = (const uint16_t *)(ws + w.act_sh);
+        d.out = ws + w.o; d.out_sh = ws + w.o_sh;
+        d.R = H; d.K = F; d.R_sh = H; d.K_sh = F_shared;
+        d.KP = stream_panel_width(F); d.KP_sh = n_shared ? stream_panel_width(F_shared) : 0;
+        e = launch_stream(d, false, s);
+        if (e != hipSuccess) return launch_failed(e);
+        e = launch_combine_rows(c, (const float *)(ws + w.o), (const float *)(ws + w.o_sh), s);
+        return e == hipSuccess ? MOE_OK : launch_failed(e);
+    }
+    FfnArgs f = {};
+    f.hidden = hidden; f.w_gate = w_gate; f.w_up = w_up; f.w_down = w_down;
+    f.sh_gate = sh_gate; f.sh_up = sh_up; f.sh_down = sh_down;
+    f.slot_count = slot_count; f.slot_offset = slot_offset; f.perm = perm;
+    f.part = (float *)(ws + w.part); f.part_sh = (float *)(ws + w.part_sh);
+    f.T = T; f.H = H; f.F = F; f.k = k; f.C = C; f.n_shared = n_shared; f.F_shared = F_shared;
+    e = launch_ffn(f, s);
+    if (e != hipSuccess) return launch_failed(e);
+    c.part = f.part; c.part_sh = f.part_sh;
+    e = launch_combine(c, s);
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
+}
+
+}  // namespace
 
 extern "C" int moe_grouped_ffn(const void *hidden, const float *topk_w, const int32_t *slot_idx,
                                const void *w_gate, const void *w_up, const void *w_down, int T, int H, int F,
@@ -192,23 +253,13 @@ extern "C" int moe_grouped_ffn(const void *hidden, const float *topk_w, const in
     if (workspace_bytes < w.total) return MOE_ERR_WORKSPACE;
     char *ws = (char *)workspace;
     hipStream_t s = (hipStream_t)stream;
-    int32_t *slot_count = (int32_t *)(ws + w.slot_count), *slot_offset = (int32_t *)(ws + w.slot_offset);
-    int32_t *perm = (int32_t *)(ws + w.perm), *pos = (int32_t *)(ws + w.pos);
-    hipError_t e = launch_lists_from_slots(slot_idx, T * k, C, slot_count, slot_offset, perm, pos, s);
+    hipError_t e = launch_lists_from_slots(slot_idx, T * k, C, (int32_t *)(ws + w.slot_count),
+                                           (int32_t *)(ws + w.slot_offset), (int32_t *)(ws + w.perm),
+                                           (int32_t *)(ws + w.pos), (int32_t *)(ws + w.active),
+                                           (unsigned *)(ws + w.ctrl) + kCtrlNActive, s);
     if (e != hipSuccess) return launch_failed(e);
-    FfnArgs f = {};
-    f.hidden = hidden; f.w_gate = w_gate; f.w_up = w_up; f.w_down = w_down;
-    f.slot_count = slot_count; f.slot_offset = slot_offset; f.perm = perm;
-    f.part = (float *)(ws + w.part); f.part_sh = nullptr;
-    f.T = T; f.H = H; f.F = F; f.k = k; f.C = C; f.n_shared = 0; f.F_shared = 0;
-    e = launch_ffn(f, s);
-    if (e != hipSuccess) return launch_failed(e);
-    CombineArgs c = {};
-    c.topk_w = topk_w; c.pos = pos; c.part = f.part; c.part_sh = nullptr; c.out = out;
-    c.T = T; c.H = H; c.F = F; c.k = k; c.n_shared = 0; c.F_shared = 0;
-    c.out_bf16 = out_bf16; c.accumulate = accumulate;
-    e = launch_combine(c, s);
-    return e == hipSuccess ? MOE_OK : launch_failed(e);
+    return run_ffn(hidden, topk_w, w_gate, w_up, w_down, nullptr, nullptr, nullptr, T, H, F, k, C, 0, 0, w, ws,
+                   out, out_bf16, accumulate, s);
 }
 
 extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const float *router_w,
@@ -243,29 +294,16 @@ extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const
     r.hidden = hidden; r.router_w = router_w; r.router_bias = router_bias;
     r.T = sh->T; r.H = sh->H; r.E = sh->E; r.k = sh->k;
     r.logits_ws = (float *)(ws + w.logits);
-    r.ticket = (unsigned *)(ws + w.ctrl);
+    r.ticket = (unsigned *)(ws + w.ctrl) + kCtrlTicket;
     r.topk_idx = topk_idx; r.topk_w = topk_w; r.logits_opt = nullptr; r.hist = hist;
     r.slot_table = slot_table; r.C = sh->C;
     r.slot_idx = slot_idx; r.miss_list = miss_list; r.miss_count = miss_count;
     r.slot_count = (int32_t *)(ws + w.slot_count); r.slot_offset = (int32_t *)(ws + w.slot_offset);
     r.perm = (int32_t *)(ws + w.perm); r.pos = (int32_t *)(ws + w.pos);
+    r.active_slots = (int32_t *)(ws + w.active); r.n_active = (unsigned *)(ws + w.ctrl) + kCtrlNActive;
     hipError_t e = launch_route(r, s);
     if (e != hipSuccess) return launch_failed(e);
-
-    FfnArgs f = {};
-    f.hidden = hidden; f.w_gate = w_gate; f.w_up = w_up; f.w_down = w_down;
-    f.sh_gate = shared_gate; f.sh_up = shared_up; f.sh_down = shared_down;
-    f.slot_count = r.slot_count; f.slot_offset = r.slot_offset; f.perm = r.perm;
-    f.part = (float *)(ws + w.part); f.part_sh = (float *)(ws + w.part_sh);
-    f.T = sh->T; f.H = sh->H; f.F = sh->F; f.k = sh->k; f.C = sh->C;
-    f.n_shared = sh->n_shared; f.F_shared = sh->n_shared ? sh->F_shared : 0;
-    e = launch_ffn(f, s);
-    if (e != hipSuccess) return launch_failed(e);
-
-    CombineArgs c = {};
-    c.topk_w = topk_w; c.pos = r.pos; c.part = f.part; c.part_sh = f.part_sh; c.out = out;
-    c.T = sh->T; c.H = sh->H; c.F = sh->F; c.k = sh->k; c.n_shared = f.n_shared; c.F_shared = f.F_shared;
-    c.out_bf16 = out_bf16; c.accumulate = accumulate;
-    e = launch_combine(c, s);
-    return e == hipSuccess ? MOE_OK : launch_failed(e);
+    return run_ffn(hidden, topk_w, w_gate, w_up, w_down, shared_gate, shared_up, shared_down, sh->T, sh->H,
+                   sh->F, sh->k, sh->C, sh->n_shared, sh->n_shared ? sh->F_shared : 0, w, ws, out, out_bf16,
+                   accumulate, s);
 }

@@ -15,13 +15,18 @@ constexpr int kSliceF = 128;      // FFN rows (gate/up outputs) owned by one wor
 constexpr int kFfnThreads = 512;  // 8 wavefronts, 16 FFN rows each
 constexpr int kLdsBytes = 160 * 1024;
 constexpr int kCtrlBytes = 256;
+constexpr int kStreamMaxT = 16;   // batches up to this size take the streaming kernels
 
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 // Byte offsets of the scratch arrays inside the caller's workspace.
 struct WsLayout {
-    size_t ctrl, logits, perm, pos, slot_count, slot_offset, part, part_sh, total;
+    size_t ctrl, logits, perm, pos, slot_count, slot_offset, active, part, part_sh, act, act_sh, o, o_sh, total;
 };
+
+// control block words
+constexpr int kCtrlTicket = 0;    // arrival counter of the routing kernel
+constexpr int kCtrlNActive = 1;   // number of resident slots that received at least one token
 
 static inline int n_slices(int F) { return (F + kSliceF - 1) / kSliceF; }
 
@@ -36,8 +41,20 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
     w.pos = o;         o += align256(A * 4);
     w.slot_count = o;  o += align256((size_t)(C > 0 ? C : 1) * 4);
     w.slot_offset = o; o += align256((size_t)(C + 1) * 4);
-    w.part = o;        o += align256((size_t)n_slices(F) * A * H * 4);
-    w.part_sh = o;     o += align256((size_t)n_shared * n_slices(F_shared) * T * H * 4);
+    w.active = o;      o += align256((size_t)(C > 0 ? C : 1) * 4);
+    if (T > kStreamMaxT) {
+        // large batches: per-slice partial sums of the fused FFN kernel
+        w.part = o;    o += align256((size_t)n_slices(F) * A * H * 4);
+        w.part_sh = o; o += align256((size_t)n_shared * n_slices(F_shared) * T * H * 4);
+        w.act = w.act_sh = w.o = w.o_sh = o;
+    } else {
+        // up to 16 tokens: activations and per-assignment outputs of the streaming kernels
+        w.part = w.part_sh = o;
+        w.act = o;     o += align256(A * F * 2);
+        w.act_sh = o;  o += align256((size_t)n_shared * T * F_shared * 2);
+        w.o = o;       o += align256(A * H * 4);
+        w.o_sh = o;    o += align256((size_t)n_shared * T * H * 4);
+    }
     w.total = o;
     return w;
 }
@@ -64,6 +81,22 @@ struct RouteArgs {
     int32_t *slot_offset;      // [C+1]
     int32_t *perm;             // [T*k]
     int32_t *pos;              // [T*k]
+    int32_t *active_slots;     // [C] slots with at least one token, ascending
+    unsigned *n_active;        // [1]
+};
+
+// Arguments of the streaming kernels (gate/up: R = F rows, K = H; down: R = H rows, K = F).
+struct StreamArgs {
+    const uint16_t *w0, *w1;   // routed pools: gate, up | down, unused
+    const uint16_t *s0, *s1;   // shared experts: same roles
+    const uint16_t *bsrc;      // gate/up: hidden [T,H]; down: act [A,F]
+    const uint16_t *bsrc_sh;   // down: act_sh [n_shared,T,F_shared]
+    void *out, *out_sh;        // gate/up: act, act_sh (bf16); down: o [A,H], o_sh [n_shared,T,H] (fp32)
+    const int32_t *slot_count, *slot_offset, *perm, *active_slots;
+    const unsigned *n_active;
+    int T, k;
+    int R, K, R_sh, K_sh, n_shared, C;
+    int KP, KP_sh;             // panel widths (columns parked in LDS at a time)
 };
 
 struct FfnArgs {
@@ -88,9 +121,15 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t s);
 hipError_t launch_histogram(const int32_t *topk_idx, int A, int E, int32_t *hist, hipStream_t s);
 hipError_t launch_resolve(const int32_t *topk_idx, const int32_t *slot_table, int A, int E, int C,
                           int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, int32_t *slot_count,
-                          int32_t *slot_offset, int32_t *perm, int32_t *pos, hipStream_t s);
+                          int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
+                          unsigned *n_active, hipStream_t s);
 hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_t *slot_count,
-                                   int32_t *slot_offset, int32_t *perm, int32_t *pos, hipStream_t s);
+                                   int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
+                                   unsigned *n_active, hipStream_t s);
+hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s);
+hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s);
+int stream_panel_width(int K);     // 0 when K has no panel split
+size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup);
 hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
 hipError_t launch_clear_ctrl(void *ctrl, hipStream_t s);

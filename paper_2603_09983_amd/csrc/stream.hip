@@ -1,0 +1,470 @@
+// Weight-streaming kernels of the expert FFN for verification batches of up to
+// 16 tokens (the regime of a single request with gamma <= 15 draft tokens):
+//      act = silu(W_gate x) * (W_up x)        (gate/up kernel)
+//      o   = W_down act                       (down kernel)
+// per (token, resident expert) pair -- Sec. 2.2 last line, experts as in App. D.
+//
+// Both kernels are bound by the bf16 weight bytes, which must come from HBM
+// once per layer call.  Measured on MI355X, only loads in which a wavefront
+// reads 1 KB of consecutive bytes and the eight wavefronts of a workgroup read
+// neighbouring kilobytes reach the HBM ceiling; the MFMA operand layout read
+// straight from row-major weights (16 rows x 64 B per instruction) gets about
+// two thirds of it.  So a workgroup streams a tile of 16 weight rows x up to
+// 2048 columns (contiguous 64 KB for H = 2048) as 1 KB pieces into registers,
+// parks it in LDS, and then every wavefront multiplies ITS share of the
+// contraction range (32-wide column blocks dealt round-robin) for all 16 rows
+// with MFMA 16x16x32 bf16; the eight partial 16x16 results are added through
+// LDS in a fixed order.  Tokens sit on the MFMA N axis (16 columns, zero beyond
+// the routed ones), so the arithmetic is free and nothing is read twice.
+//
+// Work is a flat list of items (expert, pair of 16-row tiles) over the shared experts
+// and the ACTIVE resident slots only; a fixed grid of one 16-wavefront workgroup per CU
+// takes equal contiguous runs of it, so all workgroups are resident at once,
+// share the HBM bandwidth evenly and finish together.
+#include "moe_internal.h"
+
+namespace moe {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((address_space(1))) uint16_t g_u16;
+typedef __attribute__((address_space(1))) float g_f32;
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = 16;
+constexpr int kPieces = 4;     // 1 KB pieces per wavefront per tile (64 KB tile / 16 wavefronts)
+constexpr int kRowPad = 16;    // bytes of padding per LDS tile row
+constexpr int kOutCap = 16;    // items whose results are kept in LDS between two batches of stores
+
+__device__ inline u32x4 ld_stream(const unsigned char *p)
+{
+    return __builtin_nontemporal_load((const u32x4 *)p);
+}
+
+__device__ inline f32x4 mfma(u32x4 a, u32x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                   c, 0, 0, 0);
+}
+
+__device__ inline uint32_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// One item = one expert and one tile of 16 MFMA rows:
+//   gate/up kernel: gate rows f..f+7 stacked on up rows f..f+7 (so one MFMA pass yields both
+//                   factors of 8 activations, and an item is 64 KB for H = 2048);
+//   down kernel:    down rows h..h+15.
+// Small items keep the last round of the static schedule short.
+//
+// NPI = 1 KB pieces each wavefront loads per tile = ceil(pieces of the widest tile / 16).  All NPI
+// loads of a tile are issued unconditionally (a wavefront whose piece lies beyond the tile re-reads
+// the tile's last piece and parks it on that piece's own bytes), and past the end of its run a
+// workgroup keeps "loading" a few cached kilobytes, so the steady state is straight-line code:
+// park tile t, put tile t+2 in flight, multiply.  That is what lets the wait before a park leave
+// the younger tile in flight.  The state of the two walks over the run (the tile to load next,
+// the tile being consumed) lives in plain scalars and is stepped, not recomputed.
+template <bool GATEUP, int NPI>
+__global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes)
+{
+    constexpr int RPI = GATEUP ? 8 : 16;    // output rows per item
+    constexpr int OB = GATEUP ? 2 : 4;      // bytes per output element
+    constexpr int kOutPerItem = RPI * 16;   // results of one item (rows x token columns)
+
+    extern __shared__ __align__(16) unsigned char lds[];
+    unsigned char *tile_s = lds;
+    float *red_s = (float *)(lds + tile_lds_bytes);                   // [wavefront][lane][4]
+    int *ctl_s = (int *)(lds + tile_lds_bytes + kWaves * kWave * 16);
+    int *count_s = ctl_s, *offset_s = ctl_s + a.C, *active_s = ctl_s + 2 * a.C, *perm_s = ctl_s + 3 * a.C;
+    float *out_s = (float *)(perm_s + a.T * a.k);                     // [kOutCap][kOutPerItem] results waiting to be stored
+    int *odesc_s = (int *)(out_s + kOutCap * kOutPerItem);            // [kOutCap][4]: shared?, row of token 0, column bytes, m
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wavefront id, known to be uniform
+    const int n = lane & 15, g = lane >> 4;
+
+    // The shared experts' items need nothing from the routing step, so each workgroup takes its
+    // run of them first: their weights are in flight while the slot lists are still being read.
+    const int G = gridDim.x, b = blockIdx.x;
+    const int tiles = a.R / RPI, tiles_sh = a.n_shared ? a.R_sh / RPI : 0;
+    const int n_sh_items = a.n_shared * tiles_sh;
+    const int sh_per = n_sh_items / G, sh_rem = n_sh_items % G;
+    const int s_cnt = sh_per + (b < sh_rem ? 1 : 0);
+    const int s_start = b * sh_per + (b < sh_rem ? b : sh_rem);
+    int r_start = 0, cnt = s_cnt;   // completed once the routing results are in LDS
+
+    // ---- the walk that loads: tile (item pp, panel ppan) is the next one to put in flight ----
+    const unsigned char *pw0 = nullptr, *pw1 = nullptr;   // tile rows 0..7 and 8..15, panel 0
+    int pK2 = 0, prs = 0, pnpan = 1, ppan = 0;            // row stride, panel row bytes, panels, panel
+    int pp = 0, pe = 0, prt = 0;                          // item of the run, expert within class, row tile
+    bool psh = false, pvalid = false;
+    auto prod_set = [&](bool sh, int e, int rt) {
+        psh = sh; pe = e; prt = rt; ppan = 0;
+        if (sh) {
+            const int K = a.K_sh;
+            const size_t eoff = ((size_t)e * a.R_sh + (size_t)rt * RPI) * K;
+            pw0 = (const unsigned char *)(a.s0 + eoff);
+            pw1 = GATEUP ? (const unsigned char *)(a.s1 + eoff) : pw0 + (size_t)16 * K;
+            pK2 = 2 * K; prs = 2 * a.KP_sh; pnpan = K / a.KP_sh;
+        } else {
+            const int K = a.K;
+            const size_t eoff = ((size_t)active_s[e] * a.R + (size_t)rt * RPI) * K;
+            pw0 = (const unsigned char *)(a.w0 + eoff);
+            pw1 = GATEUP ? (const unsigned char *)(a.w1 + eoff) : pw0 + (size_t)16 * K;
+            pK2 = 2 * K; prs = 2 * a.KP; pnpan = K / a.KP;
+        }
+    };
+    auto prod_advance = [&]() {
+        if (!pvalid) return;
+        if (ppan + 1 < pnpan) { ++ppan; return; }
+        ppan = 0;
+        ++pp;
+        if (pp >= cnt) {            // end of the run: stay on a few cached kilobytes from now on
+            pvalid = false;
+            pK2 = 0;
+            pw1 = pw0;
+        } else if (pp == s_cnt) {   // from the shared experts to the routed ones
+            const int e = r_start / tiles;
+            prod_set(false, e, r_start - e * tiles);
+        } else if (prt + 1 == (psh ? tiles_sh : tiles)) {
+            prod_set(psh, pe + 1, 0);
+        } else {
+            ++prt;
+            pw0 += (size_t)RPI * pK2;
+            pw1 += (size_t)RPI * pK2;
+        }
+    };
+
+    // ---- the walk that consumes: tile (item cp, panel cpan) is the one parked and multiplied ----
+    int c_rs = 0, cK = 0, cnpan = 1, cpan = 0;
+    int cp = 0, ce = 0, crt = 0;
+    int cm = 0, ckey = -1, corow0 = 0, cbrow0 = 0, cocol = 0;
+    bool csh = false;
+    auto cons_set = [&](bool sh, int e, int rt) {
+        csh = sh; ce = e; crt = rt; cpan = 0;
+        cocol = rt * RPI * OB;
+        if (sh) {
+            cK = a.K_sh; c_rs = 2 * a.KP_sh; cnpan = a.K_sh / a.KP_sh;
+            cm = a.T; ckey = e; corow0 = e * a.T;
+            cbrow0 = GATEUP ? 0 : e * a.T;            // hidden[n] | act_sh[e][n]
+        } else {
+            const int c = active_s[e];
+            cK = a.K; c_rs = 2 * a.KP; cnpan = a.K / a.KP;
+            cm = count_s[c]; ckey = a.n_shared + c; corow0 = offset_s[c];
+            cbrow0 = GATEUP ? -1 : corow0;            // hidden[perm/k] | act[row]
+        }
+    };
+    auto cons_advance = [&]() {
+        if (cpan + 1 < cnpan) { ++cpan; return; }
+        cpan = 0;
+        ++cp;
+        if (cp >= cnt) return;
+        if (cp == s_cnt) {
+            const int e = r_start / tiles;
+            cons_set(false, e, r_start - e * tiles);
+        } else if (crt + 1 == (csh ? tiles_sh : tiles)) {
+            cons_set(csh, ce + 1, 0);
+        } else {
+            ++crt;
+            cocol += RPI * OB;
+        }
+    };
+
+    // Piece i of this wavefront covers bytes [(16i+w) KB, +1 KB) of a tile seen as 16 rows of rs
+    // bytes; this lane's 16 bytes sit at (row, col), packed as row<<16 | col.  A tile of rs-byte rows
+    // has rs/64 pieces (as many as it has 32-wide column blocks).
+    // Two tiles are in flight per wavefront (st[0], st[1]); each remembers its own geometry.
+    u32x4 st[2][NPI];
+    int rc[2][NPI];
+    int st_rs[2] = {-1, -1};
+    auto issue = [&](int s) {
+        if (prs != st_rs[s]) {
+            st_rs[s] = prs;
+            const float inv_d = 16.0f / (float)prs;
+            const int np = prs / 64;
+#pragma unroll
+            for (int i = 0; i < NPI; ++i) {
+                int pc = i * kWaves + w;
+                pc = pc < np ? pc : np - 1;
+                int off = (pc << 10) + (lane << 4);
+                int row = (int)(((float)(off >> 4) + 0.5f) * inv_d);
+                rc[s][i] = (row << 16) | (off - row * prs);
+            }
+        }
+        const unsigned poff = (unsigned)ppan * (unsigned)prs;
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) {
+            const int row = rc[s][i] >> 16, col = rc[s][i] & 0xffff;
+            const unsigned char *base = row < 8 ? pw0 : pw1;
+            st[s][i] = ld_stream(base + (poff + (unsigned)((row & 7) * pK2 + col)));
+        }
+    };
+    auto park = [&](int s) {
+        const int rs = st_rs[s];
+        // (a wavefront's re-read of the last piece lands on that piece's own bytes: same data, no test)
+#pragma unroll
+        for (int i = 0; i < NPI; ++i)
+            *(u32x4 *)(tile_s + (rc[s][i] >> 16) * (rs + kRowPad) + (rc[s][i] & 0xffff)) = st[s][i];
+    };
+
+    if (s_cnt > 0) {
+        const int e = s_start / tiles_sh;
+        prod_set(true, e, s_start - e * tiles_sh);
+        cons_set(true, e, s_start - e * tiles_sh);
+        pvalid = true;
+        issue(0);
+    }
+    // one trip to memory for everything the routing step left behind
+    for (int i = tid; i < a.C; i += kThreads) {
+        count_s[i] = a.slot_count[i];
+        offset_s[i] = a.slot_offset[i];
+        active_s[i] = a.active_slots[i];
+    }
+    for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = a.perm[i];
+    const int n_act = (int)(*a.n_active);
+    __syncthreads();
+
+    // equal runs of the whole item list; this workgroup's run = its shared items, then routed ones
+    {
+        const int total = n_sh_items + n_act * tiles;
+        const int per = total / G, rem = total % G;
+        cnt = per + (b < rem ? 1 : 0);
+        r_start = b * per + (b < rem ? b : rem) - s_start;
+    }
+    if (cnt == 0) return;
+    const int ntiles = s_cnt * (a.n_shared ? a.K_sh / a.KP_sh : 0) + (cnt - s_cnt) * (a.K / a.KP);
+    if (s_cnt == 0) {
+        const int e = r_start / tiles;
+        prod_set(false, e, r_start - e * tiles);
+        cons_set(false, e, r_start - e * tiles);
+        pvalid = true;
+        issue(0);
+    }
+    prod_advance();
+    issue(1);
+    prod_advance();
+
+    u32x4 bx[kPieces];
+    int bx_key = -1, bx_panel = -1;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int flushed = 0;   // items of this run whose results have left the LDS output buffer
+
+    // Results wait in LDS and leave in batches: a store in the steady state would make every
+    // later wait on the weight loads a wait for everything (loads and stores share one counter).
+    auto flush = [&](int upto) {
+        for (int p = flushed; p < upto; ++p) {
+            const int slot = p % kOutCap;
+            const int *d = odesc_s + slot * 4;
+            if (tid < kOutPerItem) {
+                const int q = tid;
+                const int tok = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3);
+                if (tok < d[3]) {
+                    const float v = out_s[slot * kOutPerItem + q];
+                    // explicit global stores (a generic-pointer store would count as an LDS access too)
+                    if (d[0]) {
+                        unsigned char *orow = (unsigned char *)a.out_sh + (size_t)(d[1] + tok) * (a.R_sh * OB) + d[2];
+                        if (GATEUP) ((g_u16 *)(uintptr_t)orow)[row] = (uint16_t)f32_to_bf16_rne(v);
+                        else ((g_f32 *)(uintptr_t)orow)[row] = v;
+                    } else {
+                        unsigned char *orow = (unsigned char *)a.out + (size_t)(d[1] + tok) * (a.R * OB) + d[2];
+                        if (GATEUP) ((g_u16 *)(uintptr_t)orow)[row] = (uint16_t)f32_to_bf16_rne(v);
+                        else ((g_f32 *)(uintptr_t)orow)[row] = v;
+                    }
+                }
+            }
+        }
+        flushed = upto;
+        __builtin_amdgcn_s_waitcnt(0);   // every counter to zero: the stores are done before streaming resumes
+    };
+
+    // one tile: refresh the B operand if the expert changed, park the tile, put the tile two steps
+    // ahead in flight, multiply, and on the item's last panel reduce into the output buffer
+    auto step = [&](int s) {
+        const int nkb = c_rs / 64;
+        if (bx_key != ckey || bx_panel != cpan) {
+            // B operand of this wavefront's column blocks: token n on the MFMA N axis
+            const uint16_t *bbase = a.bsrc;
+            if (!GATEUP && csh) bbase = a.bsrc_sh;
+            int boff = -1;
+            if (n < cm) boff = (cbrow0 >= 0 ? cbrow0 + n : perm_s[corow0 + n] / a.k) * cK + cpan * (c_rs / 2);
+#pragma unroll
+            for (int j = 0; j < kPieces; ++j) {
+                int kb = w + kWaves * j;
+                bx[j] = (u32x4){0u, 0u, 0u, 0u};
+                if (kb < nkb && boff >= 0) bx[j] = *(const u32x4 *)(bbase + (unsigned)(boff + kb * 32 + g * 8));
+            }
+            bx_key = ckey;
+            bx_panel = cpan;
+            // rare path (a new expert): drain the loads here so that the steady state never waits
+            // on the B operand behind the weight tiles in flight
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
+        park(s);
+        issue(s);
+        prod_advance();
+        __syncthreads();
+        if (cpan == 0) acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) {
+            int kb = w + kWaves * j;
+            if (kb < nkb) {
+                u32x4 av = *(const u32x4 *)(tile_s + n * (c_rs + kRowPad) + kb * 64 + g * 16);
+                acc = mfma(av, bx[j], acc);
+            }
+        }
+        const bool last_panel = cpan + 1 == cnpan;
+        if (last_panel) *(f32x4 *)(red_s + (w * kWave + lane) * 4) = acc;
+        __syncthreads();   // every wavefront is done with the tile in LDS (and its partial result is posted)
+        if (last_panel) {
+            const int slot = cp % kOutCap;
+            if (tid < kOutPerItem) {
+                // The sixteen partial 16x16 results, added in wavefront order.  Element q = lane*4 + j
+                // of the MFMA result layout is token (q/4)%16, tile row 4*(q/64) + q%4; gate rows are
+                // tile rows 0..7 and the up row of the same activation sits 128 elements further on.
+                const int q = tid;
+                float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+                for (int v = 0; v < kWaves; ++v) {
+                    s0 += red_s[v * kWave * 4 + q];
+                    if (GATEUP) s1 += red_s[v * kWave * 4 + q + 128];
+                }
+                out_s[slot * kOutPerItem + q] = GATEUP ? s0 / (1.f + expf(-s0)) * s1 : s0;
+            }
+            if (tid == 0) {
+                odesc_s[slot * 4 + 0] = csh ? 1 : 0;
+                odesc_s[slot * 4 + 1] = corow0;
+                odesc_s[slot * 4 + 2] = cocol;
+                odesc_s[slot * 4 + 3] = cm;
+            }
+        }
+        const int done = cp + 1;
+        cons_advance();
+        if (last_panel && done - flushed == kOutCap) {
+            __syncthreads();
+            flush(done);
+        }
+    };
+
+    // (first tile peeled off so that the loop is always entered in the same state: the compiler then
+    // counts the loads in flight exactly and each park waits for its own tile only)
+    step(0);
+    int t = 1;
+    for (; t + 1 < ntiles; t += 2) {
+        step(1);
+        step(0);
+    }
+    if (t < ntiles) step(1);
+    __syncthreads();
+    flush(cnt);
+}
+
+// out[t,:] (+)= sum_j w[t,j] * o[pos[t,j],:] + sum_i o_sh[i,t,:], in a fixed order
+__global__ __launch_bounds__(128) void combine_rows_kernel(CombineArgs a, const float *o, const float *o_sh)
+{
+    const int t = blockIdx.y;
+    const int h = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (h >= a.H) return;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (a.accumulate) {
+        if (a.out_bf16) {
+            u32x2 v = *(const u32x2 *)((const uint16_t *)a.out + (size_t)t * a.H + h);
+            acc = (f32x4){__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                          __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u)};
+        } else {
+            acc = *(const f32x4 *)((const float *)a.out + (size_t)t * a.H + h);
+        }
+    }
+#pragma unroll 8
+    for (int j = 0; j < a.k; ++j) {
+        int p = a.pos[(size_t)t * a.k + j];
+        if (p >= 0) acc += a.topk_w[(size_t)t * a.k + j] * *(const f32x4 *)(o + (size_t)p * a.H + h);
+    }
+    for (int i = 0; i < a.n_shared; ++i) acc += *(const f32x4 *)(o_sh + ((size_t)i * a.T + t) * a.H + h);
+    if (a.out_bf16) {
+        u32x2 v = {f32_to_bf16_rne(acc[0]) | (f32_to_bf16_rne(acc[1]) << 16),
+                   f32_to_bf16_rne(acc[2]) | (f32_to_bf16_rne(acc[3]) << 16)};
+        *(u32x2 *)((uint16_t *)a.out + (size_t)t * a.H + h) = v;
+    } else {
+        *(f32x4 *)((float *)a.out + (size_t)t * a.H + h) = acc;
+    }
+}
+
+int g_num_cus = 0;
+
+int num_cus()
+{
+    if (g_num_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            g_num_cus = n;
+        else
+            g_num_cus = 256;
+    }
+    return g_num_cus;
+}
+
+}  // namespace
+
+int stream_panel_width(int K)
+{
+    // equal panels, each a multiple of 32 and at most 2048 columns wide
+    for (int np = (K + 2047) / 2048; np <= K / 32; ++np)
+        if (K % np == 0 && (K / np) % 32 == 0) return K / np;
+    return 0;
+}
+
+size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup)
+{
+    int kp = KP_a > KP_b ? KP_a : KP_b;
+    (void)gateup;
+    return (size_t)16 * (2 * kp + kRowPad) + (size_t)kWaves * kWave * 16;
+}
+
+hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s)
+{
+    const size_t tile = (size_t)16 * (2 * (a.KP > a.KP_sh ? a.KP : a.KP_sh) + kRowPad);
+    const size_t lds = stream_lds_bytes(a.KP, a.KP_sh, gateup) + (size_t)(3 * a.C + a.T * a.k) * 4 +
+                       (size_t)kOutCap * ((gateup ? 128 : 256) + 4) * 4;
+    const int kp_max = a.KP > a.KP_sh ? a.KP : a.KP_sh;
+    const int npi = (kp_max / 32 + kWaves - 1) / kWaves;   // 1..4 pieces per wavefront and tile
+    const void *fns[2][4] = {
+        {(const void *)stream_kernel<false, 1>, (const void *)stream_kernel<false, 2>,
+         (const void *)stream_kernel<false, 3>, (const void *)stream_kernel<false, 4>},
+        {(const void *)stream_kernel<true, 1>, (const void *)stream_kernel<true, 2>,
+         (const void *)stream_kernel<true, 3>, (const void *)stream_kernel<true, 4>}};
+    const void *fn = fns[gateup ? 1 : 0][npi - 1];
+    static bool attr_done[8] = {};
+    const int which = (gateup ? 4 : 0) + npi - 1;
+    if (!attr_done[which]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_done[which] = true;
+    }
+    const int grid = num_cus();
+    int tile_i = (int)tile;
+    StreamArgs args = a;
+    void *params[] = {&args, &tile_i};
+    prof_begin(gateup ? 2 : 4, s);
+    hipError_t le = hipLaunchKernel(fn, dim3(grid), dim3(kThreads), params, lds, s);
+    prof_end(gateup ? 2 : 4, s);
+    if (le != hipSuccess) return le;
+    return hipGetLastError();
+}
+
+hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s)
+{
+    dim3 grid((a.H / 4 + 127) / 128, a.T);
+    prof_begin(3, s);
+    hipLaunchKernelGGL(combine_rows_kernel, grid, dim3(128), 0, s, a, o, o_sh);
+    prof_end(3, s);
+    return hipGetLastError();
+}
+
+}  // namespace moe

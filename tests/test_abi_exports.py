@@ -43,8 +43,11 @@ def test_workspace_bytes_and_status_strings(lib):
     n = ctypes.c_size_t(0)
     sh = Shape(9, 2048, 64, 6, 1408, 32, 2, 1408)
     assert lib.moe_workspace_bytes(ctypes.byref(sh), ctypes.byref(n)) == 0
-    # at least the partial-sum buffers: slices * A * H * 4 + shared
-    assert n.value >= 11 * 54 * 2048 * 4 + 2 * 11 * 9 * 2048 * 4
+    # at least the activations and per-assignment outputs: A*F*2 + A*H*4 (+ the shared experts' rows)
+    assert n.value >= 54 * 1408 * 2 + 54 * 2048 * 4 + 2 * 9 * (1408 * 2 + 2048 * 4)
+    big = Shape(128, 2048, 64, 6, 1408, 48, 0, 0)      # large batch: per-slice partial sums
+    assert lib.moe_workspace_bytes(ctypes.byref(big), ctypes.byref(n)) == 0
+    assert n.value >= 11 * 768 * 2048 * 4
     assert lib.moe_workspace_bytes(None, ctypes.byref(n)) == -1
     bad = Shape(9, 2048, 64, 65, 1408, 32, 0, 0)       # k > E
     assert lib.moe_workspace_bytes(ctypes.byref(bad), ctypes.byref(n)) == -2

@@ -4,41 +4,59 @@
 //   activation-frequency histogram     (Sec. 2.3)
 //   expert id -> cache slot, miss list, per-slot token lists   (App. D)
 //
-// The fused kernel spreads the [T,H]x[H,E] contraction over one workgroup per
-// expert row; the workgroup that finishes last (ticket in the workspace
-// control block) owns every logit and runs the small integer steps out of LDS,
-// so a layer needs one launch for all of them, no grid-wide wait, and only
-// three dependent trips to memory (weights, logits, results).
+// These steps move a few hundred kilobytes; what they cost is the chain of
+// dependent trips to memory and of workgroup barriers, so the kernel is built
+// to keep that chain short.  One workgroup per expert row computes that
+// expert's logit for every token, one wavefront per token (a wavefront owns a
+// whole dot product, so there is no cross-wavefront reduction).  The
+// workgroup that finishes last (ticket in the workspace control block) owns
+// every logit and runs the integer steps out of LDS: one wavefront per token
+// ranks the logits, then the histogram, slot counts, miss list and per-slot
+// lists are produced by independent threads between three barriers.
 #include "moe_internal.h"
 
 namespace moe {
 
 namespace {
 
-constexpr int kRouteThreads = 512;
+constexpr int kRouteThreads = 1024;
 constexpr int kRouteWaves = kRouteThreads / kWave;
-constexpr int kTokBlock = 8;
 constexpr int kLdsCopy = 4096;  // assignments whose ids are mirrored in LDS
 
 __device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
+// LDS and global pointers carry their address space: a generic pointer would turn every access into
+// a flat instruction, and the dependent LDS reads below would each cost a trip through the memory
+// pipeline instead of an LDS access.
+typedef __attribute__((address_space(3))) float lds_f32;
+typedef __attribute__((address_space(3))) int lds_i32;
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const f32x4v lds_f32x4;
+typedef __attribute__((address_space(1))) const volatile float g_vf32;
+typedef __attribute__((address_space(1))) int32_t g_i32;
+typedef __attribute__((address_space(1))) float g_f32;
+
 __device__ inline float load_coherent(const float *p)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // read after the acquire fence of the last workgroup; volatile = a load that is not served from
+    // a stale cache line and that the compiler neither hoists nor merges
+    return *(g_vf32 *)(uintptr_t)p;
 }
 
 // One wavefront ranks the E logits of one token: rank(e) = number of experts
 // that beat e (larger logit, or equal logit and lower id).  The experts of
 // rank 0..k-1 are the Top-k in descending-logit order; their gate is
-// exp(s - s_max) normalised over those k.  Lane l owns experts l, l+64, ...;
-// every value is broadcast once through a scalar register (no LDS traffic).
+// exp(s - s_max) normalised over those k, summed in rank order.  Lane l owns
+// experts l, l+64, ...; the logits are shared through `lg` (E floats of LDS
+// private to the wavefront), `sel` (k floats) collects the selected ones.
 template <int NLOC>
-__device__ void wave_topk_gate_n(const float *row, bool coherent, int E, int k, int32_t *idx_out,
-                                 int32_t *idx_lds, float *w_out)
+__device__ void wave_topk_gate_n(const float *row, bool coherent, int E, int k, int32_t *idx_out_,
+                                 lds_i32 *idx_lds, float *w_out_, lds_f32 *lg, lds_f32 *sel)
 {
+    g_i32 *idx_out = (g_i32 *)(uintptr_t)idx_out_;
+    g_f32 *w_out = (g_f32 *)(uintptr_t)w_out_;
     const int lane = threadIdx.x & (kWave - 1);
-    constexpr int nloc = NLOC;
     float v[NLOC];
     int rank[NLOC];
 #pragma unroll
@@ -46,94 +64,88 @@ __device__ void wave_topk_gate_n(const float *row, bool coherent, int E, int k, 
         int e = lane + kWave * i;
         v[i] = -INFINITY;
         rank[i] = 0;
-        if (i < nloc && e < E) {
+        if (e < E) {
             float x = coherent ? load_coherent(row + e) : row[e];
             v[i] = (x == x) ? x : -INFINITY;   // NaN cannot win a comparison; rank it last
+            lg[e] = v[i];
         }
     }
+    // pad to a multiple of four with values that beat nothing
+    if (lane < 4) lg[E + lane] = -INFINITY;
+    // (LDS operations of one wavefront execute in order: the reads below see the writes above)
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll 1
+    for (int e2 = 0; e2 < E; e2 += 4) {
+        const f32x4v o4 = *(lds_f32x4 *)(lg + e2);   // same address in every lane: a broadcast read
+        const float o[4] = {o4[0], o4[1], o4[2], o4[3]};
 #pragma unroll
-    for (int i2 = 0; i2 < NLOC; ++i2) {
-        if (i2 < nloc) {
-            for (int l = 0; l < kWave; ++l) {
-                int e2 = l + kWave * i2;
-                if (e2 >= E) break;
-                float o = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v[i2]), l));
+        for (int u = 0; u < 4; ++u) {
 #pragma unroll
-                for (int i = 0; i < NLOC; ++i) {
-                    int e = lane + kWave * i;
-                    rank[i] += (o > v[i] || (o == v[i] && e2 < e)) ? 1 : 0;
-                }
+            for (int i = 0; i < NLOC; ++i) {
+                int e = lane + kWave * i;
+                rank[i] += (o[u] > v[i] || (o[u] == v[i] && e2 + u < e)) ? 1 : 0;
             }
         }
     }
-    // s_max = the logit of rank 0
-    float smax_c = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NLOC; ++i) {
         int e = lane + kWave * i;
-        if (i < nloc && e < E && rank[i] == 0) smax_c = v[i];
+        if (e < E && rank[i] < k) sel[rank[i]] = v[i];
     }
-    float smax = smax_c;
-#pragma unroll
-    for (int m = kWave / 2; m >= 1; m >>= 1) smax = fmaxf(smax, __shfl_xor(smax, m, kWave));
-    float p[NLOC];
+    __builtin_amdgcn_wave_barrier();
+    const float smax = sel[0];
     float den = 0.f;
+    for (int j = 0; j < k; ++j) den += __expf(sel[j] - smax);
 #pragma unroll
     for (int i = 0; i < NLOC; ++i) {
         int e = lane + kWave * i;
-        p[i] = 0.f;
-        if (i < nloc && e < E && rank[i] < k) p[i] = expf(v[i] - smax);
-        den += p[i];
-    }
-#pragma unroll
-    for (int m = kWave / 2; m >= 1; m >>= 1) den += __shfl_xor(den, m, kWave);
-#pragma unroll
-    for (int i = 0; i < NLOC; ++i) {
-        int e = lane + kWave * i;
-        if (i < nloc && e < E && rank[i] < k) {
+        if (e < E && rank[i] < k) {
             idx_out[rank[i]] = e;
             if (idx_lds) idx_lds[rank[i]] = e;
-            w_out[rank[i]] = p[i] / den;
+            w_out[rank[i]] = __expf(v[i] - smax) / den;
         }
     }
 }
 
 __device__ void wave_topk_gate(const float *row, bool coherent, int E, int k, int32_t *idx_out,
-                               int32_t *idx_lds, float *w_out)
+                               lds_i32 *idx_lds, float *w_out, lds_f32 *lg, lds_f32 *sel)
 {
-    if (E <= kWave) wave_topk_gate_n<1>(row, coherent, E, k, idx_out, idx_lds, w_out);
-    else if (E <= 2 * kWave) wave_topk_gate_n<2>(row, coherent, E, k, idx_out, idx_lds, w_out);
-    else if (E <= 4 * kWave) wave_topk_gate_n<4>(row, coherent, E, k, idx_out, idx_lds, w_out);
-    else wave_topk_gate_n<kMaxEPL>(row, coherent, E, k, idx_out, idx_lds, w_out);
+    if (E <= kWave) wave_topk_gate_n<1>(row, coherent, E, k, idx_out, idx_lds, w_out, lg, sel);
+    else if (E <= 2 * kWave) wave_topk_gate_n<2>(row, coherent, E, k, idx_out, idx_lds, w_out, lg, sel);
+    else if (E <= 4 * kWave) wave_topk_gate_n<4>(row, coherent, E, k, idx_out, idx_lds, w_out, lg, sel);
+    else wave_topk_gate_n<kMaxEPL>(row, coherent, E, k, idx_out, idx_lds, w_out, lg, sel);
 }
 
 // hist[e] = number of assignments naming expert e (LDS integer atomics).
-__device__ void block_histogram(const int32_t *idx, int A, int E, int32_t *hist, int *hist_s)
+__device__ void block_histogram(const int32_t *idx, int A, int E, int32_t *hist, lds_i32 *hist_s)
 {
     for (int e = threadIdx.x; e < E; e += blockDim.x) hist_s[e] = 0;
     __syncthreads();
     for (int a = threadIdx.x; a < A; a += blockDim.x) {
         int e = idx[a];
-        if ((unsigned)e < (unsigned)E) atomicAdd(&hist_s[e], 1);
+        if ((unsigned)e < (unsigned)E) __hip_atomic_fetch_add(&hist_s[e], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += blockDim.x) hist[e] = hist_s[e];
 }
 
-// Slot lookup, ascending miss list, per-slot assignment lists and the list of
-// active slots.  idx / slot_table may point to LDS copies.
-// slot_table == nullptr: slot_idx is an input (lists only).
-// LDS: cnt_s[C], off_s[C+1], scan_s[16], sidx_s[min(A, kLdsCopy)].
-__device__ void block_resolve(const int32_t *idx, const int32_t *slot_table, int A, int E, int C,
-                              int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count,
-                              int32_t *slot_count, int32_t *slot_offset, int32_t *perm, int32_t *pos,
-                              int32_t *active_slots, unsigned *n_active, int *cnt_s, int *off_s, int *scan_s,
-                              int *sidx_s)
+// Histogram (optional), slot lookup, ascending miss list, per-slot assignment lists and the
+// list of active slots, by one workgroup.  idx / slot_table may point to LDS copies.
+//   hist == nullptr: no histogram.   slot_table == nullptr: slot_idx is an input (lists only).
+// LDS: hist_s[E], cnt_s[C], off_s[C+1], scan_s[32], sidx_s[min(A, kLdsCopy)].
+__device__ void block_post(const int32_t *idx, const int32_t *slot_table, int A, int E, int C, int32_t *hist,
+                           int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, int32_t *slot_count,
+                           int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
+                           unsigned *n_active, lds_i32 *hist_s, lds_i32 *cnt_s, lds_i32 *off_s, lds_i32 *scan_s,
+                           lds_i32 *sidx_s)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
     const int nw = blockDim.x / kWave;
+    if (hist)
+        for (int e = tid; e < E; e += blockDim.x) hist_s[e] = 0;
     for (int c = tid; c < C; c += blockDim.x) cnt_s[c] = 0;
     __syncthreads();
+    // pass over the assignments: histogram, slot of each, slot counts, miss list
     int running = 0;
     for (int base = 0; base < A; base += blockDim.x) {
         int a = base + tid;
@@ -142,90 +154,121 @@ __device__ void block_resolve(const int32_t *idx, const int32_t *slot_table, int
         if (valid) {
             if (slot_table) {
                 int e = idx[a];
-                c = ((unsigned)e < (unsigned)E) ? slot_table[e] : -1;
+                bool e_ok = (unsigned)e < (unsigned)E;
+                if (hist && e_ok) __hip_atomic_fetch_add(&hist_s[e], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                c = e_ok ? slot_table[e] : -1;
             } else {
                 c = slot_idx[a];
             }
             if ((unsigned)c >= (unsigned)C) c = -1;
             if (slot_table) slot_idx[a] = c;
             if (a < kLdsCopy) sidx_s[a] = c;
-            if (c >= 0) atomicAdd(&cnt_s[c], 1);
+            if (c >= 0) __hip_atomic_fetch_add(&cnt_s[c], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         bool miss = valid && c < 0;
         unsigned long long bal = __ballot(miss);
         int before = __popcll(bal & ((1ull << lane) - 1ull));
-        if (lane == 0) scan_s[w] = __popcll(bal);
-        __syncthreads();
-        int wave_base = 0, total = 0;
-        for (int i = 0; i < nw; ++i) {
-            int s = scan_s[i];
-            if (i < w) wave_base += s;
-            total += s;
+        if (A > kWave) {
+            // more than one wavefront holds assignments: offsets across wavefronts through LDS
+            if (lane == 0) scan_s[w] = __popcll(bal);
+            __syncthreads();
+            int wave_base = 0, total = 0;
+            for (int i = 0; i < nw; ++i) {
+                int s = scan_s[i];
+                if (i < w) wave_base += s;
+                total += s;
+            }
+            if (miss && miss_list) miss_list[running + wave_base + before] = a;
+            running += total;
+            __syncthreads();
+        } else {
+            if (miss && miss_list) miss_list[before] = a;
+            if (w == 0 && lane == 0) scan_s[0] = __popcll(bal);
         }
-        if (miss && miss_list) miss_list[running + wave_base + before] = a;
-        running += total;
-        __syncthreads();
-    }
-    if (tid == 0) {
-        if (miss_count) *miss_count = running;
-        int o = 0, na = 0;
-        for (int c = 0; c < C; ++c) {
-            off_s[c] = o;
-            o += cnt_s[c];
-            if (cnt_s[c] > 0) active_slots[na++] = c;
-        }
-        off_s[C] = o;
-        *n_active = (unsigned)na;
     }
     __syncthreads();
+    if (A <= kWave) running = scan_s[0];
+    if (tid == 0 && miss_count) *miss_count = running;
+    if (hist)
+        for (int e = tid; e < E; e += blockDim.x) hist[e] = hist_s[e];
+    // offsets and active list: thread c looks at the slots before it
     for (int c = tid; c <= C; c += blockDim.x) {
-        slot_offset[c] = off_s[c];
-        if (c < C) slot_count[c] = cnt_s[c];
-    }
-    // stable: the list of a slot holds its assignments in ascending flat id
-    for (int c = tid; c < C; c += blockDim.x) {
-        if (cnt_s[c] == 0) continue;
-        int cur = off_s[c];
-        for (int a = 0; a < A; ++a) {
-            int s = (a < kLdsCopy) ? sidx_s[a] : slot_idx[a];
-            if (s == c) { perm[cur] = a; pos[a] = cur; ++cur; }
+        int o = 0, na = 0;
+#pragma unroll 8
+        for (int c2 = 0; c2 < c; ++c2) {
+            int v = cnt_s[c2];
+            o += v;
+            na += v > 0 ? 1 : 0;
+        }
+        off_s[c] = o;
+        slot_offset[c] = o;
+        if (c < C) {
+            int v = cnt_s[c];
+            slot_count[c] = v;
+            if (v > 0) active_slots[na] = c;
+        } else {
+            *n_active = (unsigned)na;
         }
     }
+    __syncthreads();
+    // lists: assignment a goes to position off[slot] + (number of earlier assignments of that slot),
+    // so the list of a slot holds its assignments in ascending flat id
     for (int a = tid; a < A; a += blockDim.x) {
         int s = (a < kLdsCopy) ? sidx_s[a] : slot_idx[a];
-        if ((unsigned)s >= (unsigned)C) pos[a] = -1;
+        if ((unsigned)s >= (unsigned)C) {
+            pos[a] = -1;
+            continue;
+        }
+        int r = 0;
+#pragma unroll 8
+        for (int a2 = 0; a2 < a; ++a2) {
+            int s2 = (a2 < kLdsCopy) ? sidx_s[a2] : slot_idx[a2];
+            if ((unsigned)s2 >= (unsigned)C) s2 = -1;
+            r += s2 == s ? 1 : 0;
+        }
+        int p = off_s[s] + r;
+        perm[p] = a;
+        pos[a] = p;
     }
 }
 
-// dynamic LDS: hist_s[E] tab_s[E] cnt_s[C] off_s[C+1] scan_s[16] sidx_s[cap] idx_s[cap], cap = min(A, kLdsCopy)
+// logits of one token in LDS: E rounded up to a multiple of four, plus four pad entries
+__host__ __device__ inline int lg_stride(int E) { return ((E + 3) & ~3) + 4; }
+
+// dynamic LDS: hist_s[E] tab_s[E] cnt_s[C] off_s[C+1] scan_s[32] sidx_s[cap] idx_s[cap] lg_s[waves*E] sel_s[waves*64]
 struct PostLds {
-    int *hist_s, *tab_s, *cnt_s, *off_s, *scan_s, *sidx_s, *idx_s;
+    lds_i32 *hist_s, *tab_s, *cnt_s, *off_s, *scan_s, *sidx_s, *idx_s;
+    lds_f32 *lg_s, *sel_s;
 };
 
-__device__ inline PostLds carve_lds(int *dyn, int E, int C, int A)
+__device__ inline PostLds carve_lds(int *dyn_, int E, int C, int A)
 {
     const int cap = A < kLdsCopy ? A : kLdsCopy;
+    lds_i32 *dyn = (lds_i32 *)dyn_;
     PostLds p;
     p.hist_s = dyn;
     p.tab_s = p.hist_s + E;
     p.cnt_s = p.tab_s + E;
     p.off_s = p.cnt_s + C;
     p.scan_s = p.off_s + C + 1;
-    p.sidx_s = p.scan_s + 16;
+    p.sidx_s = p.scan_s + 32;
     p.idx_s = p.sidx_s + cap;
+    p.lg_s = (lds_f32 *)(dyn + ((2 * E + 2 * C + 33 + 2 * cap + 3) & ~3));
+    p.sel_s = p.lg_s + kRouteWaves * lg_stride(E);
     return p;
 }
 
-size_t post_lds_bytes(int E, int C, int A)
+size_t post_lds_bytes(int E, int C, int A, bool with_topk)
 {
     const int cap = A < kLdsCopy ? A : kLdsCopy;
-    return (size_t)(2 * E + C + (C + 1) + 16 + 2 * cap) * sizeof(int);
+    size_t n = (size_t)2 * E + C + (C + 1) + 32 + 2 * cap;
+    if (with_topk) n += (size_t)kRouteWaves * lg_stride(E) + kRouteWaves * kMaxK + 4;
+    return n * sizeof(int);
 }
 
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
 {
     extern __shared__ int dyn[];
-    __shared__ float red[kRouteWaves][kTokBlock];
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
     const int e = blockIdx.x;
@@ -239,46 +282,30 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
     if (a.slot_table)
         for (int i = tid; i < E; i += kRouteThreads) L.tab_s[i] = a.slot_table[i];
 
-    // s[t,e] for every token t: the wavefronts split H, lanes stride it 4 at a time
-    for (int t0 = 0; t0 < T; t0 += kTokBlock) {
-        float acc[kTokBlock];
-#pragma unroll
-        for (int u = 0; u < kTokBlock; ++u) acc[u] = 0.f;
-        for (int h = (w * kWave + lane) * 4; h < H; h += kRouteThreads * 4) {
+    // s[t,e]: one wavefront per token owns the whole dot product, lanes stride H four at a time
+    for (int t = w; t < T; t += kRouteWaves) {
+        const uint16_t *xr = x + (size_t)t * H;
+        float acc = 0.f;
+        for (int h = lane * 4; h < H; h += kWave * 4) {
             float4 wv = *(const float4 *)(wrow + h);
-#pragma unroll
-            for (int u = 0; u < kTokBlock; ++u) {
-                int t = t0 + u;
-                if (t < T) {
-                    uint2 xv = *(const uint2 *)(x + (size_t)t * H + h);
-                    acc[u] += wv.x * bf16_lo(xv.x) + wv.y * bf16_hi(xv.x) + wv.z * bf16_lo(xv.y) +
-                              wv.w * bf16_hi(xv.y);
-                }
-            }
+            uint2 xv = *(const uint2 *)(xr + h);
+            acc += wv.x * bf16_lo(xv.x) + wv.y * bf16_hi(xv.x) + wv.z * bf16_lo(xv.y) + wv.w * bf16_hi(xv.y);
         }
 #pragma unroll
-        for (int u = 0; u < kTokBlock; ++u) {
-#pragma unroll
-            for (int m = kWave / 2; m >= 1; m >>= 1) acc[u] += __shfl_xor(acc[u], m, kWave);
-            if (lane == 0) red[w][u] = acc[u];
+        for (int m = kWave / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, kWave);
+        if (lane == 0) {
+            if (a.router_bias) acc += a.router_bias[e];
+            a.logits_ws[(size_t)t * E + e] = acc;
+            if (a.logits_opt) a.logits_opt[(size_t)t * E + e] = acc;
         }
-        __syncthreads();
-        if (tid < kTokBlock && t0 + tid < T) {
-            float s = 0.f;
-#pragma unroll
-            for (int i = 0; i < kRouteWaves; ++i) s += red[i][tid];
-            if (a.router_bias) s += a.router_bias[e];
-            a.logits_ws[(size_t)(t0 + tid) * E + e] = s;
-            if (a.logits_opt) a.logits_opt[(size_t)(t0 + tid) * E + e] = s;
-        }
-        __syncthreads();
     }
 
-    // the last workgroup to arrive sees every logit.  The logits were written by wavefront 0, so
-    // only it publishes them (a release fence per wavefront costs a cache write-back each)
-    if (w == 0) __threadfence();
+    // The last workgroup to arrive sees every logit.  One thread publishes for the workgroup: the
+    // barrier orders the wavefronts' writes before its release fence (a fence per wavefront would
+    // cost a cache write-back each).
     __syncthreads();
     if (tid == 0) {
+        __threadfence();
         unsigned old = atomicAdd(a.ticket, 1u);
         is_last = (old == gridDim.x - 1);
     }
@@ -289,15 +316,17 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
     const bool idx_in_lds = A <= kLdsCopy;
     for (int t = w; t < T; t += kRouteWaves)
         wave_topk_gate(a.logits_ws + (size_t)t * E, true, E, a.k, a.topk_idx + (size_t)t * a.k,
-                       idx_in_lds ? L.idx_s + t * a.k : nullptr, a.topk_w + (size_t)t * a.k);
+                       idx_in_lds ? L.idx_s + t * a.k : nullptr, a.topk_w + (size_t)t * a.k, L.lg_s + w * lg_stride(E),
+                       L.sel_s + w * kMaxK);
     __syncthreads();
 
-    const int32_t *idx = idx_in_lds ? L.idx_s : a.topk_idx;
-    if (a.hist) block_histogram(idx, A, E, a.hist, L.hist_s);
+    const int32_t *idx = idx_in_lds ? (const int32_t *)L.idx_s : a.topk_idx;
     if (a.slot_table)
-        block_resolve(idx, L.tab_s, A, E, a.C, a.slot_idx, a.miss_list, a.miss_count, a.slot_count,
-                      a.slot_offset, a.perm, a.pos, a.active_slots, a.n_active, L.cnt_s, L.off_s, L.scan_s,
-                      L.sidx_s);
+        block_post(idx, (const int32_t *)L.tab_s, A, E, a.C, a.hist, a.slot_idx, a.miss_list, a.miss_count, a.slot_count,
+                   a.slot_offset, a.perm, a.pos, a.active_slots, a.n_active, L.hist_s, L.cnt_s, L.off_s,
+                   L.scan_s, L.sidx_s);
+    else if (a.hist)
+        block_histogram(idx, A, E, a.hist, L.hist_s);
     if (tid == 0) atomicExch(a.ticket, 0u);
 }
 
@@ -305,7 +334,7 @@ __global__ __launch_bounds__(kRouteThreads) void histogram_kernel(const int32_t 
                                                                    int32_t *hist)
 {
     extern __shared__ int dyn[];
-    block_histogram(idx, A, E, hist, dyn);
+    block_histogram(idx, A, E, hist, (lds_i32 *)dyn);
 }
 
 // large inputs: zero, then per-workgroup LDS histograms merged with integer atomics
@@ -340,8 +369,8 @@ __global__ __launch_bounds__(kRouteThreads) void resolve_kernel(const int32_t *i
 {
     extern __shared__ int dyn[];
     PostLds L = carve_lds(dyn, 0, C, A);
-    block_resolve(idx, slot_table, A, E, C, slot_idx, miss_list, miss_count, slot_count, slot_offset, perm,
-                  pos, active_slots, n_active, L.cnt_s, L.off_s, L.scan_s, L.sidx_s);
+    block_post(idx, slot_table, A, E, C, nullptr, slot_idx, miss_list, miss_count, slot_count, slot_offset,
+               perm, pos, active_slots, n_active, L.hist_s, L.cnt_s, L.off_s, L.scan_s, L.sidx_s);
 }
 
 __global__ void clear_ctrl_kernel(unsigned *ctrl)
@@ -353,7 +382,17 @@ __global__ void clear_ctrl_kernel(unsigned *ctrl)
 
 hipError_t launch_route(const RouteArgs &a, hipStream_t s)
 {
-    size_t lds = post_lds_bytes(a.E, a.slot_table ? a.C : 0, a.T * a.k);
+    size_t lds = post_lds_bytes(a.E, a.slot_table ? a.C : 0, a.T * a.k, true);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)route_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kLdsBytes - 1024);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void *)resolve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes - 1024);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
     prof_begin(0, s);
     hipLaunchKernelGGL(route_kernel, dim3(a.E), dim3(kRouteThreads), lds, s, a);
     prof_end(0, s);
@@ -367,7 +406,7 @@ hipError_t launch_histogram(const int32_t *topk_idx, int A, int E, int32_t *hist
         hipLaunchKernelGGL(histogram_kernel, dim3(1), dim3(kRouteThreads), lds, s, topk_idx, A, E, hist);
     } else {
         hipLaunchKernelGGL(zero_kernel, dim3((E + 255) / 256), dim3(256), 0, s, hist, E);
-        int blocks = (A + kRouteThreads * 64 - 1) / (kRouteThreads * 64);
+        int blocks = (A + kRouteThreads * 16 - 1) / (kRouteThreads * 16);
         if (blocks > 1024) blocks = 1024;
         hipLaunchKernelGGL(histogram_multi_kernel, dim3(blocks), dim3(kRouteThreads), lds, s, topk_idx, A,
                            E, hist);
@@ -380,7 +419,7 @@ hipError_t launch_resolve(const int32_t *topk_idx, const int32_t *slot_table, in
                           int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
                           unsigned *n_active, hipStream_t s)
 {
-    size_t lds = post_lds_bytes(0, C, A);
+    size_t lds = post_lds_bytes(0, C, A, false);
     hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(kRouteThreads), lds, s, topk_idx, slot_table, A, E, C,
                        slot_idx, miss_list, miss_count, slot_count, slot_offset, perm, pos, active_slots,
                        n_active);
@@ -391,7 +430,7 @@ hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_
                                    int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
                                    unsigned *n_active, hipStream_t s)
 {
-    size_t lds = post_lds_bytes(0, C, A);
+    size_t lds = post_lds_bytes(0, C, A, false);
     prof_begin(1, s);
     hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(kRouteThreads), lds, s, (const int32_t *)nullptr,
                        (const int32_t *)nullptr, A, 0, C, const_cast<int32_t *>(slot_idx),

@@ -26,6 +26,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the gate/up stream kernel from rocprofv3 counters (FETCH_SIZE scaled by
+# 2.000 from a 1 GiB copy, plus WRITE_SIZE), mean over the dispatches of the default workload; the
+# two --pmc runs and the calibration are recorded in profiles/stream_kernels_cfg2.txt.
+MEASURED_TRAFFIC_BYTES = {"cfg2": int((222751.6 + 148.5) * 1024)}
 
 
 def parse_args():
@@ -38,6 +42,9 @@ def parse_args():
     p.add_argument("--copies", type=int, default=0, help="distinct layers to rotate over (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-seconds", type=float, default=10.0)
+    p.add_argument("--calibration-copy", action="store_true",
+                   help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling "
+                        "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return p.parse_args()
 
 
@@ -107,6 +114,12 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # timed region 1: K steps, wall clock between synchronisations -> value
     t0 = time.perf_counter()
@@ -139,7 +152,8 @@ def main():
     achieved = bytes_per_launch / ffn_avg_s / 1e9
     roofline = {"bound": "hbm", "kernel": "stream_kernel<gate/up>" if down_n else "ffn_kernel (gate/up/down fused)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if not args.copies else None,
                 "avg_kernel_us": round(ffn_avg_s * 1e6, 2),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch), "kernels": kernels}
     if down_n:

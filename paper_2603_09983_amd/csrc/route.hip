@@ -133,7 +133,8 @@ __device__ void block_histogram(const int32_t *idx, int A, int E, int32_t *hist,
 // list of active slots, by one workgroup.  idx / slot_table may point to LDS copies.
 //   hist == nullptr: no histogram.   slot_table == nullptr: slot_idx is an input (lists only).
 // LDS: hist_s[E], cnt_s[C], off_s[C+1], scan_s[32], sidx_s[min(A, kLdsCopy)].
-__device__ void block_post(const int32_t *idx, const int32_t *slot_table, int A, int E, int C, int32_t *hist,
+template <typename IdxPtr, typename TabPtr>
+__device__ void block_post(IdxPtr idx, TabPtr slot_table, int A, int E, int C, int32_t *hist,
                            int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, int32_t *slot_count,
                            int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
                            unsigned *n_active, lds_i32 *hist_s, lds_i32 *cnt_s, lds_i32 *off_s, lds_i32 *scan_s,
@@ -321,12 +322,19 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
     __syncthreads();
 
     const int32_t *idx = idx_in_lds ? (const int32_t *)L.idx_s : a.topk_idx;
-    if (a.slot_table)
-        block_post(idx, (const int32_t *)L.tab_s, A, E, a.C, a.hist, a.slot_idx, a.miss_list, a.miss_count, a.slot_count,
-                   a.slot_offset, a.perm, a.pos, a.active_slots, a.n_active, L.hist_s, L.cnt_s, L.off_s,
-                   L.scan_s, L.sidx_s);
-    else if (a.hist)
+    if (a.slot_table) {
+        // ids and slot table are read through LDS-typed pointers when they are in LDS (the usual case)
+        if (idx_in_lds)
+            block_post(L.idx_s, L.tab_s, A, E, a.C, a.hist, a.slot_idx, a.miss_list, a.miss_count, a.slot_count,
+                       a.slot_offset, a.perm, a.pos, a.active_slots, a.n_active, L.hist_s, L.cnt_s, L.off_s,
+                       L.scan_s, L.sidx_s);
+        else
+            block_post(idx, L.tab_s, A, E, a.C, a.hist, a.slot_idx, a.miss_list, a.miss_count, a.slot_count,
+                       a.slot_offset, a.perm, a.pos, a.active_slots, a.n_active, L.hist_s, L.cnt_s, L.off_s,
+                       L.scan_s, L.sidx_s);
+    } else if (a.hist) {
         block_histogram(idx, A, E, a.hist, L.hist_s);
+    }
     if (tid == 0) atomicExch(a.ticket, 0u);
 }
 

@@ -15,7 +15,16 @@ constexpr int kSliceF = 128;      // FFN rows (gate/up outputs) owned by one wor
 constexpr int kFfnThreads = 512;  // 8 wavefronts, 16 FFN rows each
 constexpr int kLdsBytes = 160 * 1024;
 constexpr int kCtrlBytes = 256;
-constexpr int kStreamMaxT = 16;   // batches up to this size take the streaming kernels
+// contraction lengths up to this many columns are parked in LDS whole (one panel per item)
+constexpr int kPanelMax = 2048;
+
+// The streaming kernels (stream.hip) take every batch of up to 32 tokens, and larger batches when
+// every item is a single panel; only wide matrices with large batches fall back to ffn.hip.
+static inline bool use_stream_kernels(int T, int H, int F, int n_shared, int F_shared)
+{
+    if (T <= 32) return true;
+    return H <= kPanelMax && F <= kPanelMax && (n_shared == 0 || F_shared <= kPanelMax);
+}
 
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -42,13 +51,13 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
     w.slot_count = o;  o += align256((size_t)(C > 0 ? C : 1) * 4);
     w.slot_offset = o; o += align256((size_t)(C + 1) * 4);
     w.active = o;      o += align256((size_t)(C > 0 ? C : 1) * 4);
-    if (T > kStreamMaxT) {
+    if (!use_stream_kernels(T, H, F, n_shared, F_shared)) {
         // large batches: per-slice partial sums of the fused FFN kernel
         w.part = o;    o += align256((size_t)n_slices(F) * A * H * 4);
         w.part_sh = o; o += align256((size_t)n_shared * n_slices(F_shared) * T * H * 4);
         w.act = w.act_sh = w.o = w.o_sh = o;
     } else {
-        // up to 16 tokens: activations and per-assignment outputs of the streaming kernels
+        // activations and per-assignment outputs of the streaming kernels
         w.part = w.part_sh = o;
         w.act = o;     o += align256(A * F * 2);
         w.act_sh = o;  o += align256((size_t)n_shared * T * F_shared * 2);

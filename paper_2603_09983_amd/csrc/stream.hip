@@ -70,7 +70,9 @@ __device__ inline uint32_t f32_to_bf16_rne(float f)
 // park tile t, put tile t+2 in flight, multiply.  That is what lets the wait before a park leave
 // the younger tile in flight.  The state of the two walks over the run (the tile to load next,
 // the tile being consumed) lives in plain scalars and is stepped, not recomputed.
-template <bool GATEUP, int NPI>
+// NG = token groups of 16 multiplied per pass (1 for batches up to 16 tokens, 2 up to 32; experts
+// with more tokens than one pass holds take further passes over the parked tile).
+template <bool GATEUP, int NPI, int NG>
 __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes)
 {
     constexpr int RPI = GATEUP ? 8 : 16;    // output rows per item
@@ -79,11 +81,11 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
 
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *tile_s = lds;
-    float *red_s = (float *)(lds + tile_lds_bytes);                   // [wavefront][lane][4]
-    int *ctl_s = (int *)(lds + tile_lds_bytes + kWaves * kWave * 16);
+    float *red_s = (float *)(lds + tile_lds_bytes);                   // [group][wavefront][lane][4]
+    int *ctl_s = (int *)(lds + tile_lds_bytes + NG * kWaves * kWave * 16);
     int *count_s = ctl_s, *offset_s = ctl_s + a.C, *active_s = ctl_s + 2 * a.C, *perm_s = ctl_s + 3 * a.C;
-    float *out_s = (float *)(perm_s + a.T * a.k);                     // [kOutCap][kOutPerItem] results waiting to be stored
-    int *odesc_s = (int *)(out_s + kOutCap * kOutPerItem);            // [kOutCap][4]: shared?, row of token 0, column bytes, m
+    float *out_s = (float *)(perm_s + a.T * a.k);                     // [kOutCap][NG][kOutPerItem] results waiting to be stored
+    int *odesc_s = (int *)(out_s + kOutCap * NG * kOutPerItem);       // [kOutCap][8]: shared?, row of token 0, column bytes, m, first token
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wavefront id, known to be uniform
@@ -250,22 +252,55 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     issue(1);
     prod_advance();
 
-    u32x4 bx[kPieces];
-    int bx_key = -1, bx_panel = -1;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    int flushed = 0;   // items of this run whose results have left the LDS output buffer
+    u32x4 bx[NG][kPieces];
+    int bx_key = -1, bx_panel = -1;   // expert (and panel) whose FIRST token pass the registers hold
+    f32x4 acc[NG];
+    int orec = 0, flushed = 0;   // output records written to / flushed from the LDS output buffer
+
+    // B operand of this wavefront's column blocks for the token pass starting at token tok0:
+    // token tok0 + 16*gr + n sits on column n of group gr.  Drains every load in flight (rare path).
+    auto load_bx = [&](int tok0) {
+        const int nkb = c_rs / 64;
+        const uint16_t *bbase = a.bsrc;
+        if (!GATEUP && csh) bbase = a.bsrc_sh;
+#pragma unroll
+        for (int gr = 0; gr < NG; ++gr) {
+            const int tk = tok0 + 16 * gr + n;
+            int boff = -1;
+            if (tk < cm) boff = (cbrow0 >= 0 ? cbrow0 + tk : perm_s[corow0 + tk] / a.k) * cK + cpan * (c_rs / 2);
+#pragma unroll
+            for (int j = 0; j < kPieces; ++j) {
+                int kb = w + kWaves * j;
+                bx[gr][j] = (u32x4){0u, 0u, 0u, 0u};
+                if (kb < nkb && boff >= 0) bx[gr][j] = *(const u32x4 *)(bbase + (unsigned)(boff + kb * 32 + g * 8));
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    };
+    auto multiply = [&]() {
+        const int nkb = c_rs / 64;
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) {
+            int kb = w + kWaves * j;
+            if (kb < nkb) {
+                u32x4 av = *(const u32x4 *)(tile_s + n * (c_rs + kRowPad) + kb * 64 + g * 16);
+#pragma unroll
+                for (int gr = 0; gr < NG; ++gr) acc[gr] = mfma(av, bx[gr][j], acc[gr]);
+            }
+        }
+    };
 
     // Results wait in LDS and leave in batches: a store in the steady state would make every
     // later wait on the weight loads a wait for everything (loads and stores share one counter).
-    auto flush = [&](int upto) {
-        for (int p = flushed; p < upto; ++p) {
-            const int slot = p % kOutCap;
-            const int *d = odesc_s + slot * 4;
-            if (tid < kOutPerItem) {
-                const int q = tid;
-                const int tok = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3);
+    auto flush = [&]() {
+        for (int r = flushed; r < orec; ++r) {
+            const int slot = r % kOutCap;
+            const int *d = odesc_s + slot * 8;
+            if (tid < NG * kOutPerItem) {
+                const int gr = tid / kOutPerItem, q = tid - gr * kOutPerItem;
+                const int tok = d[4] + 16 * gr + ((q >> 2) & 15), row = 4 * (q >> 6) + (q & 3);
                 if (tok < d[3]) {
-                    const float v = out_s[slot * kOutPerItem + q];
+                    const float v = out_s[slot * (NG * kOutPerItem) + tid];
                     // explicit global stores (a generic-pointer store would count as an LDS access too)
                     if (d[0]) {
                         unsigned char *orow = (unsigned char *)a.out_sh + (size_t)(d[1] + tok) * (a.R_sh * OB) + d[2];
@@ -279,75 +314,79 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
                 }
             }
         }
-        flushed = upto;
+        flushed = orec;
         __builtin_amdgcn_s_waitcnt(0);   // every counter to zero: the stores are done before streaming resumes
+    };
+
+    // The sixteen partial 16x16 results of each token group (already posted in red_s, barrier passed),
+    // added in wavefront order.  Element q = lane*4 + j of the MFMA result layout is token (q/4)%16,
+    // tile row 4*(q/64) + q%4; gate rows are tile rows 0..7 and the up row of the same activation
+    // sits 128 elements further on.
+    auto reduce_to_record = [&](int tok0) {
+        const int slot = orec % kOutCap;
+        if (tid < NG * kOutPerItem) {
+            const int gr = tid / kOutPerItem, q = tid - gr * kOutPerItem;
+            const float *r = red_s + gr * (kWaves * kWave * 4);
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int v = 0; v < kWaves; ++v) {
+                s0 += r[v * kWave * 4 + q];
+                if (GATEUP) s1 += r[v * kWave * 4 + q + 128];
+            }
+            out_s[slot * (NG * kOutPerItem) + tid] = GATEUP ? s0 / (1.f + expf(-s0)) * s1 : s0;
+        }
+        if (tid == 0) {
+            int *d = odesc_s + slot * 8;
+            d[0] = csh ? 1 : 0; d[1] = corow0; d[2] = cocol; d[3] = cm; d[4] = tok0;
+        }
+        ++orec;
+    };
+    auto post_partials = [&]() {
+#pragma unroll
+        for (int gr = 0; gr < NG; ++gr) *(f32x4 *)(red_s + ((gr * kWaves + w) * kWave + lane) * 4) = acc[gr];
     };
 
     // one tile: refresh the B operand if the expert changed, park the tile, put the tile two steps
     // ahead in flight, multiply, and on the item's last panel reduce into the output buffer
     auto step = [&](int s) {
-        const int nkb = c_rs / 64;
         if (bx_key != ckey || bx_panel != cpan) {
-            // B operand of this wavefront's column blocks: token n on the MFMA N axis
-            const uint16_t *bbase = a.bsrc;
-            if (!GATEUP && csh) bbase = a.bsrc_sh;
-            int boff = -1;
-            if (n < cm) boff = (cbrow0 >= 0 ? cbrow0 + n : perm_s[corow0 + n] / a.k) * cK + cpan * (c_rs / 2);
-#pragma unroll
-            for (int j = 0; j < kPieces; ++j) {
-                int kb = w + kWaves * j;
-                bx[j] = (u32x4){0u, 0u, 0u, 0u};
-                if (kb < nkb && boff >= 0) bx[j] = *(const u32x4 *)(bbase + (unsigned)(boff + kb * 32 + g * 8));
-            }
+            load_bx(0);
             bx_key = ckey;
             bx_panel = cpan;
-            // rare path (a new expert): drain the loads here so that the steady state never waits
-            // on the B operand behind the weight tiles in flight
-            __builtin_amdgcn_s_waitcnt(0x0F70);
         }
         park(s);
         issue(s);
         prod_advance();
         __syncthreads();
-        if (cpan == 0) acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (cpan == 0) {
 #pragma unroll
-        for (int j = 0; j < kPieces; ++j) {
-            int kb = w + kWaves * j;
-            if (kb < nkb) {
-                u32x4 av = *(const u32x4 *)(tile_s + n * (c_rs + kRowPad) + kb * 64 + g * 16);
-                acc = mfma(av, bx[j], acc);
-            }
+            for (int gr = 0; gr < NG; ++gr) acc[gr] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
+        multiply();
         const bool last_panel = cpan + 1 == cnpan;
-        if (last_panel) *(f32x4 *)(red_s + (w * kWave + lane) * 4) = acc;
+        if (last_panel) post_partials();
         __syncthreads();   // every wavefront is done with the tile in LDS (and its partial result is posted)
         if (last_panel) {
-            const int slot = cp % kOutCap;
-            if (tid < kOutPerItem) {
-                // The sixteen partial 16x16 results, added in wavefront order.  Element q = lane*4 + j
-                // of the MFMA result layout is token (q/4)%16, tile row 4*(q/64) + q%4; gate rows are
-                // tile rows 0..7 and the up row of the same activation sits 128 elements further on.
-                const int q = tid;
-                float s0 = 0.f, s1 = 0.f;
+            reduce_to_record(0);
+            // more tokens than one pass holds (only reached with a single panel per item): the tile
+            // stays parked while further passes reload the B operand
+            for (int tok0 = 16 * NG; tok0 < cm; tok0 += 16 * NG) {
+                if (orec - flushed == kOutCap) { __syncthreads(); flush(); }
+                load_bx(tok0);
+                bx_key = -1;
 #pragma unroll
-                for (int v = 0; v < kWaves; ++v) {
-                    s0 += red_s[v * kWave * 4 + q];
-                    if (GATEUP) s1 += red_s[v * kWave * 4 + q + 128];
-                }
-                out_s[slot * kOutPerItem + q] = GATEUP ? s0 / (1.f + expf(-s0)) * s1 : s0;
-            }
-            if (tid == 0) {
-                odesc_s[slot * 4 + 0] = csh ? 1 : 0;
-                odesc_s[slot * 4 + 1] = corow0;
-                odesc_s[slot * 4 + 2] = cocol;
-                odesc_s[slot * 4 + 3] = cm;
+                for (int gr = 0; gr < NG; ++gr) acc[gr] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                multiply();
+                __syncthreads();   // the previous pass has been reduced: red_s is free again
+                post_partials();
+                __syncthreads();
+                reduce_to_record(tok0);
             }
         }
-        const int done = cp + 1;
         cons_advance();
-        if (last_panel && done - flushed == kOutCap) {
+        if (last_panel && orec - flushed == kOutCap) {
             __syncthreads();
-            flush(done);
+            flush();
         }
     };
 
@@ -361,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     }
     if (t < ntiles) step(1);
     __syncthreads();
-    flush(cnt);
+    flush();
 }
 
 // out[t,:] (+)= sum_j w[t,j] * o[pos[t,j],:] + sum_i o_sh[i,t,:], in a fixed order
@@ -414,8 +453,8 @@ int num_cus()
 
 int stream_panel_width(int K)
 {
-    // equal panels, each a multiple of 32 and at most 2048 columns wide
-    for (int np = (K + 2047) / 2048; np <= K / 32; ++np)
+    // equal panels, each a multiple of 32 and at most kPanelMax columns wide
+    for (int np = (K + kPanelMax - 1) / kPanelMax; np <= K / 32; ++np)
         if (K % np == 0 && (K / np) % 32 == 0) return K / np;
     return 0;
 }
@@ -430,18 +469,23 @@ size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup)
 hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s)
 {
     const size_t tile = (size_t)16 * (2 * (a.KP > a.KP_sh ? a.KP : a.KP_sh) + kRowPad);
-    const size_t lds = stream_lds_bytes(a.KP, a.KP_sh, gateup) + (size_t)(3 * a.C + a.T * a.k) * 4 +
-                       (size_t)kOutCap * ((gateup ? 128 : 256) + 4) * 4;
+    const int ngl = a.T > 16 ? 2 : 1;
+    const size_t lds = (size_t)16 * (2 * (a.KP > a.KP_sh ? a.KP : a.KP_sh) + kRowPad) +
+                       (size_t)ngl * kWaves * kWave * 16 + (size_t)(3 * a.C + a.T * a.k) * 4 +
+                       (size_t)kOutCap * (ngl * (gateup ? 128 : 256) + 8) * 4;
+    if (lds > (size_t)kLdsBytes) return hipErrorInvalidValue;
     const int kp_max = a.KP > a.KP_sh ? a.KP : a.KP_sh;
     const int npi = (kp_max / 32 + kWaves - 1) / kWaves;   // 1..4 pieces per wavefront and tile
-    const void *fns[2][4] = {
-        {(const void *)stream_kernel<false, 1>, (const void *)stream_kernel<false, 2>,
-         (const void *)stream_kernel<false, 3>, (const void *)stream_kernel<false, 4>},
-        {(const void *)stream_kernel<true, 1>, (const void *)stream_kernel<true, 2>,
-         (const void *)stream_kernel<true, 3>, (const void *)stream_kernel<true, 4>}};
-    const void *fn = fns[gateup ? 1 : 0][npi - 1];
-    static bool attr_done[8] = {};
-    const int which = (gateup ? 4 : 0) + npi - 1;
+    const int ng = a.T > 16 ? 2 : 1;
+#define MOE_STREAM_FN(GU, N) \
+    {(const void *)stream_kernel<GU, N, 1>, (const void *)stream_kernel<GU, N, 2>}
+    static const void *const fns[2][4][2] = {
+        {MOE_STREAM_FN(false, 1), MOE_STREAM_FN(false, 2), MOE_STREAM_FN(false, 3), MOE_STREAM_FN(false, 4)},
+        {MOE_STREAM_FN(true, 1), MOE_STREAM_FN(true, 2), MOE_STREAM_FN(true, 3), MOE_STREAM_FN(true, 4)}};
+#undef MOE_STREAM_FN
+    const void *fn = fns[gateup ? 1 : 0][npi - 1][ng - 1];
+    static bool attr_done[16] = {};
+    const int which = ((gateup ? 4 : 0) + npi - 1) * 2 + ng - 1;
     if (!attr_done[which]) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;

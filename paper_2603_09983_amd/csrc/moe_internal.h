@@ -22,6 +22,8 @@ constexpr int kPanelMax = 2048;
 // every item is a single panel; only wide matrices with large batches fall back to ffn.hip.
 static inline bool use_stream_kernels(int T, int H, int F, int n_shared, int F_shared)
 {
+    // (their 1 KB pieces must not straddle the middle of a 16-row tile: row bytes a multiple of 128)
+    if (H % 64 != 0 || F % 64 != 0 || (n_shared > 0 && F_shared % 64 != 0)) return false;
     if (T <= 32) return true;
     return H <= kPanelMax && F <= kPanelMax && (n_shared == 0 || F_shared <= kPanelMax);
 }

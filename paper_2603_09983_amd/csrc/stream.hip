@@ -70,11 +70,14 @@ __device__ inline uint32_t f32_to_bf16_rne(float f)
 // park tile t, put tile t+2 in flight, multiply.  That is what lets the wait before a park leave
 // the younger tile in flight.  The state of the two walks over the run (the tile to load next,
 // the tile being consumed) lives in plain scalars and is stepped, not recomputed.
-// NG = token groups of 16 multiplied per pass (1 for batches up to 16 tokens, 2 up to 32; experts
-// with more tokens than one pass holds take further passes over the parked tile).
-template <bool GATEUP, int NPI, int NG>
+// MODE 0: batches up to 16 tokens (one group of 16 token columns per pass); MODE 1: up to 32 tokens
+// (two groups); MODE 2: larger batches: two groups per pass, and experts with more than 32 tokens
+// take further passes over the parked tile.
+template <bool GATEUP, int NPI, int MODE>
 __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes)
 {
+    constexpr int NG = MODE == 0 ? 1 : 2;   // token groups of 16 multiplied per pass
+    constexpr bool MULTIPASS = MODE == 2;
     constexpr int RPI = GATEUP ? 8 : 16;    // output rows per item
     constexpr int OB = GATEUP ? 2 : 4;      // bytes per output element
     constexpr int kOutPerItem = RPI * 16;   // results of one item (rows x token columns)
@@ -179,15 +182,19 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     };
 
     // Piece i of this wavefront covers bytes [(16i+w) KB, +1 KB) of a tile seen as 16 rows of rs
-    // bytes; this lane's 16 bytes sit at (row, col), packed as row<<16 | col.  A tile of rs-byte rows
-    // has rs/64 pieces (as many as it has 32-wide column blocks).
-    // Two tiles are in flight per wavefront (st[0], st[1]); each remembers its own geometry.
+    // bytes (rs a multiple of 128, so a piece lies wholly in tile rows 0..7 or 8..15 and the choice
+    // between the two row pointers is uniform).  A tile of rs-byte rows has rs/64 pieces (as many as
+    // it has 32-wide column blocks).  For each piece this lane keeps its global byte offset from the
+    // half-tile's first row and its LDS byte offset.  Two tiles are in flight per wavefront (st[0],
+    // st[1]); each remembers its own geometry.
     u32x4 st[2][NPI];
-    int rc[2][NPI];
-    int st_rs[2] = {-1, -1};
+    unsigned goff[2][NPI];
+    int loff[2][NPI];
+    int st_rs[2] = {-1, -1}, st_K2[2] = {-1, -1};
     auto issue = [&](int s) {
-        if (prs != st_rs[s]) {
+        if (prs != st_rs[s] || pK2 != st_K2[s]) {
             st_rs[s] = prs;
+            st_K2[s] = pK2;
             const float inv_d = 16.0f / (float)prs;
             const int np = prs / 64;
 #pragma unroll
@@ -196,23 +203,25 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
                 pc = pc < np ? pc : np - 1;
                 int off = (pc << 10) + (lane << 4);
                 int row = (int)(((float)(off >> 4) + 0.5f) * inv_d);
-                rc[s][i] = (row << 16) | (off - row * prs);
+                int col = off - row * prs;
+                goff[s][i] = (unsigned)((row & 7) * pK2 + col);
+                loff[s][i] = row * (prs + kRowPad) + col;
             }
         }
         const unsigned poff = (unsigned)ppan * (unsigned)prs;
+        const int np = prs / 64;
 #pragma unroll
         for (int i = 0; i < NPI; ++i) {
-            const int row = rc[s][i] >> 16, col = rc[s][i] & 0xffff;
-            const unsigned char *base = row < 8 ? pw0 : pw1;
-            st[s][i] = ld_stream(base + (poff + (unsigned)((row & 7) * pK2 + col)));
+            int pc = i * kWaves + w;
+            pc = pc < np ? pc : np - 1;
+            const unsigned char *base = (pc << 10) < 8 * prs ? pw0 : pw1;   // uniform
+            st[s][i] = ld_stream(base + (poff + goff[s][i]));
         }
     };
     auto park = [&](int s) {
-        const int rs = st_rs[s];
         // (a wavefront's re-read of the last piece lands on that piece's own bytes: same data, no test)
 #pragma unroll
-        for (int i = 0; i < NPI; ++i)
-            *(u32x4 *)(tile_s + (rc[s][i] >> 16) * (rs + kRowPad) + (rc[s][i] & 0xffff)) = st[s][i];
+        for (int i = 0; i < NPI; ++i) *(u32x4 *)(tile_s + loff[s][i]) = st[s][i];
     };
 
     if (s_cnt > 0) {
@@ -370,7 +379,7 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
             reduce_to_record(0);
             // more tokens than one pass holds (only reached with a single panel per item): the tile
             // stays parked while further passes reload the B operand
-            for (int tok0 = 16 * NG; tok0 < cm; tok0 += 16 * NG) {
+            for (int tok0 = 16 * NG; MULTIPASS && tok0 < cm; tok0 += 16 * NG) {
                 if (orec - flushed == kOutCap) { __syncthreads(); flush(); }
                 load_bx(tok0);
                 bx_key = -1;
@@ -476,16 +485,16 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s)
     if (lds > (size_t)kLdsBytes) return hipErrorInvalidValue;
     const int kp_max = a.KP > a.KP_sh ? a.KP : a.KP_sh;
     const int npi = (kp_max / 32 + kWaves - 1) / kWaves;   // 1..4 pieces per wavefront and tile
-    const int ng = a.T > 16 ? 2 : 1;
+    const int mode = a.T > 32 ? 2 : a.T > 16 ? 1 : 0;
 #define MOE_STREAM_FN(GU, N) \
-    {(const void *)stream_kernel<GU, N, 1>, (const void *)stream_kernel<GU, N, 2>}
-    static const void *const fns[2][4][2] = {
+    {(const void *)stream_kernel<GU, N, 0>, (const void *)stream_kernel<GU, N, 1>, (const void *)stream_kernel<GU, N, 2>}
+    static const void *const fns[2][4][3] = {
         {MOE_STREAM_FN(false, 1), MOE_STREAM_FN(false, 2), MOE_STREAM_FN(false, 3), MOE_STREAM_FN(false, 4)},
         {MOE_STREAM_FN(true, 1), MOE_STREAM_FN(true, 2), MOE_STREAM_FN(true, 3), MOE_STREAM_FN(true, 4)}};
 #undef MOE_STREAM_FN
-    const void *fn = fns[gateup ? 1 : 0][npi - 1][ng - 1];
-    static bool attr_done[16] = {};
-    const int which = ((gateup ? 4 : 0) + npi - 1) * 2 + ng - 1;
+    const void *fn = fns[gateup ? 1 : 0][npi - 1][mode];
+    static bool attr_done[24] = {};
+    const int which = ((gateup ? 4 : 0) + npi - 1) * 3 + mode;
     if (!attr_done[which]) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;

@@ -65,6 +65,16 @@ int moe_workspace_bytes(const moe_shape_t *shape, size_t *bytes_out);
  * control block cleared again when its kernels finish. */
 int moe_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
+/* Synchronous health check: waits for `stream`, then reads the control block.
+ * Kernels that wait for one another inside a launch (the layer's routing
+ * results are handed from the first workgroups to all others through device
+ * memory) poll a bounded number of times and, should that bound ever run out,
+ * set a flag in the control block and finish with unspecified results instead
+ * of waiting for ever.  Returns MOE_OK when no such flag is set,
+ * MOE_ERR_LAUNCH when one is (the flag is cleared, the workspace stays usable)
+ * or when the copy fails.  workspace: device pointer. */
+int moe_workspace_status(void *workspace, size_t workspace_bytes, void *stream);
+
 /* Step 1 -- Sec. 2.2, lines one to three of the MoE equation.
  *   s = W_g h (+ bias), the k largest logits per token (listed by descending
  *   logit, ties to the lower expert id), g = softmax restricted to those k.

@@ -36,12 +36,13 @@ _lib.moe_status_string.restype = ctypes.c_char_p
 _lib.moe_status_string.argtypes = [_i]
 _lib.moe_workspace_bytes.argtypes = [ctypes.POINTER(MoeShape), ctypes.POINTER(_sz)]
 _lib.moe_workspace_init.argtypes = [_vp, _sz, _vp]
+_lib.moe_workspace_status.argtypes = [_vp, _sz, _vp]
 _lib.moe_route_topk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moe_expert_histogram.argtypes = [_vp, _i, _i, _i, _vp, _vp]
 _lib.moe_slot_resolve.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moe_grouped_ffn.argtypes = [_vp] * 6 + [_i] * 5 + [_vp, _i, _i, _vp, _sz, _vp]
 _lib.moe_verify_layer.argtypes = [ctypes.POINTER(MoeShape)] + [_vp] * 17 + [_i, _i, _vp, _sz, _vp]
-for _f in ("moe_workspace_bytes", "moe_workspace_init", "moe_route_topk", "moe_expert_histogram",
+for _f in ("moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk", "moe_expert_histogram",
            "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer"):
     getattr(_lib, _f).restype = _i
 
@@ -53,7 +54,7 @@ _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
 KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_KINDS = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ("moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
+EXPORTS = ("moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
 
 
@@ -116,6 +117,11 @@ def moe_workspace_bytes(shape: MoeShape) -> int:
 def moe_workspace_init(workspace: torch.Tensor, stream=None, check=True) -> int:
     return _check(_lib.moe_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
                                           _stream(stream)), "moe_workspace_init", check)
+
+
+def moe_workspace_status(workspace: torch.Tensor, stream=None, check=True) -> int:
+    return _check(_lib.moe_workspace_status(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream(stream)), "moe_workspace_status", check)
 
 
 def new_workspace(shape: MoeShape, device="cuda") -> torch.Tensor:

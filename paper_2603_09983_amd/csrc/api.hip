@@ -28,7 +28,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 int check_route_shape(int T, int H, int E, int k)
 {
     if (T < 1 || H < 1 || E < 1 || k < 1 || k > E || E > kMaxE || k > kMaxK) return MOE_ERR_SHAPE;
-    if ((size_t)T * k > (size_t)1 << 30) return MOE_ERR_SHAPE;
+    if ((size_t)T * k > (size_t)1 << 30 || (size_t)T * E > (size_t)kTagEntries) return MOE_ERR_SHAPE;
     if (H % 8 != 0) return MOE_ERR_ALIGN;
     return MOE_OK;
 }
@@ -127,8 +127,26 @@ extern "C" int moe_workspace_init(void *workspace, size_t workspace_bytes, void 
     if (!workspace) return MOE_ERR_NULL;
     if (workspace_bytes < (size_t)kCtrlBytes) return MOE_ERR_WORKSPACE;
     if (!aligned16(workspace)) return MOE_ERR_ALIGN;
-    hipError_t e = launch_clear_ctrl(workspace, (hipStream_t)stream);
+    hipError_t e = launch_clear_ctrl(workspace, workspace_bytes, (hipStream_t)stream);
     return e == hipSuccess ? MOE_OK : launch_failed(e);
+}
+
+extern "C" int moe_workspace_status(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return MOE_ERR_NULL;
+    if (workspace_bytes < (size_t)kCtrlBytes) return MOE_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned ctrl[kCtrlBytes / 4];
+    hipError_t e = hipMemcpyAsync(ctrl, workspace, sizeof ctrl, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return launch_failed(e);
+    if (ctrl[kCtrlError] == 0u) return MOE_OK;
+    // a wait ran out part-way through a call: start again from a clean control block and tag region
+    e = launch_clear_ctrl(workspace, workspace_bytes, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return launch_failed(e);
+    snprintf(g_launch_msg, sizeof g_launch_msg, "a bounded wait inside a kernel ran out (results of that call are invalid)");
+    return MOE_ERR_LAUNCH;
 }
 
 extern "C" int moe_route_topk(const void *hidden, const float *router_w, const float *router_bias, int T,
@@ -140,13 +158,14 @@ extern "C" int moe_route_topk(const void *hidden, const float *router_w, const f
     if (rc) return rc;
     if (!aligned16(hidden) || !aligned16(router_w) || !aligned16(workspace)) return MOE_ERR_ALIGN;
     WsLayout w = ws_layout(T, E, k, 0, 0, 0, 0, 0);
-    if (workspace_bytes < w.perm) return MOE_ERR_WORKSPACE;   // control block + logits
+    if (workspace_bytes < w.perm) return MOE_ERR_WORKSPACE;   // control block + tagged logits
     char *ws = (char *)workspace;
     RouteArgs a = {};
     a.hidden = hidden; a.router_w = router_w; a.router_bias = router_bias;
     a.T = T; a.H = H; a.E = E; a.k = k;
-    a.logits_ws = (float *)(ws + w.logits);
-    a.ticket = (unsigned *)(ws + w.ctrl) + kCtrlTicket;
+    a.tagged_logits = (unsigned long long *)(ws + w.tagged);
+    a.epoch = (unsigned *)(ws + w.ctrl) + kCtrlEpoch;
+    a.error_flag = (unsigned *)(ws + w.ctrl) + kCtrlError;
     a.topk_idx = topk_idx; a.topk_w = topk_w; a.logits_opt = logits_opt;
     hipError_t e = launch_route(a, (hipStream_t)stream);
     return e == hipSuccess ? MOE_OK : launch_failed(e);
@@ -293,8 +312,9 @@ extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const
     RouteArgs r = {};
     r.hidden = hidden; r.router_w = router_w; r.router_bias = router_bias;
     r.T = sh->T; r.H = sh->H; r.E = sh->E; r.k = sh->k;
-    r.logits_ws = (float *)(ws + w.logits);
-    r.ticket = (unsigned *)(ws + w.ctrl) + kCtrlTicket;
+    r.tagged_logits = (unsigned long long *)(ws + w.tagged);
+    r.epoch = (unsigned *)(ws + w.ctrl) + kCtrlEpoch;
+    r.error_flag = (unsigned *)(ws + w.ctrl) + kCtrlError;
     r.topk_idx = topk_idx; r.topk_w = topk_w; r.logits_opt = nullptr; r.hist = hist;
     r.slot_table = slot_table; r.C = sh->C;
     r.slot_idx = slot_idx; r.miss_list = miss_list; r.miss_count = miss_count;

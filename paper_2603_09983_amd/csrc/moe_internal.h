@@ -30,14 +30,22 @@ static inline bool use_stream_kernels(int T, int H, int F, int n_shared, int F_s
 
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Inside the routing kernel the logits travel from the workgroups that compute them to the one
+// that ranks them as 64-bit (tag, value) entries, tag = number of the call on this workspace: an
+// entry that carries the call's tag holds the call's value, so no counter and no fence is needed.
+// The region has a fixed size and sits right behind the control block; moe_workspace_init clears
+// it (no stale entry may carry a future tag).
+constexpr int kTagEntries = 65536;   // 512 KB: T*E of the largest routing call that uses them
+
 // Byte offsets of the scratch arrays inside the caller's workspace.
 struct WsLayout {
-    size_t ctrl, logits, perm, pos, slot_count, slot_offset, active, part, part_sh, act, act_sh, o, o_sh, total;
+    size_t ctrl, tagged, perm, pos, slot_count, slot_offset, active, part, part_sh, act, act_sh, o, o_sh, total;
 };
 
 // control block words
-constexpr int kCtrlTicket = 0;    // arrival counter of the routing kernel
 constexpr int kCtrlNActive = 1;   // number of resident slots that received at least one token
+constexpr int kCtrlError = 2;     // non-zero once a bounded wait inside a kernel has run out
+constexpr int kCtrlEpoch = 3;     // routing calls completed on this workspace (the tag of the last one)
 
 static inline int n_slices(int F) { return (F + kSliceF - 1) / kSliceF; }
 
@@ -47,7 +55,7 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
     size_t A = (size_t)T * k;
     size_t o = 0;
     w.ctrl = o;        o += kCtrlBytes;
-    w.logits = o;      o += align256((size_t)T * E * 4);
+    w.tagged = o;      o += (size_t)kTagEntries * 8;   // (same place whatever the entry point and shape)
     w.perm = o;        o += align256(A * 4);
     w.pos = o;         o += align256(A * 4);
     w.slot_count = o;  o += align256((size_t)(C > 0 ? C : 1) * 4);
@@ -76,8 +84,6 @@ struct RouteArgs {
     const float *router_w;     // [E,H]
     const float *router_bias;  // [E] or null
     int T, H, E, k;
-    float *logits_ws;          // [T,E] scratch
-    unsigned *ticket;          // control word, zero on entry, zero on exit
     int32_t *topk_idx;         // [T,k]
     float *topk_w;             // [T,k]
     float *logits_opt;         // [T,E] or null
@@ -94,6 +100,9 @@ struct RouteArgs {
     int32_t *pos;              // [T*k]
     int32_t *active_slots;     // [C] slots with at least one token, ascending
     unsigned *n_active;        // [1]
+    unsigned *error_flag;      // control word set when a bounded wait inside a kernel ran out
+    unsigned long long *tagged_logits;   // [T*E] (tag << 32 | value bits)
+    unsigned *epoch;           // control word: tag of the last completed call
 };
 
 // Arguments of the streaming kernels (gate/up: R = F rows, K = H; down: R = H rows, K = F).
@@ -143,7 +152,8 @@ int stream_panel_width(int K);     // 0 when K has no panel split
 size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup);
 hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
-hipError_t launch_clear_ctrl(void *ctrl, hipStream_t s);
+// clears the control block and, if `bytes` reaches that far, the tagged-logit region behind it
+hipError_t launch_clear_ctrl(void *workspace, size_t bytes, hipStream_t s);
 // event bracketing for the measurement aid (no-ops unless enabled)
 void prof_begin(int kind, hipStream_t s);
 void prof_end(int kind, hipStream_t s);

@@ -6,13 +6,16 @@
 //
 // These steps move a few hundred kilobytes; what they cost is the chain of
 // dependent trips to memory and of workgroup barriers, so the kernel is built
-// to keep that chain short.  One workgroup per expert row computes that
-// expert's logit for every token, one wavefront per token (a wavefront owns a
-// whole dot product, so there is no cross-wavefront reduction).  The
-// workgroup that finishes last (ticket in the workspace control block) owns
-// every logit and runs the integer steps out of LDS: one wavefront per token
-// ranks the logits, then the histogram, slot counts, miss list and per-slot
-// lists are produced by independent threads between three barriers.
+// to keep that chain short.  The T*E dot products are dealt one per wavefront,
+// round-robin over as many workgroups as the device has CUs (a CU that had to
+// fetch the operands of sixteen of them takes microseconds longer than one
+// that fetches two or three).  Each logit goes to memory together with the
+// number of the call as ONE 64-bit atomic store; workgroup 0, one wavefront
+// per token, reads the entries with atomic loads until they carry that number
+// (a bounded number of times), so the hand-over needs no counter, no fence and
+// no cache write-back.  It then runs the integer steps out of LDS: ranks the
+// logits, and produces histogram, slot counts, miss list and per-slot lists
+// with independent threads between a few barriers.
 #include "moe_internal.h"
 
 namespace moe {
@@ -33,26 +36,19 @@ typedef __attribute__((address_space(3))) float lds_f32;
 typedef __attribute__((address_space(3))) int lds_i32;
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) const f32x4v lds_f32x4;
-typedef __attribute__((address_space(1))) const volatile float g_vf32;
 typedef __attribute__((address_space(1))) int32_t g_i32;
 typedef __attribute__((address_space(1))) float g_f32;
-
-__device__ inline float load_coherent(const float *p)
-{
-    // read after the acquire fence of the last workgroup; volatile = a load that is not served from
-    // a stale cache line and that the compiler neither hoists nor merges
-    return *(g_vf32 *)(uintptr_t)p;
-}
 
 // One wavefront ranks the E logits of one token: rank(e) = number of experts
 // that beat e (larger logit, or equal logit and lower id).  The experts of
 // rank 0..k-1 are the Top-k in descending-logit order; their gate is
 // exp(s - s_max) normalised over those k, summed in rank order.  Lane l owns
-// experts l, l+64, ...; the logits are shared through `lg` (E floats of LDS
-// private to the wavefront), `sel` (k floats) collects the selected ones.
+// experts l, l+64, ...; the caller has put the logits into `lg` (LDS private to
+// the wavefront: E floats, NaN replaced by -inf, four -inf entries behind the
+// E-th); `sel` (k floats) collects the selected ones.
 template <int NLOC>
-__device__ void wave_topk_gate_n(const float *row, bool coherent, int E, int k, int32_t *idx_out_,
-                                 lds_i32 *idx_lds, float *w_out_, lds_f32 *lg, lds_f32 *sel)
+__device__ __forceinline__ void wave_topk_gate_n(int E, int k, int32_t *idx_out_, lds_i32 *idx_lds,
+                                                 float *w_out_, lds_f32 *lg, lds_f32 *sel)
 {
     g_i32 *idx_out = (g_i32 *)(uintptr_t)idx_out_;
     g_f32 *w_out = (g_f32 *)(uintptr_t)w_out_;
@@ -62,19 +58,10 @@ __device__ void wave_topk_gate_n(const float *row, bool coherent, int E, int k, 
 #pragma unroll
     for (int i = 0; i < NLOC; ++i) {
         int e = lane + kWave * i;
-        v[i] = -INFINITY;
+        v[i] = e < E ? lg[e] : -INFINITY;
         rank[i] = 0;
-        if (e < E) {
-            float x = coherent ? load_coherent(row + e) : row[e];
-            v[i] = (x == x) ? x : -INFINITY;   // NaN cannot win a comparison; rank it last
-            lg[e] = v[i];
-        }
     }
-    // pad to a multiple of four with values that beat nothing
-    if (lane < 4) lg[E + lane] = -INFINITY;
-    // (LDS operations of one wavefront execute in order: the reads below see the writes above)
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll 1
+#pragma unroll 4
     for (int e2 = 0; e2 < E; e2 += 4) {
         const f32x4v o4 = *(lds_f32x4 *)(lg + e2);   // same address in every lane: a broadcast read
         const float o[4] = {o4[0], o4[1], o4[2], o4[3]};
@@ -92,6 +79,7 @@ __device__ void wave_topk_gate_n(const float *row, bool coherent, int E, int k, 
         int e = lane + kWave * i;
         if (e < E && rank[i] < k) sel[rank[i]] = v[i];
     }
+    // (LDS operations of one wavefront execute in order: the reads below see the writes above)
     __builtin_amdgcn_wave_barrier();
     const float smax = sel[0];
     float den = 0.f;
@@ -100,21 +88,25 @@ __device__ void wave_topk_gate_n(const float *row, bool coherent, int E, int k, 
     for (int i = 0; i < NLOC; ++i) {
         int e = lane + kWave * i;
         if (e < E && rank[i] < k) {
-            idx_out[rank[i]] = e;
             if (idx_lds) idx_lds[rank[i]] = e;
+            idx_out[rank[i]] = e;
             w_out[rank[i]] = __expf(v[i] - smax) / den;
         }
     }
 }
 
-__device__ void wave_topk_gate(const float *row, bool coherent, int E, int k, int32_t *idx_out,
-                               lds_i32 *idx_lds, float *w_out, lds_f32 *lg, lds_f32 *sel)
+__device__ __forceinline__ void wave_topk_gate(int E, int k, int32_t *idx_out, lds_i32 *idx_lds, float *w_out,
+                                               lds_f32 *lg, lds_f32 *sel)
 {
-    if (E <= kWave) wave_topk_gate_n<1>(row, coherent, E, k, idx_out, idx_lds, w_out, lg, sel);
-    else if (E <= 2 * kWave) wave_topk_gate_n<2>(row, coherent, E, k, idx_out, idx_lds, w_out, lg, sel);
-    else if (E <= 4 * kWave) wave_topk_gate_n<4>(row, coherent, E, k, idx_out, idx_lds, w_out, lg, sel);
-    else wave_topk_gate_n<kMaxEPL>(row, coherent, E, k, idx_out, idx_lds, w_out, lg, sel);
+    if (E <= kWave) wave_topk_gate_n<1>(E, k, idx_out, idx_lds, w_out, lg, sel);
+    else if (E <= 2 * kWave) wave_topk_gate_n<2>(E, k, idx_out, idx_lds, w_out, lg, sel);
+    else if (E <= 4 * kWave) wave_topk_gate_n<4>(E, k, idx_out, idx_lds, w_out, lg, sel);
+    else wave_topk_gate_n<kMaxEPL>(E, k, idx_out, idx_lds, w_out, lg, sel);
 }
+
+// logits of one token in LDS: E rounded up to a multiple of four, plus four pad entries
+__host__ __device__ inline int lg_stride(int E) { return ((E + 3) & ~3) + 4; }
+
 
 // hist[e] = number of assignments naming expert e (LDS integer atomics).
 __device__ void block_histogram(const int32_t *idx, int A, int E, int32_t *hist, lds_i32 *hist_s)
@@ -233,10 +225,7 @@ __device__ void block_post(IdxPtr idx, TabPtr slot_table, int A, int E, int C, i
     }
 }
 
-// logits of one token in LDS: E rounded up to a multiple of four, plus four pad entries
-__host__ __device__ inline int lg_stride(int E) { return ((E + 3) & ~3) + 4; }
-
-// dynamic LDS: hist_s[E] tab_s[E] cnt_s[C] off_s[C+1] scan_s[32] sidx_s[cap] idx_s[cap] lg_s[waves*E] sel_s[waves*64]
+// dynamic LDS: hist_s[E] tab_s[E] cnt_s[C] off_s[C+1] scan_s[48] sidx_s[cap] idx_s[cap] lg_s[waves*E] sel_s[waves*64]
 struct PostLds {
     lds_i32 *hist_s, *tab_s, *cnt_s, *off_s, *scan_s, *sidx_s, *idx_s;
     lds_f32 *lg_s, *sel_s;
@@ -252,9 +241,9 @@ __device__ inline PostLds carve_lds(int *dyn_, int E, int C, int A)
     p.cnt_s = p.tab_s + E;
     p.off_s = p.cnt_s + C;
     p.scan_s = p.off_s + C + 1;
-    p.sidx_s = p.scan_s + 32;
+    p.sidx_s = p.scan_s + 48;
     p.idx_s = p.sidx_s + cap;
-    p.lg_s = (lds_f32 *)(dyn + ((2 * E + 2 * C + 33 + 2 * cap + 3) & ~3));
+    p.lg_s = (lds_f32 *)(dyn + ((2 * E + 2 * C + 49 + 2 * cap + 3) & ~3));
     p.sel_s = p.lg_s + kRouteWaves * lg_stride(E);
     return p;
 }
@@ -262,31 +251,120 @@ __device__ inline PostLds carve_lds(int *dyn_, int E, int C, int A)
 size_t post_lds_bytes(int E, int C, int A, bool with_topk)
 {
     const int cap = A < kLdsCopy ? A : kLdsCopy;
-    size_t n = (size_t)2 * E + C + (C + 1) + 32 + 2 * cap;
+    size_t n = (size_t)2 * E + C + (C + 1) + 48 + 2 * cap;
     if (with_topk) n += (size_t)kRouteWaves * lg_stride(E) + kRouteWaves * kMaxK + 4;
     return n * sizeof(int);
+}
+
+constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before workgroup 0 gives up waiting
+
+// Small batches (T <= 32, one thread per assignment and per slot): the tokens of each slot as a
+// bit mask (a token names a slot at most once, the slot table being one-to-one), so counts,
+// offsets and list positions are population counts.  Same outputs as block_post.
+__device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, int E, int C, const RouteArgs &r,
+                                 lds_i32 *hist_s, lds_i32 *mask_s, lds_i32 *scan_s, lds_i32 *off_s)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+    const int A = T * kk;
+    const bool valid = tid < A;
+    const int tok = valid ? tid / kk : 0;
+    int c = -1;
+    if (valid) {
+        const int e = idx_s[tid];
+        __hip_atomic_fetch_add(&hist_s[e], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        c = tab_s[e];
+        if ((unsigned)c >= (unsigned)C) c = -1;
+        if (c >= 0) __hip_atomic_fetch_or(&mask_s[c], 1 << tok, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        r.slot_idx[tid] = c;
+    }
+    const bool miss = valid && c < 0;
+    const unsigned long long bal = __ballot(miss);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) scan_s[w] = __popcll(bal);
+    __syncthreads();
+    // slot `tid`: its token count; prefix sums of (count, count > 0) inside the wavefront
+    const int cntv = tid < C ? __popc((unsigned)mask_s[tid]) : 0;
+    int inc_o = cntv, inc_a = cntv > 0 ? 1 : 0;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int to = __shfl_up(inc_o, d, kWave), ta = __shfl_up(inc_a, d, kWave);
+        if (lane >= d) {
+            inc_o += to;
+            inc_a += ta;
+        }
+    }
+    if (lane == kWave - 1) {
+        scan_s[16 + w] = inc_o;
+        scan_s[32 + w] = inc_a;
+    }
+    {
+        int wave_base = 0, total = 0;
+        for (int i = 0; i < kRouteWaves; ++i) {
+            const int v = scan_s[i];
+            if (i < w) wave_base += v;
+            total += v;
+        }
+        if (miss) r.miss_list[wave_base + before] = tid;
+        if (tid == 0) *r.miss_count = total;
+        if (tid < E) r.hist[tid] = hist_s[tid];
+    }
+    __syncthreads();
+    int base_o = 0, base_a = 0, tot_o = 0, tot_a = 0;
+    for (int i = 0; i < kRouteWaves; ++i) {
+        const int vo = scan_s[16 + i], va = scan_s[32 + i];
+        if (i < w) {
+            base_o += vo;
+            base_a += va;
+        }
+        tot_o += vo;
+        tot_a += va;
+    }
+    if (tid < C) {
+        const int off = base_o + inc_o - cntv, na = base_a + inc_a - (cntv > 0 ? 1 : 0);
+        off_s[tid] = off;
+        r.slot_count[tid] = cntv;
+        r.slot_offset[tid] = off;
+        if (cntv > 0) r.active_slots[na] = tid;
+    }
+    if (tid == 0) {
+        r.slot_offset[C] = tot_o;
+        *r.n_active = (unsigned)tot_a;
+    }
+    __syncthreads();
+    // position of an assignment = offset of its slot + number of earlier tokens of that slot
+    if (valid) {
+        int p = -1;
+        if (c >= 0) {
+            p = off_s[c] + __popc((unsigned)mask_s[c] & ((1u << tok) - 1u));
+            r.perm[p] = tid;
+        }
+        r.pos[tid] = p;
+    }
 }
 
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
 {
     extern __shared__ int dyn[];
-    __shared__ int is_last;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-    const int e = blockIdx.x;
-    const int T = a.T, H = a.H, E = a.E;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int b = blockIdx.x, G = gridDim.x;
+    const int T = a.T, H = a.H, E = a.E, TE = T * E;
     const int A = T * a.k;
-    const float *wrow = a.router_w + (size_t)e * H;
+    const unsigned tag = *a.epoch + 1u;   // stamps this call's logits
+
+    // (workgroup 0) the slot table rides along with the first trip to memory
+    int tab_v = -1;
+    if (b == 0 && a.slot_table && tid < E) tab_v = a.slot_table[tid];   // (E <= kMaxE <= kRouteThreads)
+
+    // s[t,e] = W_g[e,:] . h[t,:]: one wavefront per dot product, lanes stride H four at a time
     const uint16_t *x = (const uint16_t *)a.hidden;
-    PostLds L = carve_lds(dyn, E, a.C, A);
-
-    // the slot table rides along with the first trip to memory (only the last workgroup uses it)
-    if (a.slot_table)
-        for (int i = tid; i < E; i += kRouteThreads) L.tab_s[i] = a.slot_table[i];
-
-    // s[t,e]: one wavefront per token owns the whole dot product, lanes stride H four at a time
-    for (int t = w; t < T; t += kRouteWaves) {
+    for (int q = b + w * G; q < TE; q += G * kRouteWaves) {
+        const int t = q / E, e = q - t * E;
+        const float *wrow = a.router_w + (size_t)e * H;
         const uint16_t *xr = x + (size_t)t * H;
+        const float bias = a.router_bias ? a.router_bias[e] : 0.f;
         float acc = 0.f;
+#pragma unroll 8
         for (int h = lane * 4; h < H; h += kWave * 4) {
             float4 wv = *(const float4 *)(wrow + h);
             uint2 xv = *(const uint2 *)(xr + h);
@@ -294,35 +372,57 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
         }
 #pragma unroll
         for (int m = kWave / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, kWave);
+        acc += bias;
         if (lane == 0) {
-            if (a.router_bias) acc += a.router_bias[e];
-            a.logits_ws[(size_t)t * E + e] = acc;
-            if (a.logits_opt) a.logits_opt[(size_t)t * E + e] = acc;
+            __hip_atomic_store(a.tagged_logits + q, ((unsigned long long)tag << 32) | __float_as_uint(acc),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (a.logits_opt) a.logits_opt[q] = acc;
         }
     }
+    if (b != 0) return;
 
-    // The last workgroup to arrive sees every logit.  One thread publishes for the workgroup: the
-    // barrier orders the wavefronts' writes before its release fence (a fence per wavefront would
-    // cost a cache write-back each).
-    __syncthreads();
-    if (tid == 0) {
-        __threadfence();
-        unsigned old = atomicAdd(a.ticket, 1u);
-        is_last = (old == gridDim.x - 1);
+    // ---- workgroup 0: everything after the logits ----
+    PostLds L = carve_lds(dyn, E, a.C, A);
+    const bool small = a.slot_table && a.hist && T <= 32 && A <= kRouteThreads && a.C <= kRouteThreads;
+    if (a.slot_table && tid < E) L.tab_s[tid] = tab_v;
+    if (small) {
+        if (tid < E) L.hist_s[tid] = 0;
+        if (tid < a.C) L.cnt_s[tid] = 0;   // (the token masks)
     }
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-
     const bool idx_in_lds = A <= kLdsCopy;
-    for (int t = w; t < T; t += kRouteWaves)
-        wave_topk_gate(a.logits_ws + (size_t)t * E, true, E, a.k, a.topk_idx + (size_t)t * a.k,
-                       idx_in_lds ? L.idx_s + t * a.k : nullptr, a.topk_w + (size_t)t * a.k, L.lg_s + w * lg_stride(E),
-                       L.sel_s + w * kMaxK);
+    lds_f32 *lg = L.lg_s + w * lg_stride(E);
+    for (int t = w; t < T; t += kRouteWaves) {
+        // wait (a bounded number of polls) until every logit of token t carries the tag
+        const unsigned long long *src = a.tagged_logits + (size_t)t * E;
+        for (int e0 = 0; e0 < E; e0 += kWave) {
+            const int e = e0 + lane;
+            unsigned long long v = (unsigned long long)tag << 32;
+            int polls = 0;
+            for (;;) {
+                if (e < E) v = __hip_atomic_load(src + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (__ballot((unsigned)(v >> 32) != tag) == 0ull) break;
+                if (++polls > kSpinLimit) {   // cannot happen on a healthy device; never wait for ever
+                    if (lane == 0) atomicOr(a.error_flag, 1u);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (e < E) {
+                const float f = __uint_as_float((unsigned)v);
+                lg[e] = (f == f) ? f : -INFINITY;   // NaN cannot win a comparison; rank it last
+            }
+        }
+        if (lane < 4) lg[E + lane] = -INFINITY;
+        __builtin_amdgcn_wave_barrier();
+        wave_topk_gate(E, a.k, a.topk_idx + (size_t)t * a.k, idx_in_lds ? L.idx_s + t * a.k : nullptr,
+                       a.topk_w + (size_t)t * a.k, lg, L.sel_s + w * kMaxK);
+    }
     __syncthreads();
 
     const int32_t *idx = idx_in_lds ? (const int32_t *)L.idx_s : a.topk_idx;
-    if (a.slot_table) {
+    if (small) {
+        block_post_small(L.idx_s, L.tab_s, T, a.k, E, a.C, a, L.hist_s, L.cnt_s, L.scan_s, L.off_s);
+    } else if (a.slot_table) {
         // ids and slot table are read through LDS-typed pointers when they are in LDS (the usual case)
         if (idx_in_lds)
             block_post(L.idx_s, L.tab_s, A, E, a.C, a.hist, a.slot_idx, a.miss_list, a.miss_count, a.slot_count,
@@ -335,7 +435,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
     } else if (a.hist) {
         block_histogram(idx, A, E, a.hist, L.hist_s);
     }
-    if (tid == 0) atomicExch(a.ticket, 0u);
+    if (tid == 0) *a.epoch = tag;
 }
 
 __global__ __launch_bounds__(kRouteThreads) void histogram_kernel(const int32_t *idx, int A, int E,
@@ -381,11 +481,27 @@ __global__ __launch_bounds__(kRouteThreads) void resolve_kernel(const int32_t *i
                perm, pos, active_slots, n_active, L.hist_s, L.cnt_s, L.off_s, L.scan_s, L.sidx_s);
 }
 
-__global__ void clear_ctrl_kernel(unsigned *ctrl)
+__global__ void clear_ctrl_kernel(unsigned *ws, int words)
 {
-    if (threadIdx.x < kCtrlBytes / 4) ctrl[threadIdx.x] = 0u;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x) ws[i] = 0u;
 }
 
+}  // namespace
+
+namespace {
+int route_num_cus()
+{
+    static int n_cus = 0;
+    if (n_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            n_cus = n;
+        else
+            n_cus = 256;
+    }
+    return n_cus;
+}
 }  // namespace
 
 hipError_t launch_route(const RouteArgs &a, hipStream_t s)
@@ -402,7 +518,9 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t s)
         attr_done = true;
     }
     prof_begin(0, s);
-    hipLaunchKernelGGL(route_kernel, dim3(a.E), dim3(kRouteThreads), lds, s, a);
+    int grid = route_num_cus();
+    if (grid > a.T * a.E) grid = a.T * a.E;
+    hipLaunchKernelGGL(route_kernel, dim3(grid), dim3(kRouteThreads), lds, s, a);
     prof_end(0, s);
     return hipGetLastError();
 }
@@ -448,9 +566,11 @@ hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_
     return hipGetLastError();
 }
 
-hipError_t launch_clear_ctrl(void *ctrl, hipStream_t s)
+hipError_t launch_clear_ctrl(void *workspace, size_t bytes, hipStream_t s)
 {
-    hipLaunchKernelGGL(clear_ctrl_kernel, dim3(1), dim3(64), 0, s, (unsigned *)ctrl);
+    const size_t full = (size_t)kCtrlBytes + (size_t)kTagEntries * 8;
+    const int words = (int)((bytes >= full ? full : (size_t)kCtrlBytes) / 4);
+    hipLaunchKernelGGL(clear_ctrl_kernel, dim3(words > 4096 ? 64 : 1), dim3(256), 0, s, (unsigned *)workspace, words);
     return hipGetLastError();
 }
 

@@ -60,6 +60,7 @@ def run_layer(d: DeviceLayer, buf: B.LayerBuffers | None = None, out_bf16=False,
                        d.sh_gate, d.sh_up, d.sh_down, buf.topk_idx, buf.topk_w, buf.hist, buf.slot_idx,
                        buf.miss_list, buf.miss_count, buf.out, out_bf16, accumulate, buf.workspace)
     torch.cuda.synchronize()
+    B.moe_workspace_status(buf.workspace)   # raises if a bounded wait inside a kernel ran out
     return buf
 
 

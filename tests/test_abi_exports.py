@@ -27,7 +27,8 @@ def lib():
 def test_header_symbols_are_exported(lib):
     syms = declared_symbols()
     assert {"moe_route_topk", "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn",
-            "moe_verify_layer", "moe_workspace_bytes", "moe_workspace_init", "moe_status_string"} <= set(syms)
+            "moe_verify_layer", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status",
+            "moe_status_string"} <= set(syms)
     for s in syms:
         assert hasattr(lib, s), s
 
@@ -45,9 +46,12 @@ def test_workspace_bytes_and_status_strings(lib):
     assert lib.moe_workspace_bytes(ctypes.byref(sh), ctypes.byref(n)) == 0
     # at least the activations and per-assignment outputs: A*F*2 + A*H*4 (+ the shared experts' rows)
     assert n.value >= 54 * 1408 * 2 + 54 * 2048 * 4 + 2 * 9 * (1408 * 2 + 2048 * 4)
-    big = Shape(128, 2048, 64, 6, 1408, 48, 0, 0)      # large batch: per-slice partial sums
+    big = Shape(128, 2048, 64, 6, 1408, 48, 0, 0)      # large batch, narrow matrices: same layout
     assert lib.moe_workspace_bytes(ctypes.byref(big), ctypes.byref(n)) == 0
-    assert n.value >= 11 * 768 * 2048 * 4
+    assert n.value >= 768 * 1408 * 2 + 768 * 2048 * 4
+    wide = Shape(64, 4096, 8, 2, 14336, 8, 0, 0)       # large batch, wide matrices: per-slice partial sums
+    assert lib.moe_workspace_bytes(ctypes.byref(wide), ctypes.byref(n)) == 0
+    assert n.value >= 112 * 128 * 4096 * 4
     assert lib.moe_workspace_bytes(None, ctypes.byref(n)) == -1
     bad = Shape(9, 2048, 64, 65, 1408, 32, 0, 0)       # k > E
     assert lib.moe_workspace_bytes(ctypes.byref(bad), ctypes.byref(n)) == -2

@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the gate/up stream kernel from rocprofv3 counters (FETCH_SIZE scaled by
 # 2.000 from a 1 GiB copy, plus WRITE_SIZE), mean over the dispatches of the default workload; the
 # two --pmc runs and the calibration are recorded in profiles/stream_kernels_cfg2.txt.
-MEASURED_TRAFFIC_BYTES = {"cfg2": int((222751.6 + 148.5) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"cfg2": int((222761.0 + 148.5) * 1024)}
 
 
 def parse_args():
@@ -137,16 +137,21 @@ def main():
         step(i)
     torch.cuda.synchronize()
     B.moe_profile_enable(False)
+    raw = {kind: B.moe_profile_read(kind) for kind in range(B.KERNEL_KINDS)}
+    # An event pair with nothing between its two records still spans a few microseconds (the queue
+    # going from one packet to the next).  That interval is measured here, live, and taken off every
+    # bracketed kernel's average; both figures are reported.
+    ev_us = B.moe_profile_event_overhead(512) * 1e3
     kernels = {}
-    for kind in range(B.KERNEL_KINDS):
-        ms, n = B.moe_profile_read(kind)
+    for kind, (ms, n) in raw.items():
         if n:
-            kernels[B.moe_profile_kernel_name(kind)] = {"launches": n, "avg_us": ms * 1e3 / n}
+            kernels[B.moe_profile_kernel_name(kind)] = {"launches": n, "avg_us": round(ms * 1e3 / n - ev_us, 2),
+                                                        "avg_us_event_pair": round(ms * 1e3 / n, 2)}
     # dominant kernel: the gate/up stream (2/3 of the expert-weight bytes); when the batch is large
     # enough for the fused kernel it carries gate, up and down (all of them)
-    ffn_ms, ffn_n = B.moe_profile_read(B.KERNEL_FFN)
-    down_ms, down_n = B.moe_profile_read(B.KERNEL_DOWN)
-    ffn_avg_s = ffn_ms * 1e-3 / ffn_n
+    ffn_ms, ffn_n = raw[B.KERNEL_FFN]
+    down_ms, down_n = raw[B.KERNEL_DOWN]
+    ffn_avg_s = ffn_ms * 1e-3 / ffn_n - ev_us * 1e-6
     share = 2.0 / 3.0 if down_n else 1.0
     bytes_per_launch = share * bytes_total / args.steps
     achieved = bytes_per_launch / ffn_avg_s / 1e9
@@ -154,10 +159,10 @@ def main():
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if not args.copies else None,
-                "avg_kernel_us": round(ffn_avg_s * 1e6, 2),
+                "avg_kernel_us": round(ffn_avg_s * 1e6, 2), "event_pair_overhead_us": round(ev_us, 2),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch), "kernels": kernels}
     if down_n:
-        d_s = down_ms * 1e-3 / down_n
+        d_s = down_ms * 1e-3 / down_n - ev_us * 1e-6
         roofline["down_kernel"] = {"achieved": round((bytes_total / args.steps / 3.0) / d_s / 1e9, 1),
                                    "avg_kernel_us": round(d_s * 1e6, 2)}
 

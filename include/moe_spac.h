@@ -23,9 +23,16 @@
  *     slots, A = T*k assignments (flat id a = t*k + j).
  *   - Return value: MOE_OK, or a negative code; on a negative code nothing
  *     was launched.  No exceptions, no abort, nothing printed.
- *   - Supported sizes: 1 <= k <= min(E, 64); E <= 512; C <= 1024; H and F
- *     multiples of 32; H <= 4992; bf16 tensors and `out` 16-byte aligned.
- *   - Two calls that share a workspace must not overlap in time.
+ *   - Supported sizes: 1 <= k <= min(E, 64); E <= 512; T*E <= 65536;
+ *     C <= 1024; H and F multiples of 32; H <= 4992; bf16 tensors and `out`
+ *     16-byte aligned.
+ *   - Two calls that share a workspace must not overlap in time.  A
+ *     workspace holds state between calls (a call counter and a region whose
+ *     entries are stamped with it): initialise it with moe_workspace_init
+ *     over its full size, and again after anything else wrote into it.
+ *   - The slot table maps distinct resident experts to distinct slots (it is
+ *     a cache directory); with two experts on one slot the per-slot lists are
+ *     unspecified (every access still stays in bounds).
  */
 #ifndef MOE_SPAC_H
 #define MOE_SPAC_H
@@ -60,17 +67,16 @@ const char *moe_status_string(int status);
  * (an upper bound for the single-step entry points).  shape: host pointer. */
 int moe_workspace_bytes(const moe_shape_t *shape, size_t *bytes_out);
 
-/* Clears the control block at the start of a freshly allocated workspace.
- * Call once per workspace before its first use; every entry point leaves the
- * control block cleared again when its kernels finish. */
+/* Clears the control block and the stamped-entry region at the start of a
+ * freshly allocated workspace (the first 256 B + 512 KB, as far as
+ * workspace_bytes reaches).  Call once per workspace before its first use. */
 int moe_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Synchronous health check: waits for `stream`, then reads the control block.
- * Kernels that wait for one another inside a launch (the layer's routing
- * results are handed from the first workgroups to all others through device
- * memory) poll a bounded number of times and, should that bound ever run out,
- * set a flag in the control block and finish with unspecified results instead
- * of waiting for ever.  Returns MOE_OK when no such flag is set,
+ * Inside the routing launch one workgroup waits for the logits that the others
+ * write to device memory; it polls a bounded number of times and, should that
+ * bound ever run out, sets a flag in the control block and finishes with
+ * unspecified results instead of waiting for ever.  Returns MOE_OK when no such flag is set,
  * MOE_ERR_LAUNCH when one is (the flag is cleared, the workspace stays usable)
  * or when the copy fails.  workspace: device pointer. */
 int moe_workspace_status(void *workspace, size_t workspace_bytes, void *stream);
@@ -139,6 +145,12 @@ enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2 /* gate/up
 int moe_profile_enable(int on);
 int moe_profile_read(int kind, double *total_ms, int *launches);
 const char *moe_profile_kernel_name(int kind);
+/* What a pair of events costs by itself: records `pairs` (1..8192) pairs on
+ * `stream` with nothing in between, waits for the stream and returns the mean
+ * interval in *avg_ms (host).  A bracketed kernel's record contains about this
+ * much time that is not the kernel's.  Call after moe_profile_enable(1) and
+ * after reading the records you need (it reuses the pairs of kind 0). */
+int moe_profile_event_overhead(void *stream, int pairs, double *avg_ms);
 
 #ifdef __cplusplus
 }

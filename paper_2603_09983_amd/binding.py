@@ -50,11 +50,13 @@ _lib.moe_profile_enable.argtypes = [_i]
 _lib.moe_profile_enable.restype = _i
 _lib.moe_profile_read.argtypes = [_i, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i)]
 _lib.moe_profile_read.restype = _i
+_lib.moe_profile_event_overhead.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_double)]
+_lib.moe_profile_event_overhead.restype = _i
 _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
 KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_KINDS = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ("moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
+EXPORTS = ("moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
 
 
@@ -97,6 +99,13 @@ def moe_profile_read(kind: int):
     ms, n = ctypes.c_double(0.0), _i(0)
     _check(_lib.moe_profile_read(kind, ctypes.byref(ms), ctypes.byref(n)), "moe_profile_read", True)
     return float(ms.value), int(n.value)
+
+
+def moe_profile_event_overhead(pairs: int = 256, stream=None) -> float:
+    """Mean interval (ms) of an event pair with nothing between its two records."""
+    ms = ctypes.c_double(0.0)
+    _check(_lib.moe_profile_event_overhead(_stream(stream), pairs, ctypes.byref(ms)), "moe_profile_event_overhead", True)
+    return float(ms.value)
 
 
 def moe_profile_kernel_name(kind: int) -> str:

@@ -43,6 +43,16 @@ int check_ffn_shape(int T, int H, int F, int k, int C)
 
 }  // namespace
 
+// One kernel launch, bracketed by a pair of events on its stream while the measurement aid is on.
+hipError_t moe::launch_timed(const void *fn, dim3 grid, dim3 block, void **params, size_t lds, hipStream_t s,
+                             int kind)
+{
+    prof_begin(kind, s);
+    hipError_t e = hipLaunchKernel(fn, grid, block, params, lds, s);
+    prof_end(kind, s);
+    return e;
+}
+
 void moe::prof_begin(int kind, hipStream_t s)
 {
     if (g_prof.on && g_prof.used[kind] < g_prof.created) (void)hipEventRecord(g_prof.ev[kind][g_prof.used[kind]][0], s);
@@ -84,6 +94,27 @@ extern "C" int moe_profile_read(int kind, double *total_ms, int *launches)
     }
     *total_ms = sum;
     *launches = g_prof.used[kind];
+    return MOE_OK;
+}
+
+extern "C" int moe_profile_event_overhead(void *stream, int pairs, double *avg_ms)
+{
+    if (!avg_ms) return MOE_ERR_NULL;
+    if (pairs < 1 || pairs > kProfMax || g_prof.created == 0) return MOE_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    // the pairs of kind 0 serve as scratch: nothing between the two records of a pair
+    for (int i = 0; i < pairs; ++i) {
+        if (hipEventRecord(g_prof.ev[0][i][0], s) != hipSuccess) return MOE_ERR_LAUNCH;
+        if (hipEventRecord(g_prof.ev[0][i][1], s) != hipSuccess) return MOE_ERR_LAUNCH;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) return MOE_ERR_LAUNCH;
+    double sum = 0.0;
+    for (int i = 0; i < pairs; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_prof.ev[0][i][0], g_prof.ev[0][i][1]) != hipSuccess) return MOE_ERR_LAUNCH;
+        sum += ms;
+    }
+    *avg_ms = sum / pairs;
     return MOE_OK;
 }
 

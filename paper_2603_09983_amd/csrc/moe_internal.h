@@ -154,6 +154,8 @@ hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
 // clears the control block and, if `bytes` reaches that far, the tagged-logit region behind it
 hipError_t launch_clear_ctrl(void *workspace, size_t bytes, hipStream_t s);
+// a launch that the measurement aid times by the dispatch's own start and end stamps when enabled
+hipError_t launch_timed(const void *fn, dim3 grid, dim3 block, void **params, size_t lds, hipStream_t s, int kind);
 // event bracketing for the measurement aid (no-ops unless enabled)
 void prof_begin(int kind, hipStream_t s);
 void prof_end(int kind, hipStream_t s);

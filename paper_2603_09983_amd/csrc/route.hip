@@ -517,12 +517,12 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    prof_begin(0, s);
     int grid = route_num_cus();
     if (grid > a.T * a.E) grid = a.T * a.E;
-    hipLaunchKernelGGL(route_kernel, dim3(grid), dim3(kRouteThreads), lds, s, a);
-    prof_end(0, s);
-    return hipGetLastError();
+    RouteArgs args = a;
+    void *params[] = {&args};
+    hipError_t e = launch_timed((const void *)route_kernel, dim3(grid), dim3(kRouteThreads), params, lds, s, 0);
+    return e != hipSuccess ? e : hipGetLastError();
 }
 
 hipError_t launch_histogram(const int32_t *topk_idx, int A, int E, int32_t *hist, hipStream_t s)

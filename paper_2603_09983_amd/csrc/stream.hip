@@ -504,9 +504,7 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s)
     int tile_i = (int)tile;
     StreamArgs args = a;
     void *params[] = {&args, &tile_i};
-    prof_begin(gateup ? 2 : 4, s);
-    hipError_t le = hipLaunchKernel(fn, dim3(grid), dim3(kThreads), params, lds, s);
-    prof_end(gateup ? 2 : 4, s);
+    hipError_t le = launch_timed(fn, dim3(grid), dim3(kThreads), params, lds, s, gateup ? 2 : 4);
     if (le != hipSuccess) return le;
     return hipGetLastError();
 }
@@ -514,10 +512,10 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s)
 hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s)
 {
     dim3 grid((a.H / 4 + 127) / 128, a.T);
-    prof_begin(3, s);
-    hipLaunchKernelGGL(combine_rows_kernel, grid, dim3(128), 0, s, a, o, o_sh);
-    prof_end(3, s);
-    return hipGetLastError();
+    CombineArgs args = a;
+    void *params[] = {&args, &o, &o_sh};
+    hipError_t e = launch_timed((const void *)combine_rows_kernel, grid, dim3(128), params, 0, s, 3);
+    return e != hipSuccess ? e : hipGetLastError();
 }
 
 }  // namespace moe

@@ -121,7 +121,7 @@ int moe_grouped_ffn(const void *hidden, const float *topk_w, const int32_t *slot
                     const void *w_up, const void *w_down, int T, int H, int F, int k, int C, void *out,
                     int out_bf16, int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Steps 1-4 for one verification batch in three launches on `stream`.
+/* Steps 1-4 for one verification batch in four launches on `stream`.
  * shape: host pointer.  shared_gate/up [n_shared,F_shared,H] and shared_down
  * [n_shared,H,F_shared] bf16 (NULL when n_shared = 0) are added with weight 1
  * for every token.  All step outputs are produced: topk_idx, topk_w [T,k];

@@ -127,6 +127,24 @@ class Oracle:
         self._lib.oracle_shared_ffn_add(_p(hidden), _p(sh_gate), _p(sh_up), _p(sh_down), T, H, Fs, n, _p(y))
         return y
 
+    def utility_step(self, f, f_prev, s, th_up, th_dn, K: int, lam_num: int, lam_den: int):
+        """One step of Alg. 1 for the N experts of one layer; returns the new (f_prev, s, th_up, th_dn)."""
+        f = _c(f, np.int32)
+        f_prev, s = np.array(f_prev, dtype=np.int32), np.array(s, dtype=np.int32)
+        th_up, th_dn = np.array(th_up, dtype=np.int32), np.array(th_dn, dtype=np.int32)
+        N = f.shape[0]
+        assert f_prev.shape == s.shape == th_up.shape == th_dn.shape == (N,)
+        self._lib.oracle_utility_step(_p(f), _p(f_prev), _p(s), _p(th_up), _p(th_dn), N, K, lam_num, lam_den)
+        return f_prev, s, th_up, th_dn
+
+    def prefetch_counts(self, s, slot_table, K: int) -> np.ndarray:
+        """n(tau), tau = 0..K: experts with utility >= tau that hold no cache slot."""
+        s = _c(s, np.int32)
+        slot_table = _c(slot_table, np.int32)
+        n_tau = np.empty(K + 1, dtype=np.int32)
+        self._lib.oracle_prefetch_counts(_p(s), _p(slot_table), s.shape[0], K, _p(n_tau))
+        return n_tau
+
     def verify_layer(self, hidden, router_w, router_bias, slot_table, w_gate, w_up, w_down, k: int,
                      sh_gate=None, sh_up=None, sh_down=None) -> LayerResult:
         hidden = _c(hidden, np.uint16)

@@ -24,6 +24,14 @@
  * host's share completes); shared experts are added with weight 1 for every
  * token and are outside routing, histogram and miss list.
  *
+ * Also here, for the consumer of the activation frequencies: one step of the
+ * Speculative Utility Estimator (Sec. 3.2, Alg. 1 and the utility-transition
+ * equation) and the prefetch count n(tau) of the balancer's notation table
+ * (Sec. 3.3).  Readings: f_{i,0} = 0; the forgetting factor is a rational
+ * lam_num/lam_den and the floor is taken in exact integer arithmetic; the
+ * upward test comes first, so a boundary of 0 lets a fluctuation of 0 raise
+ * the utility, as the listing's ">=" says.
+ *
  * Pinned by tests/test_oracle_pins.py (brute-force dense evaluation in
  * numpy, textbook SwiGLU through torch's own linear/silu, closed forms,
  * the worked example of App. C.1, invariants).  No function here is
@@ -198,4 +206,47 @@ void oracle_verify_layer(const uint16_t *hidden, const float *router_w, const fl
     oracle_routed_ffn(hidden, topk_idx, gate, slot_table, w_gate, w_up, w_down, T, H, F, k, y);
     if (n_shared > 0)
         oracle_shared_ffn_add(hidden, sh_gate, sh_up, sh_down, T, H, Fs, n_shared, y);
+}
+
+/* ---------------------------------------------------------------------------
+ * Speculative Utility Estimator, one inference step t for the N experts of one
+ * layer (Sec. 3.2, Alg. 1).  State, updated in place: utility s_i in [0,K],
+ * boundaries th_up_i, th_dn_i, and the previous frequencies f_prev_i.
+ *   fluctuation          d = f_i - f_prev_i
+ *   inertial transition  d >= th_up: s <- min(K, s+1);  else -d >= th_dn: s <- max(0, s-1)
+ *   boundary calibration d > 0: th_up <- floor((1-lam) th_up + lam d)
+ *                        d < 0: th_dn <- floor((1-lam) th_dn + lam |d|)
+ * The transition uses the boundaries of step t; calibration produces those of
+ * step t+1.  lam = lam_num / lam_den, floor by integer division of
+ * non-negative integers.
+ * ------------------------------------------------------------------------- */
+void oracle_utility_step(const int32_t *f, int32_t *f_prev, int32_t *s, int32_t *th_up, int32_t *th_dn,
+                         int N, int K, int lam_num, int lam_den)
+{
+    for (int i = 0; i < N; ++i) {
+        int64_t d = (int64_t)f[i] - (int64_t)f_prev[i];
+        if (d >= (int64_t)th_up[i]) {
+            s[i] = s[i] + 1 < K ? s[i] + 1 : K;
+        } else if (-d >= (int64_t)th_dn[i]) {
+            s[i] = s[i] - 1 > 0 ? s[i] - 1 : 0;
+        }
+        if (d > 0) {
+            th_up[i] = (int32_t)(((int64_t)(lam_den - lam_num) * th_up[i] + (int64_t)lam_num * d) / lam_den);
+        } else if (d < 0) {
+            th_dn[i] = (int32_t)(((int64_t)(lam_den - lam_num) * th_dn[i] + (int64_t)lam_num * (-d)) / lam_den);
+        }
+        f_prev[i] = f[i];
+    }
+}
+
+/* n(tau) of the balancer's notation (Sec. 3.3): the number of hot experts (s_i >= tau) that are not
+ * on the GPU (slot_table[i] < 0), for tau = 0..K. */
+void oracle_prefetch_counts(const int32_t *s, const int32_t *slot_table, int N, int K, int32_t *n_tau)
+{
+    for (int tau = 0; tau <= K; ++tau) {
+        int32_t n = 0;
+        for (int i = 0; i < N; ++i)
+            if (s[i] >= tau && slot_table[i] < 0) n += 1;
+        n_tau[tau] = n;
+    }
 }

@@ -387,3 +387,120 @@ def pin_layer_composition(O):
 
 
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]
+
+
+# ---------------------------------------------------------------------------
+# Speculative Utility Estimator (Sec. 3.2, Alg. 1) and n(tau) (Sec. 3.3)
+# ---------------------------------------------------------------------------
+def _est_init(N, gamma):
+    z = np.zeros(N, dtype=np.int32)
+    th = np.full(N, gamma // 2, dtype=np.int32)
+    return z.copy(), z.copy(), th.copy(), th.copy()   # f_prev, s, th_up, th_dn
+
+
+def pin_est_hand_trace(O):
+    """The pencil trace in tests/golden/utility_trace_alg1.txt (gamma = 4, lambda = 1/2)."""
+    import os
+    from conftest import GOLDEN
+    with open(os.path.join(GOLDEN, "utility_trace_alg1.txt")) as fh:
+        rows = [l.split("#")[0].split() for l in fh]
+    rows = [r for r in rows if r]
+    assert len(rows) == 14
+    state = {}
+    for name, K, f, s1, up1, dn1 in rows:
+        if name not in state:
+            state[name] = _est_init(1, 4)
+        fp, s, up, dn = state[name]
+        fp, s, up, dn = O.utility_step(np.array([int(f)], dtype=np.int32), fp, s, up, dn, int(K), 1, 2)
+        state[name] = (fp, s, up, dn)
+        assert (int(s[0]), int(up[0]), int(dn[0])) == (int(s1), int(up1), int(dn1)), (name, f, s, up, dn)
+        assert int(fp[0]) == int(f)
+
+
+def pin_est_closed_forms(O):
+    """lambda = 0 freezes the boundaries, which gives closed forms: a constant frequency never moves
+    the utility; a ramp of slope >= boundary reaches min(K, t); a square wave of height >= boundary
+    alternates 1, 0; and a slope one below the boundary never moves it."""
+    N, gamma, K = 4, 6, 5
+    th = gamma // 2
+    fp, s, up, dn = _est_init(N, gamma)
+    for t in range(1, 12):
+        f = np.array([7, th * t, (t % 2) * th, (th - 1) * t], dtype=np.int32)
+        fp, s, up, dn = O.utility_step(f, fp, s, up, dn, K, 0, 10)
+        want0 = 1 if 7 >= th else 0              # the jump 0 -> 7 at t = 1 counts once, then d = 0
+        assert s[0] == want0 and s[1] == min(K, t) and s[2] == t % 2 and s[3] == 0, (t, s)
+        assert np.all(up == th) and np.all(dn == th)
+    # lambda = 1: the boundary becomes the last fluctuation of its sign
+    fp, s, up, dn = _est_init(1, 6)
+    for f, eu, ed in ((5, 5, 3), (7, 2, 3), (1, 2, 6), (1, 2, 6), (0, 2, 1)):
+        fp, s, up, dn = O.utility_step(np.array([f], dtype=np.int32), fp, s, up, dn, 4, 1, 1)
+        assert (up[0], dn[0]) == (eu, ed), (f, up, dn)
+
+
+def pin_est_zero_boundary_and_floor(O):
+    """gamma = 1 starts the boundaries at 0: the upward test d >= 0 then holds for d = 0 too, so a
+    constant frequency climbs to K (the listing's '>=', upward test first).  And the floor is exact:
+    boundary 10 with fluctuation +10 at lambda = 1/10 stays 10; 3 with +7 gives floor(3.4) = 3; 1
+    with -1 stays floor(0.9 + 0.1) = 1 (never reaches 0 through calibration)."""
+    fp, s, up, dn = _est_init(1, 1)
+    for t in range(1, 6):
+        fp, s, up, dn = O.utility_step(np.array([0], dtype=np.int32), fp, s, up, dn, 3, 1, 10)
+        assert s[0] == min(3, t) and up[0] == 0 and dn[0] == 0
+    for th0, d, want in ((10, 10, 10), (3, 7, 3), (9, 19, 10), (1, 1, 1), (29, 1, 26)):
+        fp = np.array([100], dtype=np.int32)
+        s = np.array([2], dtype=np.int32)
+        up = np.array([th0], dtype=np.int32)
+        dn = np.array([th0], dtype=np.int32)
+        _, _, up2, dn2 = O.utility_step(np.array([100 + d], dtype=np.int32), fp, s, up, dn, 4, 1, 10)
+        assert up2[0] == want and dn2[0] == th0, (th0, d, up2, dn2)
+        _, _, up3, dn3 = O.utility_step(np.array([100 - d], dtype=np.int32), fp, s, up, dn, 4, 1, 10)
+        assert dn3[0] == want and up3[0] == th0, (th0, d, up3, dn3)
+
+
+def pin_est_invariants(O):
+    """On random frequency sequences: 0 <= s <= K and |s_{t+1} - s_t| <= 1; the boundary on the side
+    of the fluctuation lands between its old value and |d| (a convex combination, floored), the
+    other one is untouched; d = 0 with positive boundaries changes nothing; experts do not
+    interact (running them one at a time gives the same states); f_prev follows f."""
+    rng = np.random.default_rng(7)
+    N, gamma, K = 16, 8, 4
+    fp, s, up, dn = _est_init(N, gamma)
+    solo = [_est_init(1, gamma) for _ in range(N)]
+    for t in range(60):
+        f = rng.integers(0, gamma + 2, size=N).astype(np.int32)
+        if t % 7 == 3:
+            f = fp.copy()
+        d = f.astype(np.int64) - fp
+        fp2, s2, up2, dn2 = O.utility_step(f, fp, s, up, dn, K, 1, 10)
+        assert np.all(s2 >= 0) and np.all(s2 <= K) and np.all(np.abs(s2 - s) <= 1)
+        pos, neg, zero = d > 0, d < 0, d == 0
+        assert np.all(up2[~pos] == up[~pos]) and np.all(dn2[~neg] == dn[~neg])
+        assert np.all(up2[pos] >= np.minimum(up[pos], d[pos])) and np.all(up2[pos] <= np.maximum(up[pos], d[pos]))
+        assert np.all(dn2[neg] >= np.minimum(dn[neg], -d[neg])) and np.all(dn2[neg] <= np.maximum(dn[neg], -d[neg]))
+        still = zero & (up > 0)
+        assert np.all(s2[still] == s[still])
+        assert np.all(s2[d >= up] == np.minimum(K, s[d >= up] + 1))
+        assert np.array_equal(fp2, f)
+        for i in range(N):
+            solo[i] = O.utility_step(f[i:i + 1], *solo[i], K, 1, 10)
+            assert (solo[i][1][0], solo[i][2][0], solo[i][3][0]) == (s2[i], up2[i], dn2[i])
+        fp, s, up, dn = fp2, s2, up2, dn2
+
+
+def pin_prefetch_counts(O):
+    """n(tau) by brute force with numpy, its monotonicity in tau, and the worked example of
+    App. C.1 read as utilities: resident set {3}, so every other hot expert must be fetched."""
+    rng = np.random.default_rng(3)
+    for N, K in ((8, 4), (64, 4), (130, 7)):
+        s = rng.integers(0, K + 1, size=N).astype(np.int32)
+        tab = np.where(rng.random(N) < 0.4, np.arange(N), -1).astype(np.int32)
+        n = O.prefetch_counts(s, tab, K)
+        want = np.array([int(np.sum((s >= tau) & (tab < 0))) for tau in range(K + 1)])
+        assert np.array_equal(n, want)
+        assert n[0] == int(np.sum(tab < 0)) and np.all(np.diff(n) <= 0)
+    s = np.array([1, 0, 1, 2], dtype=np.int32)
+    tab = np.array([-1, -1, -1, 0], dtype=np.int32)
+    assert np.array_equal(O.prefetch_counts(s, tab, 2), [3, 2, 0])
+
+
+ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

@@ -26,6 +26,18 @@ MUTANTS = {
     "shared_weight_half": ("1.0, y + (size_t)t * H);", "0.5, y + (size_t)t * H);"),
     "weights_by_slot": ("size_t off = (size_t)e * F * H;", "size_t off = (size_t)slot_table[e] * F * H;"),
     "gate_not_normalised": ("- smax) / den;", "- smax);"),
+    "est_downward_test_first": ("if (d >= (int64_t)th_up[i]) {\n            s[i] = s[i] + 1 < K ? s[i] + 1 : K;\n        } else if (-d >= (int64_t)th_dn[i]) {\n            s[i] = s[i] - 1 > 0 ? s[i] - 1 : 0;\n        }",
+                                "if (-d >= (int64_t)th_dn[i]) {\n            s[i] = s[i] - 1 > 0 ? s[i] - 1 : 0;\n        } else if (d >= (int64_t)th_up[i]) {\n            s[i] = s[i] + 1 < K ? s[i] + 1 : K;\n        }"),
+    "est_strict_upward": ("if (d >= (int64_t)th_up[i]) {", "if (d > (int64_t)th_up[i]) {"),
+    "est_no_upper_clamp": ("s[i] = s[i] + 1 < K ? s[i] + 1 : K;", "s[i] = s[i] + 1;"),
+    "est_no_lower_clamp": ("s[i] = s[i] - 1 > 0 ? s[i] - 1 : 0;", "s[i] = s[i] - 1;"),
+    "est_calibrates_wrong_side": ("th_dn[i] = (int32_t)(((int64_t)(lam_den - lam_num) * th_dn[i]", "th_up[i] = (int32_t)(((int64_t)(lam_den - lam_num) * th_dn[i]"),
+    "est_floor_becomes_round": ("+ (int64_t)lam_num * d) / lam_den);", "+ (int64_t)lam_num * d + lam_den / 2) / lam_den);"),
+    "est_lambda_swapped": ("(int64_t)(lam_den - lam_num) * th_up[i] + (int64_t)lam_num * d)", "(int64_t)lam_num * th_up[i] + (int64_t)(lam_den - lam_num) * d)"),
+    "est_f_prev_not_kept": ("        f_prev[i] = f[i];\n", ""),
+    "est_signed_fluctuation_in_dn": ("(int64_t)lam_num * (-d)) / lam_den);", "(int64_t)lam_num * d) / lam_den);"),
+    "prefetch_counts_residents": ("if (s[i] >= tau && slot_table[i] < 0) n += 1;", "if (s[i] >= tau && slot_table[i] >= 0) n += 1;"),
+    "prefetch_strict_threshold": ("if (s[i] >= tau && slot_table[i] < 0) n += 1;", "if (s[i] > tau && slot_table[i] < 0) n += 1;"),
     "descending_order_lost": ("topk_idx[(size_t)t * k + j] = best;", "topk_idx[(size_t)t * k + (k - 1 - j)] = best;"),
 }
 

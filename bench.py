@@ -41,6 +41,7 @@ def parse_args():
                    help="cfg2 | cfg3 | cfg4_c8 | cfg4_c4 | cfg5_T<n> (24-layer sweep at T=n)")
     p.add_argument("--copies", type=int, default=0, help="distinct layers to rotate over (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-estimator", action="store_true", help="skip the utility-estimator measurement")
     p.add_argument("--cpu-seconds", type=float, default=10.0)
     p.add_argument("--calibration-copy", action="store_true",
                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling "
@@ -166,6 +167,53 @@ def main():
         roofline["down_kernel"] = {"achieved": round((bytes_total / args.steps / 3.0) / d_s / 1e9, 1),
                                    "avg_kernel_us": round(d_s * 1e6, 2)}
 
+    # NEXT row: the Speculative Utility Estimator consuming the histograms of 24 layers per inference
+    # step (one launch for all layers); frequencies are synthetic histograms of T*k assignments.
+    est = None
+    if not args.no_estimator:
+        L_est, K_est, gamma = 24, 4, shape.T - 1
+        rng = np.random.default_rng(0)
+        fr = np.zeros((8, L_est, shape.E), dtype=np.int32)
+        for t in range(8):
+            for l in range(L_est):
+                for _ in range(shape.T):
+                    fr[t, l, rng.choice(shape.E, size=shape.k, replace=False)] += 1
+        d_fr = torch.from_numpy(fr).cuda()
+        i32 = dict(dtype=torch.int32, device="cuda")
+        st = [torch.zeros((L_est, shape.E), **i32) for _ in range(4)]
+        d_tab = torch.from_numpy(np.stack([layers[i % len(layers)].slot_table for i in range(L_est)])).cuda()
+        d_n = torch.zeros((L_est, K_est + 1), **i32)
+        B.moe_utility_init(*st, L_est, shape.E, gamma)
+        for t in range(16):
+            B.moe_utility_update(d_fr[t % 8], *st, d_tab, d_n, L_est, shape.E, K_est, 1, 10)
+        torch.cuda.synchronize()
+        B.moe_profile_enable(True)
+        n_est = 200
+        for t in range(n_est):
+            B.moe_utility_update(d_fr[t % 8], *st, d_tab, d_n, L_est, shape.E, K_est, 1, 10)
+        torch.cuda.synchronize()
+        B.moe_profile_enable(False)
+        ms, n = B.moe_profile_read(B.KERNEL_ESTIMATOR)
+        est_us = ms * 1e3 / n - ev_us
+        est_bytes = L_est * shape.E * 4 * (6 + 4) + L_est * (K_est + 1) * 4   # 6 words read, 4 written per expert
+        est = {"kernel": "utility_update_kernel", "layers": L_est, "experts": shape.E, "K": K_est,
+               "lambda": "1/10", "avg_us": round(est_us, 2), "avg_us_event_pair": round(ms * 1e3 / n, 2),
+               "bound": "latency", "algorithmic_bytes": est_bytes,
+               "note": "one launch advances all layers by one inference step and counts n(tau)"}
+        if not args.no_cpu_baseline:
+            import oracle
+            z = np.zeros(shape.E, dtype=np.int32)
+            th = np.full(shape.E, gamma // 2, dtype=np.int32)
+            o_st = [(z.copy(), z.copy(), th.copy(), th.copy()) for _ in range(L_est)]
+            tabs = d_tab.cpu().numpy()
+            t_c0 = time.perf_counter()
+            reps = 50
+            for t in range(reps):
+                for l in range(L_est):
+                    o_st[l] = oracle.utility_step(fr[t % 8, l], *o_st[l], K_est, 1, 10)
+                    oracle.prefetch_counts(o_st[l][1], tabs[l], K_est)
+            est["cpu_oracle_us"] = round((time.perf_counter() - t_c0) * 1e6 / reps, 1)
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -177,7 +225,7 @@ def main():
             oracle.layer_from_inputs(li)
             n += 1
             el = time.perf_counter() - t_cpu0
-            if el >= args.cpu_seconds or n >= 200:
+            if el >= args.cpu_seconds or n >= 5000:
                 break
         cpu_s = el / n
         cpu = {"value": round(layer_bytes[0] / cpu_s / 1e9, 3), "unit": "GB/s", "cores": threads,
@@ -193,7 +241,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic", "config": {"workload": desc, "layers": len(layers),
                                         "mean_weight_bytes_per_layer": int(np.mean(layer_bytes))},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "estimator": est,
     }
     print(json.dumps(out))
 

@@ -133,6 +133,34 @@ int moe_verify_layer(const moe_shape_t *shape, const void *hidden, const float *
                      int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, void *out, int out_bf16,
                      int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 
+/* NEXT STEP AFTER THE HISTOGRAM -- Sec. 3.2, Alg. 1 (Speculative Utility
+ * Estimator) and the utility-transition equation; n(tau) as in the notation
+ * table of Sec. 3.3.
+ *
+ * State per (layer, expert), int32, row-major [L,N], owned by the caller:
+ * utility s in [0,K], boundaries theta_up and theta_dn, previous frequencies
+ * f_prev.  moe_utility_init sets s = 0, f_prev = 0 (the reading taken for
+ * f_{i,0}) and both boundaries to floor(gamma/2).
+ *
+ * moe_utility_update advances all L layers by one inference step from the
+ * observed frequencies f [L,N] (for one layer: the `hist` output of step 2):
+ *   d = f - f_prev;
+ *   d >= theta_up: s <- min(K, s+1);  else -d >= theta_dn: s <- max(0, s-1);
+ *   d > 0: theta_up <- floor((1-lam) theta_up + lam d);
+ *   d < 0: theta_dn <- floor((1-lam) theta_dn + lam |d|);   f_prev <- f.
+ * The transition uses the boundaries as they were before this call.  lam =
+ * lam_num / lam_den (0 <= lam_num <= lam_den, e.g. 1/10); the floor is exact
+ * integer arithmetic.  0 <= K <= 64.
+ * Optional: slot_table [L,N] (expert -> slot or -1) and n_tau [L,K+1] out:
+ * n_tau[l,tau] = number of experts of layer l with s >= tau (after the
+ * update) that hold no slot, tau = 0..K.  Pass both or n_tau = NULL.
+ * One launch on `stream`; nothing is allocated. */
+int moe_utility_init(int32_t *f_prev, int32_t *s, int32_t *theta_up, int32_t *theta_dn, int L, int N, int gamma,
+                     void *stream);
+int moe_utility_update(const int32_t *f, int32_t *f_prev, int32_t *s, int32_t *theta_up, int32_t *theta_dn,
+                       const int32_t *slot_table, int32_t *n_tau, int L, int N, int K, int lam_num, int lam_den,
+                       void *stream);
+
 /* Measurement aid (host-side state only; not part of the layer's arithmetic).
  * While enabled, every kernel the library launches is bracketed by a pair of
  * HIP events recorded on the caller's stream.  kind: MOE_KERNEL_*.
@@ -141,7 +169,7 @@ int moe_verify_layer(const moe_shape_t *shape, const void *hidden, const float *
  * moe_profile_read sums hipEventElapsedTime over the records of one kind; the
  * caller must have synchronised the stream.  total_ms, launches: host. */
 enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2 /* gate/up (and down when fused) */,
-       MOE_KERNEL_COMBINE = 3, MOE_KERNEL_DOWN = 4, MOE_KERNEL_KINDS = 5 };
+       MOE_KERNEL_COMBINE = 3, MOE_KERNEL_DOWN = 4, MOE_KERNEL_ESTIMATOR = 5, MOE_KERNEL_KINDS = 6 };
 int moe_profile_enable(int on);
 int moe_profile_read(int kind, double *total_ms, int *launches);
 const char *moe_profile_kernel_name(int kind);

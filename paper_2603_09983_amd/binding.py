@@ -42,7 +42,9 @@ _lib.moe_expert_histogram.argtypes = [_vp, _i, _i, _i, _vp, _vp]
 _lib.moe_slot_resolve.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moe_grouped_ffn.argtypes = [_vp] * 6 + [_i] * 5 + [_vp, _i, _i, _vp, _sz, _vp]
 _lib.moe_verify_layer.argtypes = [ctypes.POINTER(MoeShape)] + [_vp] * 17 + [_i, _i, _vp, _sz, _vp]
-for _f in ("moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk", "moe_expert_histogram",
+_lib.moe_utility_init.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]
+_lib.moe_utility_update.argtypes = [_vp] * 7 + [_i] * 5 + [_vp]
+for _f in ("moe_utility_init", "moe_utility_update", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk", "moe_expert_histogram",
            "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer"):
     getattr(_lib, _f).restype = _i
 
@@ -54,9 +56,9 @@ _lib.moe_profile_event_overhead.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_dou
 _lib.moe_profile_event_overhead.restype = _i
 _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
-KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_KINDS = 0, 1, 2, 3, 4, 5
+KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6
 
-EXPORTS = ("moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
+EXPORTS = ("moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
 
 
@@ -179,6 +181,18 @@ def moe_verify_layer(shape: MoeShape, hidden, router_w, router_bias, slot_table,
                                int(accumulate), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                _stream(stream))
     return _check(rc, "moe_verify_layer", check)
+
+
+def moe_utility_init(f_prev, s, theta_up, theta_dn, L, N, gamma, stream=None, check=True) -> int:
+    return _check(_lib.moe_utility_init(_ptr(f_prev), _ptr(s), _ptr(theta_up), _ptr(theta_dn), L, N, gamma,
+                                        _stream(stream)), "moe_utility_init", check)
+
+
+def moe_utility_update(f, f_prev, s, theta_up, theta_dn, slot_table, n_tau, L, N, K, lam_num, lam_den,
+                       stream=None, check=True) -> int:
+    rc = _lib.moe_utility_update(_ptr(f), _ptr(f_prev), _ptr(s), _ptr(theta_up), _ptr(theta_dn),
+                                 _ptr(slot_table), _ptr(n_tau), L, N, K, lam_num, lam_den, _stream(stream))
+    return _check(rc, "moe_utility_update", check)
 
 
 # ---------------------------------------------------------------------------

@@ -126,6 +126,7 @@ extern "C" const char *moe_profile_kernel_name(int kind)
     case MOE_KERNEL_FFN: return "ffn_gate_up";
     case MOE_KERNEL_COMBINE: return "combine_kernel";
     case MOE_KERNEL_DOWN: return "ffn_down";
+    case MOE_KERNEL_ESTIMATOR: return "utility_update_kernel";
     default: return "?";
     }
 }

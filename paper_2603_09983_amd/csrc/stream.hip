@@ -81,6 +81,10 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     constexpr int RPI = GATEUP ? 8 : 16;    // output rows per item
     constexpr int OB = GATEUP ? 2 : 4;      // bytes per output element
     constexpr int kOutPerItem = RPI * 16;   // results of one item (rows x token columns)
+    // Gate/up kernel, batch within one pass: column n of the MFMA result is TOKEN n for every expert
+    // (the arithmetic is free), so the B operand never changes and no expert change stalls the
+    // stream; the expert's own tokens are picked out when the results are stored.
+    constexpr bool ALLTOK = GATEUP && MODE == 1;
 
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *tile_s = lds;
@@ -156,13 +160,13 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         cocol = rt * RPI * OB;
         if (sh) {
             cK = a.K_sh; c_rs = 2 * a.KP_sh; cnpan = a.K_sh / a.KP_sh;
-            cm = a.T; ckey = e; corow0 = e * a.T;
+            cm = a.T; ckey = ALLTOK ? 0 : e; corow0 = e * a.T;
             cbrow0 = GATEUP ? 0 : e * a.T;            // hidden[n] | act_sh[e][n]
         } else {
             const int c = active_s[e];
             cK = a.K; c_rs = 2 * a.KP; cnpan = a.K / a.KP;
-            cm = count_s[c]; ckey = a.n_shared + c; corow0 = offset_s[c];
-            cbrow0 = GATEUP ? -1 : corow0;            // hidden[perm/k] | act[row]
+            cm = count_s[c]; ckey = ALLTOK ? 0 : a.n_shared + c; corow0 = offset_s[c];
+            cbrow0 = ALLTOK ? 0 : GATEUP ? -1 : corow0;   // hidden[n] | hidden[token of list entry n] | act[row]
         }
     };
     auto cons_advance = [&]() {
@@ -237,7 +241,7 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         offset_s[i] = a.slot_offset[i];
         active_s[i] = a.active_slots[i];
     }
-    for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = a.perm[i];
+    for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = a.perm[i] / a.k;   // token of each list entry
     const int n_act = (int)(*a.n_active);
     __syncthreads();
 
@@ -276,7 +280,8 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         for (int gr = 0; gr < NG; ++gr) {
             const int tk = tok0 + 16 * gr + n;
             int boff = -1;
-            if (tk < cm) boff = (cbrow0 >= 0 ? cbrow0 + tk : perm_s[corow0 + tk] / a.k) * cK + cpan * (c_rs / 2);
+            if (tk < (ALLTOK ? a.T : cm))
+                boff = (cbrow0 >= 0 ? cbrow0 + tk : perm_s[corow0 + tk]) * cK + cpan * (c_rs / 2);
 #pragma unroll
             for (int j = 0; j < kPieces; ++j) {
                 int kb = w + kWaves * j;
@@ -309,7 +314,12 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
                 const int gr = tid / kOutPerItem, q = tid - gr * kOutPerItem;
                 const int tok = d[4] + 16 * gr + ((q >> 2) & 15), row = 4 * (q >> 6) + (q & 3);
                 if (tok < d[3]) {
-                    const float v = out_s[slot * (NG * kOutPerItem) + tid];
+                    int src = tid;
+                    if (ALLTOK && !d[0]) {   // entry `tok` of the expert's list: its token's column
+                        const int t = perm_s[d[1] + tok];
+                        src = (t >> 4) * kOutPerItem + ((q >> 6) << 6 | (t & 15) << 2 | (q & 3));
+                    }
+                    const float v = out_s[slot * (NG * kOutPerItem) + src];
                     // explicit global stores (a generic-pointer store would count as an LDS access too)
                     if (d[0]) {
                         unsigned char *orow = (unsigned char *)a.out_sh + (size_t)(d[1] + tok) * (a.R_sh * OB) + d[2];

@@ -261,9 +261,6 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         pvalid = true;
         issue(0);
     }
-    prod_advance();
-    issue(1);
-    prod_advance();
 
     u32x4 bx[NG][kPieces];
     int bx_key = -1, bx_panel = -1;   // expert (and panel) whose FIRST token pass the registers hold
@@ -408,6 +405,16 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
             flush();
         }
     };
+
+    // The first B operand is fetched before the second tile is requested: its wait drains every
+    // load in flight, and here that is only the first tile; inside step(0) it would hold back the
+    // request for the third tile until the second had arrived.
+    load_bx(0);
+    bx_key = ckey;
+    bx_panel = cpan;
+    prod_advance();
+    issue(1);
+    prod_advance();
 
     // (first tile peeled off so that the loop is always entered in the same state: the compiler then
     // counts the loads in flight exactly and each park waits for its own tile only)

@@ -145,6 +145,23 @@ class Oracle:
         self._lib.oracle_prefetch_counts(_p(s), _p(slot_table), s.shape[0], K, _p(n_tau))
         return n_tau
 
+    def balance_threshold(self, f, n_tau, r_c, r_g, K: int, gamma: int, k: int, t_cpu: float, t_gpu: float,
+                          t_io: float, t_draft: float, l_target: int, w_expert: int, vram_left: int):
+        """tau* of one layer and (b, T_cpu[0..K], T_gpu[0..K]); entry 0 of the time tables is NaN."""
+        f, n_tau = _c(f, np.int32), _c(n_tau, np.int32)
+        r_c, r_g = _c(r_c, np.float64), _c(r_g, np.float64)
+        assert n_tau.shape == r_c.shape == r_g.shape == (K + 1,)
+        b = np.zeros(1, dtype=np.int32)
+        tc = np.full(K + 1, np.nan)
+        tg = np.full(K + 1, np.nan)
+        fn = self._lib.oracle_balance_threshold
+        fn.restype = ctypes.c_int
+        fn.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 4 + [ctypes.c_double] * 4 + [ctypes.c_int,
+                       ctypes.c_int64, ctypes.c_int64] + [ctypes.c_void_p] * 3
+        tau = fn(_p(f), _p(n_tau), _p(r_c), _p(r_g), f.shape[0], K, gamma, k, t_cpu, t_gpu, t_io, t_draft,
+                 l_target, w_expert, vram_left, _p(b), _p(tc), _p(tg))
+        return int(tau), int(b[0]), tc, tg
+
     def verify_layer(self, hidden, router_w, router_bias, slot_table, w_gate, w_up, w_down, k: int,
                      sh_gate=None, sh_up=None, sh_down=None) -> LayerResult:
         hidden = _c(hidden, np.uint16)

@@ -32,6 +32,14 @@
  * upward test comes first, so a boundary of 0 lets a fluctuation of 0 raise
  * the utility, as the listing's ">=" says.
  *
+ * And the Heterogeneous Workload Balancer's threshold (Sec. 3.3 and the
+ * appendix on its formulation): tau* = the feasible integer tau in [1,K] that
+ * minimises |T_cpu(tau) - T_gpu(tau)|, by evaluating every tau (the
+ * definition; the paper's four-candidate shortcut is a method that relies on
+ * convexity and is checked against this in the tests).  Readings: ties go to
+ * the smaller tau; b counts the experts with a non-zero frequency; both
+ * constraints are "<=" as printed; no feasible tau gives K.
+ *
  * Pinned by tests/test_oracle_pins.py (brute-force dense evaluation in
  * numpy, textbook SwiGLU through torch's own linear/silu, closed forms,
  * the worked example of App. C.1, invariants).  No function here is
@@ -249,4 +257,48 @@ void oracle_prefetch_counts(const int32_t *s, const int32_t *slot_table, int N, 
             if (s[i] >= tau && slot_table[i] < 0) n += 1;
         n_tau[tau] = n;
     }
+}
+
+/* ---------------------------------------------------------------------------
+ * Heterogeneous Workload Balancer for one layer (Sec. 3.3: the two time
+ * equations, the objective and its three constraints; appendix "Solution
+ * Derivation": fallback tau = K when nothing is feasible).
+ *   b            = number of experts with f_i > 0 (de-duplicated activated experts)
+ *   T_cpu(tau)   = r_c(tau) * gamma * k * t_cpu
+ *   T_gpu(tau)   = r_g(tau) * b * t_gpu
+ *   feasible     : t_io * n(tau) <= max(T_cpu, T_gpu) + gamma * t_draft / l_target
+ *                  w_expert * n(tau) <= vram_left           (bytes, integers)
+ *   tau*         = argmin over feasible tau in 1..K of |T_cpu - T_gpu|, smaller tau on ties
+ * r_c, r_g, n_tau are tables indexed by tau = 0..K (entry 0 unused here).
+ * t_cpu_out / t_gpu_out (K+1 doubles each, may be NULL) receive the two times.
+ * Returns tau*.
+ * ------------------------------------------------------------------------- */
+int oracle_balance_threshold(const int32_t *f, const int32_t *n_tau, const double *r_c, const double *r_g,
+                             int N, int K, int gamma, int k, double t_cpu, double t_gpu, double t_io,
+                             double t_draft, int l_target, int64_t w_expert, int64_t vram_left,
+                             int32_t *b_out, double *t_cpu_out, double *t_gpu_out)
+{
+    int b = 0;
+    for (int i = 0; i < N; ++i)
+        if (f[i] > 0) b += 1;
+    if (b_out) *b_out = b;
+    int best = -1;
+    double best_f = 0.0;
+    for (int tau = 1; tau <= K; ++tau) {
+        double tc = ((r_c[tau] * (double)gamma) * (double)k) * t_cpu;
+        double tg = (r_g[tau] * (double)b) * t_gpu;
+        if (t_cpu_out) t_cpu_out[tau] = tc;
+        if (t_gpu_out) t_gpu_out[tau] = tg;
+        double total = tc > tg ? tc : tg;
+        double window = total + ((double)gamma * t_draft) / (double)l_target;
+        int io_ok = t_io * (double)n_tau[tau] <= window;
+        int mem_ok = w_expert * (int64_t)n_tau[tau] <= vram_left;
+        if (!io_ok || !mem_ok) continue;
+        double obj = fabs(tc - tg);
+        if (best < 0 || obj < best_f) {
+            best = tau;
+            best_f = obj;
+        }
+    }
+    return best < 0 ? K : best;
 }

@@ -504,3 +504,111 @@ def pin_prefetch_counts(O):
 
 
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]
+
+
+# ---------------------------------------------------------------------------
+# Heterogeneous Workload Balancer (Sec. 3.3; appendix on its formulation)
+# ---------------------------------------------------------------------------
+_BAL = dict(t_cpu=40.0, t_gpu=3.0, t_io=25.0, t_draft=600.0, l_target=24, w_expert=17_301_504, vram_left=10**12)
+
+
+def _bal(O, f, n_tau, r_c, r_g, K, gamma, k, **kw):
+    p = dict(_BAL)
+    p.update(kw)
+    return O.balance_threshold(f, n_tau, r_c, r_g, K, gamma, k, **p)
+
+
+def pin_balancer_worked_example(O):
+    """App. C.1: gamma = 2, k = 2, resident {3}, tokens {0,3},{2,3}: r_c = 1/2, b = 3, r_g = 1/3, so
+    the host takes r_c * 4 = 2 unit times and the device r_g * 3 = 1 unit time."""
+    g = _worked_example()[0]
+    hist = np.array([int(v) for v in g["hist"]], dtype=np.int32)
+    r_c = np.array([0.0, float(g["r_c"][0])])
+    r_g = np.array([0.0, float(g["r_g"][0])])
+    tau, b, tc, tg = _bal(O, hist, np.zeros(2, dtype=np.int32), r_c, r_g, 1, 2, 2, t_cpu=7.0, t_gpu=5.0)
+    assert b == 3 == int(g["distinct_active"][0]) and tau == 1
+    close(tc[1], 2 * 7.0)
+    close(tg[1], 1 * 5.0)
+
+
+def _four_candidates(tc, tg, feas, K):
+    """The appendix's shortcut, written independently: feasible bounds, and floor / ceil of the point
+    where the two (linearly interpolated) time curves cross; smaller tau on ties; K if infeasible."""
+    S = [t for t in range(1, K + 1) if feas[t]]
+    if not S:
+        return K
+    cand = {S[0], S[-1]}
+    d = tc - tg
+    for t in range(1, K):
+        if d[t] == 0:
+            cand.add(t)
+        if d[t] * d[t + 1] < 0:
+            cross = t + d[t] / (d[t] - d[t + 1])
+            cand.update({int(np.floor(cross)), int(np.ceil(cross))})
+    if d[K] == 0:
+        cand.add(K)
+    cand = sorted(c for c in cand if c in S)
+    return min(cand, key=lambda t: (abs(d[t]), t))
+
+
+def pin_balancer_convex_shortcut(O):
+    """With r_c increasing and r_g decreasing in tau (the paper's premise) and a contiguous feasible
+    range, evaluating every tau and the four-candidate shortcut agree."""
+    rng = np.random.default_rng(11)
+    for trial in range(200):
+        K = int(rng.integers(1, 9))
+        gamma, k = int(rng.integers(K, 16)), int(rng.integers(1, 9))
+        r_c = np.concatenate([[0.0], np.sort(rng.random(K))])
+        r_g = np.concatenate([[1.0], np.sort(rng.random(K))[::-1]])
+        N = 64
+        f = (rng.random(N) < 0.3).astype(np.int32) * rng.integers(1, gamma + 2, size=N).astype(np.int32)
+        n_tau = np.concatenate([[40], np.sort(rng.integers(0, 40, size=K))[::-1]]).astype(np.int32)
+        kw = dict(t_cpu=float(rng.uniform(5, 80)), t_gpu=float(rng.uniform(0.5, 10)),
+                  t_io=float(rng.uniform(1, 60)), t_draft=float(rng.uniform(100, 900)))
+        tau, b, tc, tg = _bal(O, f, n_tau, r_c, r_g, K, gamma, k, **kw)
+        assert b == int((f > 0).sum())
+        win = np.maximum(tc, tg) + gamma * kw["t_draft"] / _BAL["l_target"]
+        feas = np.zeros(K + 1, dtype=bool)
+        feas[1:] = kw["t_io"] * n_tau[1:] <= win[1:]
+        S = np.flatnonzero(feas)
+        if len(S) and S[-1] - S[0] + 1 != len(S):
+            continue   # (n(tau) decreasing makes the feasible set an upper range; skip oddities of random draws)
+        assert tau == _four_candidates(tc, tg, feas, K), (trial, tau, tc, tg, feas)
+
+
+def pin_balancer_constraints_and_limits(O):
+    """Closed cases: an idle host (t_cpu = 0) sends everything above the largest feasible threshold
+    to it; an idle device the smallest; the I/O and the memory limits each cut the range from below
+    ('<=' holds with equality); nothing feasible gives K; scaling every time by 8 changes nothing."""
+    K, gamma, k = 4, 8, 6
+    f = np.array([3, 0, 1, 2, 0, 9], dtype=np.int32)             # b = 4
+    r_c = np.array([0.0, 0.1, 0.3, 0.6, 0.9])
+    r_g = np.array([1.0, 0.9, 0.7, 0.4, 0.2])
+    n_tau = np.array([6, 5, 3, 2, 0], dtype=np.int32)
+    assert _bal(O, f, n_tau, r_c, r_g, K, gamma, k, t_cpu=0.0)[0] == 4
+    assert _bal(O, f, n_tau, r_c, r_g, K, gamma, k, t_gpu=0.0)[0] == 1
+    tau0, b, tc, tg = _bal(O, f, n_tau, r_c, r_g, K, gamma, k)
+    assert b == 4
+    want = min(range(1, K + 1), key=lambda t: (abs(r_c[t] * gamma * k * 40.0 - r_g[t] * 4 * 3.0), t))
+    assert tau0 == want
+    # memory: room for exactly n(2) = 3 experts -> tau = 1 (5 experts) is out, tau = 2 is in
+    w = _BAL["w_expert"]
+    assert _bal(O, f, n_tau, r_c, r_g, K, gamma, k, t_gpu=0.0, vram_left=3 * w)[0] == 2
+    assert _bal(O, f, n_tau, r_c, r_g, K, gamma, k, t_gpu=0.0, vram_left=3 * w - 1)[0] == 3
+    # I/O: window(tau) = max(Tc,Tg) + gamma*t_draft/L; choose t_io so that tau = 1 sits exactly on the limit
+    win1 = max(tc[1], tg[1]) + gamma * 600.0 / 24
+    assert _bal(O, f, n_tau, r_c, r_g, K, gamma, k, t_gpu=0.0, t_io=win1 / 5 * (1 + 1e-9))[0] >= 2
+    tc0 = r_c[1] * gamma * k * 40.0
+    assert _bal(O, f, n_tau, r_c, r_g, K, gamma, k, t_gpu=0.0, t_io=(tc0 + gamma * 600.0 / 24) / 5)[0] == 1
+    # nothing feasible -> K
+    assert _bal(O, f, np.array([6, 5, 5, 5, 5], dtype=np.int32), r_c, r_g, K, gamma, k, vram_left=w)[0] == K
+    # tie -> smaller tau
+    r_sym = np.array([0.0, 0.2, 0.2, 0.2, 0.2])
+    assert _bal(O, f, np.zeros(5, dtype=np.int32), r_sym, r_sym, K, gamma, k)[0] == 1
+    s8 = _bal(O, f, n_tau, r_c, r_g, K, gamma, k, t_cpu=320.0, t_gpu=24.0, t_io=200.0, t_draft=4800.0)
+    assert s8[0] == tau0
+    close(s8[2][1:], 8 * tc[1:])
+    close(s8[3][1:], 8 * tg[1:])
+
+
+ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

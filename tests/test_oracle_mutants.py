@@ -38,6 +38,18 @@ MUTANTS = {
     "est_signed_fluctuation_in_dn": ("(int64_t)lam_num * (-d)) / lam_den);", "(int64_t)lam_num * d) / lam_den);"),
     "prefetch_counts_residents": ("if (s[i] >= tau && slot_table[i] < 0) n += 1;", "if (s[i] >= tau && slot_table[i] >= 0) n += 1;"),
     "prefetch_strict_threshold": ("if (s[i] >= tau && slot_table[i] < 0) n += 1;", "if (s[i] > tau && slot_table[i] < 0) n += 1;"),
+    "bal_b_counts_assignments": ("if (f[i] > 0) b += 1;", "if (f[i] > 0) b += f[i];"),
+    "bal_cpu_time_uses_b": ("double tc = ((r_c[tau] * (double)gamma) * (double)k) * t_cpu;", "double tc = (r_c[tau] * (double)b) * t_cpu;"),
+    "bal_gpu_time_uses_gamma_k": ("double tg = (r_g[tau] * (double)b) * t_gpu;", "double tg = ((r_g[tau] * (double)gamma) * (double)k) * t_gpu;"),
+    "bal_window_uses_min": ("double total = tc > tg ? tc : tg;", "double total = tc < tg ? tc : tg;"),
+    "bal_draft_term_not_per_layer": ("((double)gamma * t_draft) / (double)l_target;", "((double)gamma * t_draft);"),
+    "bal_io_strict": ("<= window;", "< window;"),
+    "bal_memory_ignored": ("if (!io_ok || !mem_ok) continue;", "if (!io_ok) continue;"),
+    "bal_io_ignored": ("if (!io_ok || !mem_ok) continue;", "if (!mem_ok) continue;"),
+    "bal_signed_objective": ("double obj = fabs(tc - tg);", "double obj = tc - tg;"),
+    "bal_ties_to_larger": ("if (best < 0 || obj < best_f) {", "if (best < 0 || obj <= best_f) {"),
+    "bal_fallback_one": ("return best < 0 ? K : best;", "return best < 0 ? 1 : best;"),
+    "bal_tau_from_zero": ("for (int tau = 1; tau <= K; ++tau) {\n        double tc", "for (int tau = 0; tau <= K; ++tau) {\n        double tc"),
     "descending_order_lost": ("topk_idx[(size_t)t * k + j] = best;", "topk_idx[(size_t)t * k + (k - 1 - j)] = best;"),
 }
 

@@ -187,19 +187,30 @@ def main():
         for t in range(16):
             B.moe_utility_update(d_fr[t % 8], *st, d_tab, d_n, L_est, shape.E, K_est, 1, 10)
         torch.cuda.synchronize()
+        # ... and the balancer's threshold per layer from those counts (tables r_c, r_g: synthetic, monotone)
+        r_c = torch.from_numpy(np.sort(rng.random((L_est, K_est + 1)), axis=1)).cuda()
+        r_g = torch.from_numpy(np.ascontiguousarray(np.sort(rng.random((L_est, K_est + 1)), axis=1)[:, ::-1])).cuda()
+        bal_p = B.BalanceParams(40.0, 3.0, 6.0, 600.0, L_est, 6 * shape.H * shape.F, 16 * 6 * shape.H * shape.F)
+        d_tau = torch.zeros(L_est, **i32)
+        B.moe_balance_threshold(d_fr[0], d_n, r_c, r_g, L_est, shape.E, K_est, gamma, shape.k, bal_p, d_tau)
+        torch.cuda.synchronize()
         B.moe_profile_enable(True)
         n_est = 200
         for t in range(n_est):
             B.moe_utility_update(d_fr[t % 8], *st, d_tab, d_n, L_est, shape.E, K_est, 1, 10)
+            B.moe_balance_threshold(d_fr[t % 8], d_n, r_c, r_g, L_est, shape.E, K_est, gamma, shape.k, bal_p, d_tau)
         torch.cuda.synchronize()
         B.moe_profile_enable(False)
         ms, n = B.moe_profile_read(B.KERNEL_ESTIMATOR)
+        bal_ms, bal_n = B.moe_profile_read(B.KERNEL_BALANCER)
         est_us = ms * 1e3 / n - ev_us
         est_bytes = L_est * shape.E * 4 * (6 + 4) + L_est * (K_est + 1) * 4   # 6 words read, 4 written per expert
         est = {"kernel": "utility_update_kernel", "layers": L_est, "experts": shape.E, "K": K_est,
                "lambda": "1/10", "avg_us": round(est_us, 2), "avg_us_event_pair": round(ms * 1e3 / n, 2),
                "bound": "latency", "algorithmic_bytes": est_bytes,
-               "note": "one launch advances all layers by one inference step and counts n(tau)"}
+               "note": "one launch advances all layers by one inference step and counts n(tau)",
+               "balancer": {"kernel": "balance_kernel", "avg_us": round(bal_ms * 1e3 / bal_n - ev_us, 2),
+                            "avg_us_event_pair": round(bal_ms * 1e3 / bal_n, 2), "bound": "latency"}}
         if not args.no_cpu_baseline:
             import oracle
             z = np.zeros(shape.E, dtype=np.int32)

@@ -161,6 +161,35 @@ int moe_utility_update(const int32_t *f, int32_t *f_prev, int32_t *s, int32_t *t
                        const int32_t *slot_table, int32_t *n_tau, int L, int N, int K, int lam_num, int lam_den,
                        void *stream);
 
+/* Sec. 3.3 (the two time equations, the objective, its constraints) and the
+ * appendix on its solution: the per-layer threshold tau* that balances host
+ * and device time.  For each layer l (one launch for all L):
+ *   b          = number of experts with f[l,i] > 0
+ *   T_cpu(tau) = r_c[l,tau] * gamma * k * t_cpu
+ *   T_gpu(tau) = r_g[l,tau] * b * t_gpu
+ *   feasible   : t_io * n_tau[l,tau] <= max(T_cpu, T_gpu) + gamma * t_draft / l_target
+ *                and w_expert_bytes * n_tau[l,tau] <= vram_left_bytes
+ *   tau_out[l] = the feasible tau in 1..K with the smallest |T_cpu - T_gpu|
+ *                (the smaller tau on ties), K if none is feasible.
+ * Every tau is evaluated (K <= 64), in fp64 in the order written above, so
+ * the result is the definition's, with or without the convexity the paper's
+ * shortcut assumes.  f [L,N] int32 (the histograms); n_tau [L,K+1] int32 (as
+ * moe_utility_update writes it); r_c, r_g [L,K+1] fp64 tables indexed by tau
+ * (entry 0 unused; the paper learns them in a warm-up run, here they are
+ * inputs); params: HOST pointer; b_out [L] int32 or NULL.  All other
+ * pointers are device pointers. */
+typedef struct moe_balance_params {
+    double t_cpu, t_gpu;          /* unit time of one activated expert on host / device */
+    double t_io;                  /* unit time to load one expert */
+    double t_draft;               /* unit time of one draft-model token */
+    int l_target;                 /* layers of the target model */
+    int64_t w_expert_bytes;       /* memory of one expert */
+    int64_t vram_left_bytes;      /* memory available for prefetched experts */
+} moe_balance_params_t;
+int moe_balance_threshold(const int32_t *f, const int32_t *n_tau, const double *r_c, const double *r_g, int L,
+                          int N, int K, int gamma, int k, const moe_balance_params_t *params, int32_t *tau_out,
+                          int32_t *b_out, void *stream);
+
 /* Measurement aid (host-side state only; not part of the layer's arithmetic).
  * While enabled, every kernel the library launches is bracketed by a pair of
  * HIP events recorded on the caller's stream.  kind: MOE_KERNEL_*.
@@ -169,7 +198,8 @@ int moe_utility_update(const int32_t *f, int32_t *f_prev, int32_t *s, int32_t *t
  * moe_profile_read sums hipEventElapsedTime over the records of one kind; the
  * caller must have synchronised the stream.  total_ms, launches: host. */
 enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2 /* gate/up (and down when fused) */,
-       MOE_KERNEL_COMBINE = 3, MOE_KERNEL_DOWN = 4, MOE_KERNEL_ESTIMATOR = 5, MOE_KERNEL_KINDS = 6 };
+       MOE_KERNEL_COMBINE = 3, MOE_KERNEL_DOWN = 4, MOE_KERNEL_ESTIMATOR = 5, MOE_KERNEL_BALANCER = 6,
+       MOE_KERNEL_KINDS = 7 };
 int moe_profile_enable(int on);
 int moe_profile_read(int kind, double *total_ms, int *launches);
 const char *moe_profile_kernel_name(int kind);

@@ -42,6 +42,14 @@ _lib.moe_expert_histogram.argtypes = [_vp, _i, _i, _i, _vp, _vp]
 _lib.moe_slot_resolve.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moe_grouped_ffn.argtypes = [_vp] * 6 + [_i] * 5 + [_vp, _i, _i, _vp, _sz, _vp]
 _lib.moe_verify_layer.argtypes = [ctypes.POINTER(MoeShape)] + [_vp] * 17 + [_i, _i, _vp, _sz, _vp]
+class BalanceParams(ctypes.Structure):
+    _fields_ = [("t_cpu", ctypes.c_double), ("t_gpu", ctypes.c_double), ("t_io", ctypes.c_double),
+                ("t_draft", ctypes.c_double), ("l_target", ctypes.c_int), ("w_expert_bytes", ctypes.c_int64),
+                ("vram_left_bytes", ctypes.c_int64)]
+
+
+_lib.moe_balance_threshold.argtypes = [_vp] * 4 + [_i] * 5 + [ctypes.POINTER(BalanceParams), _vp, _vp, _vp]
+_lib.moe_balance_threshold.restype = _i
 _lib.moe_utility_init.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]
 _lib.moe_utility_update.argtypes = [_vp] * 7 + [_i] * 5 + [_vp]
 for _f in ("moe_utility_init", "moe_utility_update", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk", "moe_expert_histogram",
@@ -56,9 +64,9 @@ _lib.moe_profile_event_overhead.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_dou
 _lib.moe_profile_event_overhead.restype = _i
 _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
-KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6
+KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_BALANCER, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6, 7
 
-EXPORTS = ("moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
+EXPORTS = ("moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
 
 
@@ -193,6 +201,13 @@ def moe_utility_update(f, f_prev, s, theta_up, theta_dn, slot_table, n_tau, L, N
     rc = _lib.moe_utility_update(_ptr(f), _ptr(f_prev), _ptr(s), _ptr(theta_up), _ptr(theta_dn),
                                  _ptr(slot_table), _ptr(n_tau), L, N, K, lam_num, lam_den, _stream(stream))
     return _check(rc, "moe_utility_update", check)
+
+
+def moe_balance_threshold(f, n_tau, r_c, r_g, L, N, K, gamma, k, params: BalanceParams, tau_out, b_out=None,
+                          stream=None, check=True) -> int:
+    rc = _lib.moe_balance_threshold(_ptr(f), _ptr(n_tau), _ptr(r_c), _ptr(r_g), L, N, K, gamma, k,
+                                    ctypes.byref(params), _ptr(tau_out), _ptr(b_out), _stream(stream))
+    return _check(rc, "moe_balance_threshold", check)
 
 
 # ---------------------------------------------------------------------------

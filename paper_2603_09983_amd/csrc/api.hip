@@ -127,6 +127,7 @@ extern "C" const char *moe_profile_kernel_name(int kind)
     case MOE_KERNEL_COMBINE: return "combine_kernel";
     case MOE_KERNEL_DOWN: return "ffn_down";
     case MOE_KERNEL_ESTIMATOR: return "utility_update_kernel";
+    case MOE_KERNEL_BALANCER: return "balance_kernel";
     default: return "?";
     }
 }

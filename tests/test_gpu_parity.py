@@ -40,6 +40,8 @@ SMALL_CASES = {
                      hidden="unit"),
     # more experts than one lane each (E > 64)
     "E130": dict(T=5, H=128, E=130, k=7, F=64, C=40, hidden="unit"),
+    # the 128-expert / top-8 shape class (two logits per lane in the wavefront ranking)
+    "E128_k8": dict(T=9, H=256, E=128, k=8, F=128, C=48, hidden="unit"),
     # nothing resident: output is the shared expert alone, every assignment missed
     "cache_empty": dict(T=4, H=128, E=8, k=2, F=128, C=0, n_shared=1, Fs=128),
 }
@@ -103,6 +105,36 @@ def test_device_part_plus_host_part_is_the_whole(G):
     ref_all = oracle.layer_from_inputs(li)
     y = buf.out.cpu().numpy().astype(np.float64)
     assert np.max(np.abs(y - ref_all.y)) <= G.RTOL_RMS * G.rms(ref_all.y)
+
+
+def test_miss_list_consumer_completes_the_layer(G):
+    """App. D end to end: the device leaves the missed assignments in miss_list; a host consumer
+    computes exactly those (expert of topk_idx, gate of topk_w, plain numpy fp64), hands its
+    partial result back in `out`, and the second call with accumulate=1 joins the two.  The sum
+    must be the layer with every expert resident.  Shape class E = 128, top-8."""
+    li = layer(21, T=9, H=256, E=128, k=8, F=128, C=40, hidden="unit")
+    d = G.upload(li)
+    buf = G.run_layer(d)
+    n = int(buf.miss_count.item())
+    miss = buf.miss_list.cpu().numpy()[:n]
+    idx = buf.topk_idx.cpu().numpy()
+    gate = buf.topk_w.cpu().numpy().astype(np.float64)
+    assert n > 0 and np.all(li.slot_table[idx.reshape(-1)[miss]] < 0)
+    k = li.shape.k
+    x = synth.bf16_bits_to_f32(li.hidden).astype(np.float64)
+    host = np.zeros((li.shape.T, li.shape.H))
+    for a in miss:
+        t, j = divmod(int(a), k)
+        e = int(idx[t, j])
+        wg, wu, wd = (synth.bf16_bits_to_f32(w[e]).astype(np.float64) for w in (li.w_gate, li.w_up, li.w_down))
+        g_, u_ = wg @ x[t], wu @ x[t]
+        host[t] += gate[t, j] * (wd @ (g_ / (1.0 + np.exp(-g_)) * u_))
+    buf.out.copy_(torch.from_numpy(host.astype(np.float32)).cuda())
+    G.run_layer(d, buf, accumulate=True)
+    li.slot_table = np.arange(li.shape.E, dtype=np.int32)
+    whole = oracle.layer_from_inputs(li)
+    y = buf.out.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(y - whole.y)) <= G.RTOL_RMS * G.rms(whole.y)
 
 
 def test_bf16_output(G):

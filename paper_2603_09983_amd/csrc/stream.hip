@@ -304,14 +304,16 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     // Results wait in LDS and leave in batches: a store in the steady state would make every
     // later wait on the weight loads a wait for everything (loads and stores share one counter).
     auto flush = [&]() {
-        for (int r = flushed; r < orec; ++r) {
+        // one wavefront per waiting record, so the whole batch leaves in one round of stores
+        for (int r = flushed + w; r < orec; r += kWaves) {
             const int slot = r % kOutCap;
             const int *d = odesc_s + slot * 8;
-            if (tid < NG * kOutPerItem) {
-                const int gr = tid / kOutPerItem, q = tid - gr * kOutPerItem;
+#pragma unroll
+            for (int i = lane; i < NG * kOutPerItem; i += kWave) {
+                const int gr = i / kOutPerItem, q = i - gr * kOutPerItem;
                 const int tok = d[4] + 16 * gr + ((q >> 2) & 15), row = 4 * (q >> 6) + (q & 3);
                 if (tok < d[3]) {
-                    int src = tid;
+                    int src = i;
                     if (ALLTOK && !d[0]) {   // entry `tok` of the expert's list: its token's column
                         const int t = perm_s[d[1] + tok];
                         src = (t >> 4) * kOutPerItem + ((q >> 6) << 6 | (t & 15) << 2 | (q & 3));

@@ -67,9 +67,9 @@ const char *moe_status_string(int status);
  * (an upper bound for the single-step entry points).  shape: host pointer. */
 int moe_workspace_bytes(const moe_shape_t *shape, size_t *bytes_out);
 
-/* Clears the control block and the stamped-entry region at the start of a
- * freshly allocated workspace (the first 256 B + 512 KB, as far as
- * workspace_bytes reaches).  Call once per workspace before its first use. */
+/* Zero-fills a freshly allocated workspace (control block, call counter and
+ * every region whose entries the kernels stamp with the call number).  Call
+ * once per workspace, over its full size, before its first use. */
 int moe_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Synchronous health check: waits for `stream`, then reads the control block.
@@ -121,7 +121,8 @@ int moe_grouped_ffn(const void *hidden, const float *topk_w, const int32_t *slot
                     const void *w_up, const void *w_down, int T, int H, int F, int k, int C, void *out,
                     int out_bf16, int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Steps 1-4 for one verification batch in four launches on `stream`.
+/* Steps 1-4 for one verification batch in three launches on `stream` (four
+ * for batches above 16 tokens).
  * shape: host pointer.  shared_gate/up [n_shared,F_shared,H] and shared_down
  * [n_shared,H,F_shared] bf16 (NULL when n_shared = 0) are added with weight 1
  * for every token.  All step outputs are produced: topk_idx, topk_w [T,k];

@@ -174,8 +174,9 @@ extern "C" int moe_workspace_status(void *workspace, size_t workspace_bytes, voi
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return launch_failed(e);
     if (ctrl[kCtrlError] == 0u) return MOE_OK;
-    // a wait ran out part-way through a call: start again from a clean control block and tag region
-    e = launch_clear_ctrl(workspace, workspace_bytes, s);
+    // a wait ran out part-way through a call: clear the flag (the call counter keeps counting)
+    ctrl[kCtrlError] = 0u;
+    e = hipMemcpyAsync(workspace, ctrl, sizeof ctrl, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return launch_failed(e);
     snprintf(g_launch_msg, sizeof g_launch_msg, "a bounded wait inside a kernel ran out (results of that call are invalid)");
@@ -240,6 +241,7 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
             int n_shared, int F_shared, const WsLayout &w, char *ws, void *out, int out_bf16, int accumulate,
             hipStream_t s)
 {
+    // (the caller's routing / list kernel has given this call its number in the control block)
     int32_t *slot_count = (int32_t *)(ws + w.slot_count), *slot_offset = (int32_t *)(ws + w.slot_offset);
     int32_t *perm = (int32_t *)(ws + w.perm), *pos = (int32_t *)(ws + w.pos);
     CombineArgs c = {};
@@ -259,7 +261,7 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
         g.T = T; g.k = k; g.C = C;
         g.R = F; g.K = H; g.R_sh = F_shared; g.K_sh = H; g.n_shared = n_shared;
         g.KP = g.KP_sh = stream_panel_width(H);
-        e = launch_stream(g, true, s);
+        e = launch_stream(g, true, nullptr, s);
         if (e != hipSuccess) return launch_failed(e);
         StreamArgs d = g;
         d.w0 = (const uint16_t *)w_down; d.w1 = nullptr;
@@ -268,7 +270,17 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
         d.out = ws + w.o; d.out_sh = ws + w.o_sh;
         d.R = H; d.K = F; d.R_sh = H; d.K_sh = F_shared;
         d.KP = stream_panel_width(F); d.KP_sh = n_shared ? stream_panel_width(F_shared) : 0;
-        e = launch_stream(d, false, s);
+        if (stream_can_join(d)) {
+            // small batch: the down kernel also sums the per-assignment outputs into `out`
+            JoinArgs j = {};
+            j.topk_w = topk_w; j.pos = pos; j.out = out;
+            j.epoch = (const unsigned *)(ws + w.ctrl) + kCtrlEpoch;
+            j.error_flag = (unsigned *)(ws + w.ctrl) + kCtrlError;
+            j.out_bf16 = out_bf16; j.accumulate = accumulate;
+            e = launch_stream(d, false, &j, s);
+            return e == hipSuccess ? MOE_OK : launch_failed(e);
+        }
+        e = launch_stream(d, false, nullptr, s);
         if (e != hipSuccess) return launch_failed(e);
         e = launch_combine_rows(c, (const float *)(ws + w.o), (const float *)(ws + w.o_sh), s);
         return e == hipSuccess ? MOE_OK : launch_failed(e);
@@ -308,7 +320,8 @@ extern "C" int moe_grouped_ffn(const void *hidden, const float *topk_w, const in
     hipError_t e = launch_lists_from_slots(slot_idx, T * k, C, (int32_t *)(ws + w.slot_count),
                                            (int32_t *)(ws + w.slot_offset), (int32_t *)(ws + w.perm),
                                            (int32_t *)(ws + w.pos), (int32_t *)(ws + w.active),
-                                           (unsigned *)(ws + w.ctrl) + kCtrlNActive, s);
+                                           (unsigned *)(ws + w.ctrl) + kCtrlNActive,
+                                           (unsigned *)(ws + w.ctrl) + kCtrlEpoch, s);
     if (e != hipSuccess) return launch_failed(e);
     return run_ffn(hidden, topk_w, w_gate, w_up, w_down, nullptr, nullptr, nullptr, T, H, F, k, C, 0, 0, w, ws,
                    out, out_bf16, accumulate, s);

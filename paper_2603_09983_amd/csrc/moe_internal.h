@@ -71,8 +71,9 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
         w.part = w.part_sh = o;
         w.act = o;     o += align256(A * F * 2);
         w.act_sh = o;  o += align256((size_t)n_shared * T * F_shared * 2);
-        w.o = o;       o += align256(A * H * 4);
-        w.o_sh = o;    o += align256((size_t)n_shared * T * H * 4);
+        // (8 bytes per element: small batches store (call number, value) entries, see JoinArgs)
+        w.o = o;       o += align256(A * H * 8);
+        w.o_sh = o;    o += align256((size_t)n_shared * T * H * 8);
     }
     w.total = o;
     return w;
@@ -119,6 +120,16 @@ struct StreamArgs {
     int KP, KP_sh;             // panel widths (columns parked in LDS at a time)
 };
 
+// The weighted sum back into token order at the end of the down kernel (small batches).
+struct JoinArgs {
+    const float *topk_w;       // [T,k]
+    const int32_t *pos;        // [T*k] row of the per-assignment outputs, or -1
+    void *out;                 // [T,H] fp32 or bf16
+    const unsigned *epoch;     // control word: number of this call (stamps the 64-bit entries)
+    unsigned *error_flag;      // control word set when a bounded wait ran out
+    int out_bf16, accumulate;
+};
+
 struct FfnArgs {
     const void *hidden;        // [T,H] bf16
     const void *w_gate, *w_up, *w_down;        // slot-major pools
@@ -143,16 +154,20 @@ hipError_t launch_resolve(const int32_t *topk_idx, const int32_t *slot_table, in
                           int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, int32_t *slot_count,
                           int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
                           unsigned *n_active, hipStream_t s);
+// (epoch: control word stepped by one, so that the FFN kernels of this call have a number of their own)
 hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_t *slot_count,
                                    int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
-                                   unsigned *n_active, hipStream_t s);
-hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s);
+                                   unsigned *n_active, unsigned *epoch, hipStream_t s);
+// join != null (down kernel only, stream_can_join() true): outputs leave as stamped 64-bit entries
+// and the kernel ends with the weighted sum into `out`; no combine launch is needed then
+hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join, hipStream_t s);
+bool stream_can_join(const StreamArgs &d);
 hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s);
 int stream_panel_width(int K);     // 0 when K has no panel split
 size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup);
 hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
-// clears the control block and, if `bytes` reaches that far, the tagged-logit region behind it
+// zero-fills the workspace (control block, stamped-entry regions and everything else)
 hipError_t launch_clear_ctrl(void *workspace, size_t bytes, hipStream_t s);
 // a launch that the measurement aid times by the dispatch's own start and end stamps when enabled
 hipError_t launch_timed(const void *fn, dim3 grid, dim3 block, void **params, size_t lds, hipStream_t s, int kind);

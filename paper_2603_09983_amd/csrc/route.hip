@@ -473,12 +473,14 @@ __global__ __launch_bounds__(kRouteThreads) void resolve_kernel(const int32_t *i
                                                                  int32_t *miss_list, int32_t *miss_count,
                                                                  int32_t *slot_count, int32_t *slot_offset,
                                                                  int32_t *perm, int32_t *pos,
-                                                                 int32_t *active_slots, unsigned *n_active)
+                                                                 int32_t *active_slots, unsigned *n_active,
+                                                                 unsigned *epoch)
 {
     extern __shared__ int dyn[];
     PostLds L = carve_lds(dyn, 0, C, A);
     block_post(idx, slot_table, A, E, C, nullptr, slot_idx, miss_list, miss_count, slot_count, slot_offset,
                perm, pos, active_slots, n_active, L.hist_s, L.cnt_s, L.off_s, L.scan_s, L.sidx_s);
+    if (epoch && threadIdx.x == 0) *epoch += 1u;   // the kernels that follow stamp their entries with this number
 }
 
 __global__ void clear_ctrl_kernel(unsigned *ws, int words)
@@ -548,29 +550,32 @@ hipError_t launch_resolve(const int32_t *topk_idx, const int32_t *slot_table, in
     size_t lds = post_lds_bytes(0, C, A, false);
     hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(kRouteThreads), lds, s, topk_idx, slot_table, A, E, C,
                        slot_idx, miss_list, miss_count, slot_count, slot_offset, perm, pos, active_slots,
-                       n_active);
+                       n_active, (unsigned *)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_t *slot_count,
                                    int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
-                                   unsigned *n_active, hipStream_t s)
+                                   unsigned *n_active, unsigned *epoch, hipStream_t s)
 {
     size_t lds = post_lds_bytes(0, C, A, false);
     prof_begin(1, s);
     hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(kRouteThreads), lds, s, (const int32_t *)nullptr,
                        (const int32_t *)nullptr, A, 0, C, const_cast<int32_t *>(slot_idx),
                        (int32_t *)nullptr, (int32_t *)nullptr, slot_count, slot_offset, perm, pos,
-                       active_slots, n_active);
+                       active_slots, n_active, epoch);
     prof_end(1, s);
     return hipGetLastError();
 }
 
 hipError_t launch_clear_ctrl(void *workspace, size_t bytes, hipStream_t s)
 {
-    const size_t full = (size_t)kCtrlBytes + (size_t)kTagEntries * 8;
-    const int words = (int)((bytes >= full ? full : (size_t)kCtrlBytes) / 4);
-    hipLaunchKernelGGL(clear_ctrl_kernel, dim3(words > 4096 ? 64 : 1), dim3(256), 0, s, (unsigned *)workspace, words);
+    // everything: a stale 64-bit entry anywhere in the workspace must not carry a future call number
+    const size_t words = bytes / 4;
+    if (words > (size_t)1 << 31) return hipErrorInvalidValue;
+    int blocks = (int)((words + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(clear_ctrl_kernel, dim3(blocks), dim3(256), 0, s, (unsigned *)workspace, (int)words);
     return hipGetLastError();
 }
 

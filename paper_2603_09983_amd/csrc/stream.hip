@@ -39,6 +39,7 @@ constexpr int kWaves = 16;
 constexpr int kPieces = 4;     // 1 KB pieces per wavefront per tile (64 KB tile / 16 wavefronts)
 constexpr int kRowPad = 16;    // bytes of padding per LDS tile row
 constexpr int kOutCap = 16;    // items whose results are kept in LDS between two batches of stores
+constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before a workgroup gives up waiting
 
 __device__ inline u32x4 ld_stream(const unsigned char *p)
 {
@@ -73,9 +74,19 @@ __device__ inline uint32_t f32_to_bf16_rne(float f)
 // MODE 0: batches up to 16 tokens (one group of 16 token columns per pass); MODE 1: up to 32 tokens
 // (two groups); MODE 2: larger batches: two groups per pass, and experts with more than 32 tokens
 // take further passes over the parked tile.
-template <bool GATEUP, int NPI, int MODE>
-__global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes)
+//
+// JOIN (down kernel, batches of one pass): the weighted sum back into token order (Sec. 2.2 last
+// line; the join of App. D when `accumulate` is set) rides at the end of the down kernel instead
+// of a launch of its own.  Every per-assignment output goes to memory as ONE 64-bit relaxed atomic
+// store (call number << 32 | fp32 bits); a workgroup that has finished its items takes a strip of 8
+// output columns, reads the entries that strip needs with atomic loads until they carry this
+// call's number (a bounded number of times: every other workgroup is resident and none of them
+// waits before it has stored), and adds them up in a fixed order.  No counter, no fence: an entry
+// with the right number IS the value.
+template <bool GATEUP, int NPI, int MODE, bool JOIN>
+__global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes, JoinArgs jn)
 {
+    static_assert(!JOIN || (!GATEUP && MODE == 0), "the join rides on the down kernel of small batches");
     constexpr int NG = MODE == 0 ? 1 : 2;   // token groups of 16 multiplied per pass
     constexpr bool MULTIPASS = MODE == 2;
     constexpr int RPI = GATEUP ? 8 : 16;    // output rows per item
@@ -252,7 +263,59 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         cnt = per + (b < rem ? 1 : 0);
         r_start = b * per + (b < rem ? b : rem) - s_start;
     }
-    if (cnt == 0) return;
+    const unsigned tag = JOIN ? *jn.epoch : 0u;   // number of this call (set by the routing / list kernel)
+    auto join = [&]() {
+        if (!JOIN) return;
+        typedef unsigned long long u64;
+        const int S = a.k + a.n_shared, nent = a.T * 8 * S;
+        float *val_s = (float *)tile_s;   // [token][column of the strip][source]; the tile buffer is free by now
+        for (int u = b; u < a.R / 8; u += G) {
+            __syncthreads();
+            for (int i = tid; i < nent; i += kThreads) {
+                const int tc = i / S, src = i - tc * S, t = tc >> 3, col = u * 8 + (tc & 7);
+                const u64 *p = nullptr;
+                if (src < a.k) {
+                    const int row = jn.pos[t * a.k + src];
+                    if (row >= 0) p = (const u64 *)a.out + (size_t)row * a.R + col;
+                } else {
+                    p = (const u64 *)a.out_sh + ((size_t)(src - a.k) * a.T + t) * a.R_sh + col;
+                }
+                float v = 0.f;   // an assignment whose expert is not resident adds nothing here
+                if (p) {
+                    u64 x = 0;
+                    int polls = 0;
+                    for (;;) {
+                        x = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if ((unsigned)(x >> 32) == tag) break;
+                        if (++polls > kSpinLimit) {   // cannot happen with the whole grid resident; never wait for ever
+                            atomicOr(jn.error_flag, 1u);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                    v = __uint_as_float((unsigned)x);
+                }
+                val_s[i] = v;
+            }
+            __syncthreads();
+            if (tid < a.T * 8) {
+                const int t = tid >> 3, col = u * 8 + (tid & 7);
+                const size_t o = (size_t)t * a.R + col;
+                float acc = 0.f;
+                if (jn.accumulate)
+                    acc = jn.out_bf16 ? __uint_as_float((uint32_t)((const uint16_t *)jn.out)[o] << 16)
+                                      : ((const float *)jn.out)[o];
+                for (int jj = 0; jj < a.k; ++jj) acc += jn.topk_w[t * a.k + jj] * val_s[tid * S + jj];
+                for (int i = 0; i < a.n_shared; ++i) acc += val_s[tid * S + a.k + i];
+                if (jn.out_bf16) ((uint16_t *)jn.out)[o] = (uint16_t)f32_to_bf16_rne(acc);
+                else ((float *)jn.out)[o] = acc;
+            }
+        }
+    };
+    if (cnt == 0) {
+        join();
+        return;
+    }
     const int ntiles = s_cnt * (a.n_shared ? a.K_sh / a.KP_sh : 0) + (cnt - s_cnt) * (a.K / a.KP);
     if (s_cnt == 0) {
         const int e = r_start / tiles;
@@ -320,7 +383,16 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
                     }
                     const float v = out_s[slot * (NG * kOutPerItem) + src];
                     // explicit global stores (a generic-pointer store would count as an LDS access too)
-                    if (d[0]) {
+                    if (JOIN) {
+                        // (call number, value) as one 64-bit entry; d[2] / OB = first column of the item
+                        const unsigned long long e = ((unsigned long long)tag << 32) | __float_as_uint(v);
+                        if (d[0])
+                            __hip_atomic_store((unsigned long long *)a.out_sh + (size_t)(d[1] + tok) * a.R_sh +
+                                                   (d[2] / OB + row), e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        else
+                            __hip_atomic_store((unsigned long long *)a.out + (size_t)(d[1] + tok) * a.R +
+                                                   (d[2] / OB + row), e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    } else if (d[0]) {
                         unsigned char *orow = (unsigned char *)a.out_sh + (size_t)(d[1] + tok) * (a.R_sh * OB) + d[2];
                         if (GATEUP) ((g_u16 *)(uintptr_t)orow)[row] = (uint16_t)f32_to_bf16_rne(v);
                         else ((g_f32 *)(uintptr_t)orow)[row] = v;
@@ -429,6 +501,7 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     if (t < ntiles) step(1);
     __syncthreads();
     flush();
+    join();
 }
 
 // out[t,:] (+)= sum_j w[t,j] * o[pos[t,j],:] + sum_i o_sh[i,t,:], in a fixed order
@@ -494,8 +567,16 @@ size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup)
     return (size_t)16 * (2 * kp + kRowPad) + (size_t)kWaves * kWave * 16;
 }
 
-hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s)
+bool stream_can_join(const StreamArgs &d)
 {
+    // one pass of tokens; the strip's entries (T x 8 columns x sources) fit the tile buffer
+    const size_t tile = (size_t)16 * (2 * (d.KP > d.KP_sh ? d.KP : d.KP_sh) + kRowPad);
+    return d.T <= 16 && d.R % 8 == 0 && (size_t)d.T * 8 * (d.k + d.n_shared) * 4 <= tile;
+}
+
+hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join, hipStream_t s)
+{
+    if (join && (gateup || !stream_can_join(a))) return hipErrorInvalidValue;
     const size_t tile = (size_t)16 * (2 * (a.KP > a.KP_sh ? a.KP : a.KP_sh) + kRowPad);
     const int ngl = a.T > 16 ? 2 : 1;
     const size_t lds = (size_t)16 * (2 * (a.KP > a.KP_sh ? a.KP : a.KP_sh) + kRowPad) +
@@ -505,15 +586,19 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s)
     const int kp_max = a.KP > a.KP_sh ? a.KP : a.KP_sh;
     const int npi = (kp_max / 32 + kWaves - 1) / kWaves;   // 1..4 pieces per wavefront and tile
     const int mode = a.T > 32 ? 2 : a.T > 16 ? 1 : 0;
-#define MOE_STREAM_FN(GU, N) \
-    {(const void *)stream_kernel<GU, N, 0>, (const void *)stream_kernel<GU, N, 1>, (const void *)stream_kernel<GU, N, 2>}
+#define MOE_STREAM_FN(GU, N)                                                                     \
+    {(const void *)stream_kernel<GU, N, 0, false>, (const void *)stream_kernel<GU, N, 1, false>, \
+     (const void *)stream_kernel<GU, N, 2, false>}
+    static const void *const join_fns[4] = {
+        (const void *)stream_kernel<false, 1, 0, true>, (const void *)stream_kernel<false, 2, 0, true>,
+        (const void *)stream_kernel<false, 3, 0, true>, (const void *)stream_kernel<false, 4, 0, true>};
     static const void *const fns[2][4][3] = {
         {MOE_STREAM_FN(false, 1), MOE_STREAM_FN(false, 2), MOE_STREAM_FN(false, 3), MOE_STREAM_FN(false, 4)},
         {MOE_STREAM_FN(true, 1), MOE_STREAM_FN(true, 2), MOE_STREAM_FN(true, 3), MOE_STREAM_FN(true, 4)}};
 #undef MOE_STREAM_FN
-    const void *fn = fns[gateup ? 1 : 0][npi - 1][mode];
-    static bool attr_done[24] = {};
-    const int which = ((gateup ? 4 : 0) + npi - 1) * 3 + mode;
+    const void *fn = join ? join_fns[npi - 1] : fns[gateup ? 1 : 0][npi - 1][mode];
+    static bool attr_done[28] = {};
+    const int which = join ? 24 + npi - 1 : ((gateup ? 4 : 0) + npi - 1) * 3 + mode;
     if (!attr_done[which]) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
@@ -522,7 +607,9 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, hipStream_t s)
     const int grid = num_cus();
     int tile_i = (int)tile;
     StreamArgs args = a;
-    void *params[] = {&args, &tile_i};
+    JoinArgs jargs = {};
+    if (join) jargs = *join;
+    void *params[] = {&args, &tile_i, &jargs};
     hipError_t le = launch_timed(fn, dim3(grid), dim3(kThreads), params, lds, s, gateup ? 2 : 4);
     if (le != hipSuccess) return le;
     return hipGetLastError();

@@ -162,6 +162,17 @@ class Oracle:
                  l_target, w_expert, vram_left, _p(b), _p(tc), _p(tg))
         return int(tau), int(b[0]), tc, tg
 
+    def cache_plan(self, s, in_use, slot_table, C: int, K: int, tau: int, budget: int):
+        """One planning step of the cache manager; returns (new_slot_table, evict_list, fetch_list, fetch_slot)."""
+        s, in_use = _c(s, np.int32), _c(in_use, np.int32)
+        tab = np.array(slot_table, dtype=np.int32)
+        N = s.shape[0]
+        ev, fl, fs = (np.full(max(N, 1), -1, dtype=np.int32) for _ in range(3))
+        ne, nf = np.zeros(1, dtype=np.int32), np.zeros(1, dtype=np.int32)
+        self._lib.oracle_cache_plan(_p(s), _p(in_use), _p(tab), N, C, K, tau, budget, _p(ev), _p(ne), _p(fl), _p(fs),
+                                    _p(nf))
+        return tab, ev[:int(ne[0])].copy(), fl[:int(nf[0])].copy(), fs[:int(nf[0])].copy()
+
     def verify_layer(self, hidden, router_w, router_bias, slot_table, w_gate, w_up, w_down, k: int,
                      sh_gate=None, sh_up=None, sh_down=None) -> LayerResult:
         hidden = _c(hidden, np.uint16)

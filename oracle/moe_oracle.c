@@ -40,6 +40,17 @@
  * the smaller tau; b counts the experts with a non-zero frequency; both
  * constraints are "<=" as printed; no feasible tau gives K.
  *
+ * And one planning step of the utility-guided cache manager for one layer
+ * (Sec. 3.4 "Utility-Guided Prefetching / Eviction"; appendix on the engine:
+ * frozen experts): evict the residents whose utility fell below tau, then
+ * fetch the non-resident experts of utility >= tau, level K first, into the
+ * free slots.  Readings: inside a level requests are served in ascending
+ * expert id (the order the estimator emits them); every resident below tau is
+ * evicted, not only as many as needed; an expert in use (frozen, the K+1 tag)
+ * is never evicted; fetched expert j takes the j-th free slot in ascending
+ * slot order; at most `budget` experts are fetched (the balancer's I/O and
+ * memory limits expressed as a count).
+ *
  * Pinned by tests/test_oracle_pins.py (brute-force dense evaluation in
  * numpy, textbook SwiGLU through torch's own linear/silu, closed forms,
  * the worked example of App. C.1, invariants).  No function here is
@@ -301,4 +312,47 @@ int oracle_balance_threshold(const int32_t *f, const int32_t *n_tau, const doubl
         }
     }
     return best < 0 ? K : best;
+}
+
+/* ---------------------------------------------------------------------------
+ * Cache manager, one planning step for one layer (Sec. 3.4; appendix on the
+ * execution engine).  s[N]: utilities; in_use[N]: non-zero = frozen;
+ * slot_table[N]: expert -> slot or -1, updated in place; C slots.
+ *   evict_list  : evicted experts, ascending utility, ascending id inside a utility
+ *   fetch_list  : fetched experts, descending utility (K .. tau), ascending id inside a level
+ *   fetch_slot  : the slot each fetched expert receives
+ * ------------------------------------------------------------------------- */
+void oracle_cache_plan(const int32_t *s, const int32_t *in_use, int32_t *slot_table, int N, int C, int K,
+                       int tau, int budget, int32_t *evict_list, int32_t *n_evict, int32_t *fetch_list,
+                       int32_t *fetch_slot, int32_t *n_fetch)
+{
+    int ne = 0, nf = 0;
+    /* utility-guided eviction */
+    for (int level = 0; level < tau; ++level)
+        for (int i = 0; i < N; ++i)
+            if (slot_table[i] >= 0 && !in_use[i] && s[i] == level) evict_list[ne++] = i;
+    for (int j = 0; j < ne; ++j) slot_table[evict_list[j]] = -1;
+    /* free slots, ascending */
+    int *slot_free = (int *)malloc((size_t)(C > 0 ? C : 1) * sizeof(int));
+    for (int c = 0; c < C; ++c) slot_free[c] = 1;
+    for (int i = 0; i < N; ++i)
+        if (slot_table[i] >= 0 && slot_table[i] < C) slot_free[slot_table[i]] = 0;
+    /* utility-guided prefetching: levels K down to tau, request order inside a level */
+    int next_slot = 0;
+    for (int level = K; level >= tau && level >= 0; --level) {
+        for (int i = 0; i < N; ++i) {
+            if (slot_table[i] >= 0 || s[i] != level) continue;
+            if (nf >= budget) continue;
+            while (next_slot < C && !slot_free[next_slot]) ++next_slot;
+            if (next_slot >= C) continue;
+            slot_free[next_slot] = 0;
+            slot_table[i] = next_slot;
+            fetch_list[nf] = i;
+            fetch_slot[nf] = next_slot;
+            ++nf;
+        }
+    }
+    free(slot_free);
+    *n_evict = ne;
+    *n_fetch = nf;
 }

@@ -612,3 +612,55 @@ def pin_balancer_constraints_and_limits(O):
 
 
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]
+
+
+# ---------------------------------------------------------------------------
+# Utility-guided cache manager, one planning step (Sec. 3.4; appendix on the engine)
+# ---------------------------------------------------------------------------
+def pin_cache_plan_hand_example(O):
+    g = read_golden("cache_plan_example.txt")
+    ints = lambda k: np.array([int(v) for v in g[k]], dtype=np.int32)
+    tab, ev, fl, fs = O.cache_plan(ints("utility"), ints("in_use"), ints("slot_before"), 4, 4, 2, 3)
+    assert ev.tolist() == ints("evict").tolist() and fl.tolist() == ints("fetch").tolist()
+    assert fs.tolist() == ints("fetch_slot").tolist() and tab.tolist() == ints("slot_after").tolist()
+    # a budget of one fetch takes only the first request of the highest level
+    tab, ev, fl, fs = O.cache_plan(ints("utility"), ints("in_use"), ints("slot_before"), 4, 4, 2, 1)
+    assert fl.tolist() == [0] and fs.tolist() == [0] and tab.tolist() == [0, -1, 1, -1, 3, -1, -1, -1]
+
+
+def pin_cache_plan_invariants_and_sorted_reference(O):
+    """Random states: frozen experts are never evicted; exactly the unfrozen residents below tau are;
+    the table stays one-to-one and within C; what is fetched is the head of the candidates sorted by
+    (utility descending, id ascending) by a library sort, cut at the free slots and the budget; slots
+    are handed out ascending; nothing is both evicted and fetched; every unfrozen resident after the
+    step has utility >= tau."""
+    rng = np.random.default_rng(17)
+    for trial in range(300):
+        N, K = int(rng.integers(1, 40)), int(rng.integers(1, 7))
+        C = int(rng.integers(0, N + 3))
+        s = rng.integers(0, K + 1, size=N).astype(np.int32)
+        tab = np.full(N, -1, dtype=np.int32)
+        res = rng.permutation(N)[:int(rng.integers(0, min(N, C) + 1))]
+        tab[res] = rng.permutation(C)[:len(res)]
+        in_use = ((rng.random(N) < 0.2) & (tab >= 0)).astype(np.int32)
+        tau, budget = int(rng.integers(0, K + 2)), int(rng.integers(0, N + 1))
+        new, ev, fl, fs = O.cache_plan(s, in_use, tab, C, K, tau, budget)
+        want_ev = sorted([i for i in range(N) if tab[i] >= 0 and not in_use[i] and s[i] < tau], key=lambda i: (s[i], i))
+        assert ev.tolist() == want_ev
+        kept = [i for i in range(N) if tab[i] >= 0 and i not in want_ev]
+        free = sorted(set(range(C)) - {int(tab[i]) for i in kept})
+        cand = sorted([i for i in range(N) if (tab[i] < 0 or i in want_ev) and tau <= s[i] <= K], key=lambda i: (-s[i], i))
+        # (an expert evicted in this step has utility < tau, so it is never a candidate)
+        n = min(len(cand), len(free), budget)
+        assert fl.tolist() == cand[:n] and fs.tolist() == free[:n]
+        want = tab.copy()
+        want[want_ev] = -1
+        want[cand[:n]] = free[:n]
+        assert np.array_equal(new, want)
+        held = new[new >= 0]
+        assert len(set(held.tolist())) == len(held) and (len(held) == 0 or held.max() < C)
+        assert all(s[i] >= tau or in_use[i] for i in range(N) if new[i] >= 0)
+        assert not set(ev.tolist()) & set(fl.tolist())
+
+
+ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

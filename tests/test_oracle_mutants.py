@@ -50,6 +50,14 @@ MUTANTS = {
     "bal_ties_to_larger": ("if (best < 0 || obj < best_f) {", "if (best < 0 || obj <= best_f) {"),
     "bal_fallback_one": ("return best < 0 ? K : best;", "return best < 0 ? 1 : best;"),
     "bal_tau_from_zero": ("for (int tau = 1; tau <= K; ++tau) {\n        double tc", "for (int tau = 0; tau <= K; ++tau) {\n        double tc"),
+    "plan_evicts_frozen": ("if (slot_table[i] >= 0 && !in_use[i] && s[i] == level) evict_list[ne++] = i;", "if (slot_table[i] >= 0 && s[i] == level) evict_list[ne++] = i;"),
+    "plan_evicts_at_threshold": ("for (int level = 0; level < tau; ++level)", "for (int level = 0; level <= tau; ++level)"),
+    "plan_fetch_low_levels_first": ("for (int level = K; level >= tau && level >= 0; --level) {", "for (int level = tau < 0 ? 0 : tau; level <= K; ++level) {"),
+    "plan_fetch_below_threshold": ("for (int level = K; level >= tau && level >= 0; --level) {", "for (int level = K; level >= tau - 1 && level >= 0; --level) {"),
+    "plan_ignores_budget": ("            if (nf >= budget) continue;\n", ""),
+    "plan_reuses_taken_slot": ("            slot_free[next_slot] = 0;\n            slot_table[i] = next_slot;", "            slot_table[i] = next_slot;"),
+    "plan_keeps_evicted_in_table": ("    for (int j = 0; j < ne; ++j) slot_table[evict_list[j]] = -1;\n", ""),
+    "plan_refetches_residents": ("if (slot_table[i] >= 0 || s[i] != level) continue;", "if (s[i] != level) continue;"),
     "descending_order_lost": ("topk_idx[(size_t)t * k + j] = best;", "topk_idx[(size_t)t * k + (k - 1 - j)] = best;"),
 }
 

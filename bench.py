@@ -231,6 +231,48 @@ def main():
                "note": "one launch advances all layers by one inference step and counts n(tau)",
                "balancer": {"kernel": "balance_kernel", "avg_us": round(bal_ms * 1e3 / bal_n - ev_us, 2),
                             "avg_us_event_pair": round(bal_ms * 1e3 / bal_n, 2), "bound": "latency"}}
+        # ... and the cache manager: one planning step for all layers, then the copy of 4 fetched experts
+        # of one layer from a full expert store (device memory here) into pool slots
+        if shape.C >= 4:
+            d_ev = torch.zeros((L_est, shape.E), **i32)
+            d_fl, d_fs = torch.zeros((L_est, shape.C), **i32), torch.zeros((L_est, shape.C), **i32)
+            d_ne, d_nf = torch.zeros(L_est, **i32), torch.zeros(L_est, **i32)
+            tab0 = d_tab.clone()
+            n_plan = 100
+            B.moe_profile_enable(True)
+            for t in range(n_plan):
+                d_tab.copy_(tab0)
+                B.moe_cache_plan(st[1], None, d_tab, d_tau, None, L_est, shape.E, shape.C, K_est, d_ev, d_ne, d_fl,
+                                 d_fs, d_nf)
+            torch.cuda.synchronize()
+            B.moe_profile_enable(False)
+            plan_ms, plan_n = B.moe_profile_read(B.KERNEL_CACHE_PLAN)
+            n_move = 4
+            store = [torch.empty((n_move * 3, *w.shape[1:]), dtype=w.dtype, device="cuda").normal_()
+                     for w in (dev_layers[0].w_gate, dev_layers[0].w_up, dev_layers[0].w_down)]
+            mv_list = torch.arange(0, n_move * 3, 3, **i32)
+            mv_slot = torch.arange(n_move, **i32)
+            mv_n = torch.full((1,), n_move, **i32)
+            d0 = dev_layers[0]
+            saved = [w[:n_move].clone() for w in (d0.w_gate, d0.w_up, d0.w_down)]
+            B.moe_pool_load(*store, d0.w_gate, d0.w_up, d0.w_down, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F)
+            torch.cuda.synchronize()
+            B.moe_profile_enable(True)
+            for t in range(20):
+                B.moe_pool_load(*store, d0.w_gate, d0.w_up, d0.w_down, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F)
+            torch.cuda.synchronize()
+            B.moe_profile_enable(False)
+            load_ms, load_n = B.moe_profile_read(B.KERNEL_POOL_LOAD)
+            for w, sv in zip((d0.w_gate, d0.w_up, d0.w_down), saved):
+                w[:n_move].copy_(sv)           # the pools go back to what the layer needs
+            load_us = load_ms * 1e3 / load_n - ev_us
+            moved = n_move * 6 * shape.H * shape.F
+            est["cache_manager"] = {
+                "plan_kernel": {"avg_us": round(plan_ms * 1e3 / plan_n - ev_us, 2), "layers": L_est, "bound": "latency"},
+                "load_kernel": {"avg_us": round(load_us, 2), "experts": n_move, "bytes_moved": moved,
+                                "bound": "hbm", "achieved_GBs_read_plus_write": round(2 * moved / load_us / 1e3, 1),
+                                "frac_of_8TBs": round(2 * moved / load_us / 1e3 / HBM_PEAK_GBS, 4),
+                                "store": "device memory"}}
         if not args.no_cpu_baseline:
             import oracle
             z = np.zeros(shape.E, dtype=np.int32)

@@ -191,6 +191,37 @@ int moe_balance_threshold(const int32_t *f, const int32_t *n_tau, const double *
                           int N, int K, int gamma, int k, const moe_balance_params_t *params, int32_t *tau_out,
                           int32_t *b_out, void *stream);
 
+/* Sec. 3.4 (utility-guided prefetching and eviction) and the appendix on the
+ * execution engine: one planning step of the cache manager for L layers, one
+ * launch.  For each layer l, with tau = tau[l]:
+ *   evicted    = resident experts (slot_table >= 0) with s < tau that are not
+ *                in use (in_use != 0 marks the frozen experts; NULL = none),
+ *                listed by ascending utility, ascending id inside a utility;
+ *   fetched    = non-resident experts with tau <= s <= K, level K first,
+ *                ascending id inside a level, as many as there are free slots
+ *                (after the evictions) and at most budget[l] (NULL = no limit);
+ *   fetch_slot = the free slots in ascending order, one per fetched expert;
+ *   slot_table is updated in place (evicted -> -1, fetched -> their slot).
+ * s, in_use, slot_table [L,N] int32; tau, budget, n_evict, n_fetch [L];
+ * evict_list [L,N]; fetch_list, fetch_slot [L,C].  N <= 512, C <= 1024,
+ * K <= 64.  The weights do not move here: see moe_pool_load. */
+int moe_cache_plan(const int32_t *s, const int32_t *in_use, int32_t *slot_table, const int32_t *tau,
+                   const int32_t *budget, int L, int N, int C, int K, int32_t *evict_list, int32_t *n_evict,
+                   int32_t *fetch_list, int32_t *fetch_slot, int32_t *n_fetch, void *stream);
+
+/* Moves the fetched experts of ONE layer into their slots: for j < *n_fetch,
+ * pool_x[fetch_slot[j]] = store_x[fetch_list[j]] for x in gate, up [.,F,H] and
+ * down [.,H,F] (bf16).  store_*: every expert of the layer, in device memory
+ * or in pinned host memory mapped into the device; pool_*: the slot-major
+ * pools that moe_verify_layer reads.  fetch_list, fetch_slot, n_fetch: that
+ * layer's rows of moe_cache_plan's outputs (device).  max_fetch (host): upper
+ * bound of *n_fetch used to size the launch (entries beyond *n_fetch do
+ * nothing).  One launch on `stream`; launched on a stream of its own it
+ * overlaps with other layers' verify steps.  F*H*2 a multiple of 16. */
+int moe_pool_load(const void *store_gate, const void *store_up, const void *store_down, void *pool_gate,
+                  void *pool_up, void *pool_down, const int32_t *fetch_list, const int32_t *fetch_slot,
+                  const int32_t *n_fetch, int max_fetch, int H, int F, void *stream);
+
 /* Measurement aid (host-side state only; not part of the layer's arithmetic).
  * While enabled, every kernel the library launches is bracketed by a pair of
  * HIP events recorded on the caller's stream.  kind: MOE_KERNEL_*.
@@ -200,7 +231,7 @@ int moe_balance_threshold(const int32_t *f, const int32_t *n_tau, const double *
  * caller must have synchronised the stream.  total_ms, launches: host. */
 enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2 /* gate/up (and down when fused) */,
        MOE_KERNEL_COMBINE = 3, MOE_KERNEL_DOWN = 4, MOE_KERNEL_ESTIMATOR = 5, MOE_KERNEL_BALANCER = 6,
-       MOE_KERNEL_KINDS = 7 };
+       MOE_KERNEL_CACHE_PLAN = 7, MOE_KERNEL_POOL_LOAD = 8, MOE_KERNEL_KINDS = 9 };
 int moe_profile_enable(int on);
 int moe_profile_read(int kind, double *total_ms, int *launches);
 const char *moe_profile_kernel_name(int kind);

@@ -50,6 +50,10 @@ class BalanceParams(ctypes.Structure):
 
 _lib.moe_balance_threshold.argtypes = [_vp] * 4 + [_i] * 5 + [ctypes.POINTER(BalanceParams), _vp, _vp, _vp]
 _lib.moe_balance_threshold.restype = _i
+_lib.moe_cache_plan.argtypes = [_vp] * 5 + [_i] * 4 + [_vp] * 6
+_lib.moe_cache_plan.restype = _i
+_lib.moe_pool_load.argtypes = [_vp] * 9 + [_i] * 3 + [_vp]
+_lib.moe_pool_load.restype = _i
 _lib.moe_utility_init.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]
 _lib.moe_utility_update.argtypes = [_vp] * 7 + [_i] * 5 + [_vp]
 for _f in ("moe_utility_init", "moe_utility_update", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk", "moe_expert_histogram",
@@ -64,9 +68,9 @@ _lib.moe_profile_event_overhead.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_dou
 _lib.moe_profile_event_overhead.restype = _i
 _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
-KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_BALANCER, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6, 7
+KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_BALANCER, KERNEL_CACHE_PLAN, KERNEL_POOL_LOAD, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
 
-EXPORTS = ("moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
+EXPORTS = ("moe_cache_plan", "moe_pool_load", "moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
 
 
@@ -208,6 +212,22 @@ def moe_balance_threshold(f, n_tau, r_c, r_g, L, N, K, gamma, k, params: Balance
     rc = _lib.moe_balance_threshold(_ptr(f), _ptr(n_tau), _ptr(r_c), _ptr(r_g), L, N, K, gamma, k,
                                     ctypes.byref(params), _ptr(tau_out), _ptr(b_out), _stream(stream))
     return _check(rc, "moe_balance_threshold", check)
+
+
+def moe_cache_plan(s, in_use, slot_table, tau, budget, L, N, C, K, evict_list, n_evict, fetch_list, fetch_slot,
+                   n_fetch, stream=None, check=True) -> int:
+    rc = _lib.moe_cache_plan(_ptr(s), _ptr(in_use), _ptr(slot_table), _ptr(tau), _ptr(budget), L, N, C, K,
+                             _ptr(evict_list), _ptr(n_evict), _ptr(fetch_list), _ptr(fetch_slot), _ptr(n_fetch),
+                             _stream(stream))
+    return _check(rc, "moe_cache_plan", check)
+
+
+def moe_pool_load(store_gate, store_up, store_down, pool_gate, pool_up, pool_down, fetch_list, fetch_slot, n_fetch,
+                  max_fetch, H, F, stream=None, check=True) -> int:
+    rc = _lib.moe_pool_load(_ptr(store_gate), _ptr(store_up), _ptr(store_down), _ptr(pool_gate), _ptr(pool_up),
+                            _ptr(pool_down), _ptr(fetch_list), _ptr(fetch_slot), _ptr(n_fetch), max_fetch, H, F,
+                            _stream(stream))
+    return _check(rc, "moe_pool_load", check)
 
 
 # ---------------------------------------------------------------------------

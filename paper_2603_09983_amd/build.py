@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_spac.so")
-SOURCES = ["api.hip", "route.hip", "ffn.hip", "stream.hip", "estimator.hip", "balancer.hip"]
+SOURCES = ["api.hip", "route.hip", "ffn.hip", "stream.hip", "estimator.hip", "balancer.hip", "cache.hip"]
 HEADERS = [os.path.join(CSRC, "moe_internal.h"), os.path.join(ROOT, "include", "moe_spac.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-fp32 instruction selection is switched off for every kernel of this library

@@ -128,6 +128,8 @@ extern "C" const char *moe_profile_kernel_name(int kind)
     case MOE_KERNEL_DOWN: return "ffn_down";
     case MOE_KERNEL_ESTIMATOR: return "utility_update_kernel";
     case MOE_KERNEL_BALANCER: return "balance_kernel";
+    case MOE_KERNEL_CACHE_PLAN: return "plan_kernel";
+    case MOE_KERNEL_POOL_LOAD: return "load_kernel";
     default: return "?";
     }
 }

@@ -1,0 +1,113 @@
+"""Parity of the cache-manager kernels (Sec. 3.4) with the CPU oracle: the planning step bit-exact
+(lists, counts, new slot table) over random and edge states, and the whole between-steps chain:
+plan -> load the fetched experts into the pools -> the next verify step with the new slot table
+gives the oracle's layer for that table."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_09983_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _random_state(rng, L, N, C, K, frozen_p=0.2):
+    s = rng.integers(0, K + 1, size=(L, N)).astype(np.int32)
+    tab = np.full((L, N), -1, dtype=np.int32)
+    for l in range(L):
+        res = rng.permutation(N)[:int(rng.integers(0, min(N, C) + 1))]
+        tab[l, res] = rng.permutation(C)[:len(res)]
+    in_use = ((rng.random((L, N)) < frozen_p) & (tab >= 0)).astype(np.int32)
+    tau = rng.integers(0, K + 2, size=L).astype(np.int32)
+    budget = rng.integers(0, N + 1, size=L).astype(np.int32)
+    return s, in_use, tab, tau, budget
+
+
+def _plan(B, s, in_use, tab, tau, budget, C, K):
+    L, N = s.shape
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_tab = _dev(tab)
+    ev, fl, fs = torch.full((L, N), -9, **i32), torch.full((L, max(C, 1)), -9, **i32), torch.full((L, max(C, 1)), -9, **i32)
+    ne, nf = torch.full((L,), -9, **i32), torch.full((L,), -9, **i32)
+    B.moe_cache_plan(_dev(s), None if in_use is None else _dev(in_use), d_tab, _dev(tau),
+                     None if budget is None else _dev(budget), L, N, C, K, ev, ne, fl, fs, nf)
+    torch.cuda.synchronize()
+    return d_tab.cpu().numpy(), ev.cpu().numpy(), ne.cpu().numpy(), fl.cpu().numpy(), fs.cpu().numpy(), nf.cpu().numpy()
+
+
+@pytest.mark.parametrize("L,N,C,K", [(24, 64, 32, 4), (3, 8, 4, 4), (5, 130, 40, 7), (2, 512, 1024, 64), (4, 60, 0, 3),
+                                     (6, 64, 64, 1), (1, 1, 1, 1)])
+def test_plan_parity(L, N, C, K):
+    from paper_2603_09983_amd import binding as B
+    rng = np.random.default_rng(31 * N + C + K)
+    for trial in range(4):
+        s, in_use, tab, tau, budget = _random_state(rng, L, N, C, K)
+        if trial == 1:
+            budget = None
+        if trial == 2:
+            in_use = None
+        new, ev, ne, fl, fs, nf = _plan(B, s, in_use, tab, tau, budget, C, K)
+        for l in range(L):
+            o_new, o_ev, o_fl, o_fs = oracle.cache_plan(s[l], np.zeros(N, dtype=np.int32) if in_use is None else in_use[l],
+                                                        tab[l], C, K, int(tau[l]), N + C if budget is None else int(budget[l]))
+            assert ne[l] == len(o_ev) and nf[l] == len(o_fl), (l, ne[l], len(o_ev), nf[l], len(o_fl))
+            assert ev[l, :ne[l]].tolist() == o_ev.tolist()
+            assert fl[l, :nf[l]].tolist() == o_fl.tolist() and fs[l, :nf[l]].tolist() == o_fs.tolist()
+            assert np.array_equal(new[l], o_new)
+
+
+def test_plan_errors():
+    from paper_2603_09983_amd import binding as B
+    i32 = dict(dtype=torch.int32, device="cuda")
+    t = torch.zeros((1, 8), **i32)
+    one = torch.zeros(1, **i32)
+    assert B.moe_cache_plan(t, None, t, one, None, 1, 8, 4, 4, t, one, t, t, one, check=False) == B.OK
+    assert B.moe_cache_plan(t, None, t, one, None, 1, 513, 4, 4, t, one, t, t, one, check=False) == B.ERR_SHAPE
+    assert B.moe_cache_plan(t, None, t, None, None, 1, 8, 4, 4, t, one, t, t, one, check=False) == B.ERR_NULL
+    torch.cuda.synchronize()
+
+
+def test_plan_load_then_verify_step():
+    """Between two verify steps: utilities change, the manager evicts and fetches, the fetched weights
+    are copied from the full expert store into the pools, and the next verify step uses the new
+    table.  The layer output must be the oracle's for the NEW table (bit-exact routing outputs,
+    FFN within tolerance), and the untouched slots must still hold their old experts."""
+    from paper_2603_09983_amd import binding as B
+    import gpu_util as G
+    rec = synth.small_recipe("cache_chain", 77, T=9, H=256, E=64, k=6, F=256, C=24, n_shared=1, F_shared=128)
+    li = synth.make_layer(rec)
+    d = G.upload(li)
+    buf = G.run_layer(d)
+    G.check_against_oracle(li, buf, tag="before")
+    E, C, K = 64, 24, 4
+    rng = np.random.default_rng(9)
+    s = rng.integers(0, K + 1, size=(1, E)).astype(np.int32)
+    in_use = np.zeros((1, E), dtype=np.int32)
+    resident = np.flatnonzero(li.slot_table >= 0)
+    in_use[0, resident[:3]] = 1
+    tau = np.array([2], dtype=np.int32)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_tab = _dev(li.slot_table.reshape(1, E))
+    ev, fl, fs = torch.zeros((1, E), **i32), torch.zeros((1, C), **i32), torch.zeros((1, C), **i32)
+    ne, nf = torch.zeros(1, **i32), torch.zeros(1, **i32)
+    B.moe_cache_plan(_dev(s), _dev(in_use), d_tab, _dev(tau), None, 1, E, C, K, ev, ne, fl, fs, nf)
+    store = [_dev(w.view(np.int16)) for w in (li.w_gate, li.w_up, li.w_down)]   # every expert of the layer, [E,...]
+    B.moe_pool_load(*store, d.w_gate, d.w_up, d.w_down, fl[0], fs[0], nf, C, 256, 256)
+    torch.cuda.synchronize()
+    o_tab, o_ev, o_fl, o_fs = oracle.cache_plan(s[0], in_use[0], li.slot_table, C, K, 2, E + C)
+    assert int(nf.item()) == len(o_fl) > 0 and int(ne.item()) == len(o_ev) > 0
+    assert np.array_equal(d_tab.cpu().numpy()[0], o_tab)
+    # pools: fetched slots hold the fetched experts, kept slots their old ones
+    pg = d.w_gate.view(torch.int16).cpu().numpy().view(np.uint16)
+    for e in np.flatnonzero(o_tab >= 0):
+        assert np.array_equal(pg[o_tab[e]], li.w_gate[e]), e
+    # next verify step with the new table
+    li.slot_table = o_tab.copy()
+    d.slot_table = d_tab[0].contiguous()
+    buf = G.run_layer(d, buf)
+    G.check_against_oracle(li, buf, tag="after")

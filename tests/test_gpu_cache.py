@@ -111,3 +111,56 @@ def test_plan_load_then_verify_step():
     d.slot_table = d_tab[0].contiguous()
     buf = G.run_layer(d, buf)
     G.check_against_oracle(li, buf, tag="after")
+
+
+def test_full_control_loop_three_steps():
+    """verify step -> histogram -> utility update (+ n(tau)) -> threshold -> cache plan -> weight load
+    -> next verify step, three times round, every stage against the oracle's own chain."""
+    from paper_2603_09983_amd import binding as B
+    import gpu_util as G
+    E, C, K, gamma, k = 64, 24, 4, 8, 6
+    rec = synth.small_recipe("control_loop", 91, T=gamma + 1, H=256, E=E, k=k, F=256, C=C)
+    li = synth.make_layer(rec)
+    d = G.upload(li)
+    store = [_dev(w.view(np.int16)) for w in (li.w_gate, li.w_up, li.w_down)]
+    i32 = dict(dtype=torch.int32, device="cuda")
+    st = [torch.zeros((1, E), **i32) for _ in range(4)]
+    B.moe_utility_init(*st, 1, E, gamma)
+    z, th = np.zeros(E, dtype=np.int32), np.full(E, gamma // 2, dtype=np.int32)
+    o_st = (z.copy(), z.copy(), th.copy(), th.copy())
+    d_tab = _dev(li.slot_table.reshape(1, E))
+    d_n, d_tau = torch.zeros((1, K + 1), **i32), torch.zeros(1, **i32)
+    ev, fl, fs = torch.zeros((1, E), **i32), torch.zeros((1, C), **i32), torch.zeros((1, C), **i32)
+    ne, nf = torch.zeros(1, **i32), torch.zeros(1, **i32)
+    rng = np.random.default_rng(4)
+    r_c = np.sort(rng.random((1, K + 1)), axis=1)
+    r_g = np.ascontiguousarray(np.sort(rng.random((1, K + 1)), axis=1)[:, ::-1])
+    p = dict(t_cpu=40.0, t_gpu=3.0, t_io=2.0, t_draft=600.0, l_target=24, w_expert=6 * 256 * 256, vram_left=12 * 6 * 256 * 256)
+    params = B.BalanceParams(p["t_cpu"], p["t_gpu"], p["t_io"], p["t_draft"], p["l_target"], p["w_expert"], p["vram_left"])
+    o_tab = li.slot_table.copy()
+    buf = None
+    moved = 0
+    for step in range(3):
+        li_t = synth.make_layer(rec, hidden_seed=500 + step)
+        li_t.slot_table = o_tab.copy()
+        d.hidden = G.upload(li_t).hidden
+        d.slot_table = d_tab[0].contiguous()
+        buf = G.run_layer(d, buf)
+        G.check_against_oracle(li_t, buf, tag=f"step{step}")
+        hist = buf.hist.view(1, E)
+        B.moe_utility_update(hist, *st, d_tab, d_n, 1, E, K, 1, 2)
+        B.moe_balance_threshold(hist, d_n, _dev(r_c), _dev(r_g), 1, E, K, gamma, k, params, d_tau)
+        B.moe_cache_plan(st[1], None, d_tab, d_tau, None, 1, E, C, K, ev, ne, fl, fs, nf)
+        B.moe_pool_load(*store, d.w_gate, d.w_up, d.w_down, fl[0], fs[0], nf, C, 256, 256)
+        torch.cuda.synchronize()
+        ref = oracle.layer_from_inputs(li_t)
+        o_st = oracle.utility_step(ref.hist, *o_st, K, 1, 2)
+        n_tau = oracle.prefetch_counts(o_st[1], o_tab, K)
+        tau = oracle.balance_threshold(ref.hist, n_tau, r_c[0], r_g[0], K, gamma, k, **p)[0]
+        o_tab, o_ev, o_fl, o_fs = oracle.cache_plan(o_st[1], np.zeros(E, dtype=np.int32), o_tab, C, K, tau, E + C)
+        assert int(d_tau.item()) == tau, step
+        assert np.array_equal(st[1].cpu().numpy()[0], o_st[1])
+        assert np.array_equal(d_tab.cpu().numpy()[0], o_tab), step
+        assert fl[0, :len(o_fl)].cpu().tolist() == o_fl.tolist() and int(nf.item()) == len(o_fl)
+        moved += len(o_fl) + len(o_ev)
+    assert moved > 0   # the loop did move experts

@@ -202,9 +202,12 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     // it has 32-wide column blocks).  For each piece this lane keeps its global byte offset from the
     // half-tile's first row and its LDS byte offset.  Two tiles are in flight per wavefront (st[0],
     // st[1]); each remembers its own geometry.
+    // (The two-group variants are short of registers: they keep row and column packed in one word
+    // per piece and derive both offsets where they are used.)
+    constexpr bool PACKED = NG == 2;
     u32x4 st[2][NPI];
-    unsigned goff[2][NPI];
-    int loff[2][NPI];
+    unsigned goff[2][PACKED ? 1 : NPI];   // PACKED: unused
+    int loff[2][NPI];                     // PACKED: row << 16 | column
     int st_rs[2] = {-1, -1}, st_K2[2] = {-1, -1};
     auto issue = [&](int s) {
         if (prs != st_rs[s] || pK2 != st_K2[s]) {
@@ -219,8 +222,12 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
                 int off = (pc << 10) + (lane << 4);
                 int row = (int)(((float)(off >> 4) + 0.5f) * inv_d);
                 int col = off - row * prs;
-                goff[s][i] = (unsigned)((row & 7) * pK2 + col);
-                loff[s][i] = row * (prs + kRowPad) + col;
+                if (PACKED) {
+                    loff[s][i] = row << 16 | col;
+                } else {
+                    goff[s][i] = (unsigned)((row & 7) * pK2 + col);
+                    loff[s][i] = row * (prs + kRowPad) + col;
+                }
             }
         }
         const unsigned poff = (unsigned)ppan * (unsigned)prs;
@@ -230,13 +237,18 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
             int pc = i * kWaves + w;
             pc = pc < np ? pc : np - 1;
             const unsigned char *base = (pc << 10) < 8 * prs ? pw0 : pw1;   // uniform
-            st[s][i] = ld_stream(base + (poff + goff[s][i]));
+            const unsigned go = PACKED ? (unsigned)(((loff[s][i] >> 16) & 7) * pK2 + (loff[s][i] & 0xffff))
+                                       : goff[s][i];
+            st[s][i] = ld_stream(base + (poff + go));
         }
     };
     auto park = [&](int s) {
         // (a wavefront's re-read of the last piece lands on that piece's own bytes: same data, no test)
 #pragma unroll
-        for (int i = 0; i < NPI; ++i) *(u32x4 *)(tile_s + loff[s][i]) = st[s][i];
+        for (int i = 0; i < NPI; ++i) {
+            const int lo = PACKED ? (loff[s][i] >> 16) * (st_rs[s] + kRowPad) + (loff[s][i] & 0xffff) : loff[s][i];
+            *(u32x4 *)(tile_s + lo) = st[s][i];
+        }
     };
 
     if (s_cnt > 0) {

@@ -200,6 +200,7 @@ extern "C" int moe_route_topk(const void *hidden, const float *router_w, const f
     a.hidden = hidden; a.router_w = router_w; a.router_bias = router_bias;
     a.T = T; a.H = H; a.E = E; a.k = k;
     a.tagged_logits = (unsigned long long *)(ws + w.tagged);
+    a.tagged_idx = (unsigned long long *)(ws + w.tagged_idx);
     a.epoch = (unsigned *)(ws + w.ctrl) + kCtrlEpoch;
     a.error_flag = (unsigned *)(ws + w.ctrl) + kCtrlError;
     a.topk_idx = topk_idx; a.topk_w = topk_w; a.logits_opt = logits_opt;
@@ -361,6 +362,7 @@ extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const
     r.hidden = hidden; r.router_w = router_w; r.router_bias = router_bias;
     r.T = sh->T; r.H = sh->H; r.E = sh->E; r.k = sh->k;
     r.tagged_logits = (unsigned long long *)(ws + w.tagged);
+    r.tagged_idx = (unsigned long long *)(ws + w.tagged_idx);
     r.epoch = (unsigned *)(ws + w.ctrl) + kCtrlEpoch;
     r.error_flag = (unsigned *)(ws + w.ctrl) + kCtrlError;
     r.topk_idx = topk_idx; r.topk_w = topk_w; r.logits_opt = nullptr; r.hist = hist;

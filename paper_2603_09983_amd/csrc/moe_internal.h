@@ -36,10 +36,13 @@ static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 // The region has a fixed size and sits right behind the control block; moe_workspace_init clears
 // it (no stale entry may carry a future tag).
 constexpr int kTagEntries = 65536;   // 512 KB: T*E of the largest routing call that uses them
+// Behind them, the same kind of entries for the Top-k ids when more than one workgroup ranks
+// (batches above 16 tokens): T*k of them.
+constexpr int kTagIdxEntries = 4096;   // (at most as many as the routing kernel mirrors in LDS)
 
 // Byte offsets of the scratch arrays inside the caller's workspace.
 struct WsLayout {
-    size_t ctrl, tagged, perm, pos, slot_count, slot_offset, active, part, part_sh, act, act_sh, o, o_sh, total;
+    size_t ctrl, tagged, tagged_idx, perm, pos, slot_count, slot_offset, active, part, part_sh, act, act_sh, o, o_sh, total;
 };
 
 // control block words
@@ -56,6 +59,7 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
     size_t o = 0;
     w.ctrl = o;        o += kCtrlBytes;
     w.tagged = o;      o += (size_t)kTagEntries * 8;   // (same place whatever the entry point and shape)
+    w.tagged_idx = o;  o += (size_t)kTagIdxEntries * 8;
     w.perm = o;        o += align256(A * 4);
     w.pos = o;         o += align256(A * 4);
     w.slot_count = o;  o += align256((size_t)(C > 0 ? C : 1) * 4);
@@ -103,6 +107,7 @@ struct RouteArgs {
     unsigned *n_active;        // [1]
     unsigned *error_flag;      // control word set when a bounded wait inside a kernel ran out
     unsigned long long *tagged_logits;   // [T*E] (tag << 32 | value bits)
+    unsigned long long *tagged_idx;      // [T*k] (tag << 32 | expert id), batches above 16 tokens
     unsigned *epoch;           // control word: tag of the last completed call
 };
 

@@ -225,7 +225,7 @@ __device__ void block_post(IdxPtr idx, TabPtr slot_table, int A, int E, int C, i
     }
 }
 
-// dynamic LDS: hist_s[E] tab_s[E] cnt_s[C] off_s[C+1] scan_s[48] sidx_s[cap] idx_s[cap] lg_s[waves*E] sel_s[waves*64]
+// dynamic LDS: hist_s[E] tab_s[E] cnt_s[4C] off_s[C+1] scan_s[48] sidx_s[cap] idx_s[cap] lg_s[waves*E] sel_s[waves*64]
 struct PostLds {
     lds_i32 *hist_s, *tab_s, *cnt_s, *off_s, *scan_s, *sidx_s, *idx_s;
     lds_f32 *lg_s, *sel_s;
@@ -239,11 +239,11 @@ __device__ inline PostLds carve_lds(int *dyn_, int E, int C, int A)
     p.hist_s = dyn;
     p.tab_s = p.hist_s + E;
     p.cnt_s = p.tab_s + E;
-    p.off_s = p.cnt_s + C;
+    p.off_s = p.cnt_s + 4 * C;   // (counters of the general builder, or up to four mask words per slot)
     p.scan_s = p.off_s + C + 1;
     p.sidx_s = p.scan_s + 48;
     p.idx_s = p.sidx_s + cap;
-    p.lg_s = (lds_f32 *)(dyn + ((2 * E + 2 * C + 49 + 2 * cap + 3) & ~3));
+    p.lg_s = (lds_f32 *)(dyn + ((2 * E + 5 * C + 49 + 2 * cap + 3) & ~3));
     p.sel_s = p.lg_s + kRouteWaves * lg_stride(E);
     return p;
 }
@@ -251,21 +251,22 @@ __device__ inline PostLds carve_lds(int *dyn_, int E, int C, int A)
 size_t post_lds_bytes(int E, int C, int A, bool with_topk)
 {
     const int cap = A < kLdsCopy ? A : kLdsCopy;
-    size_t n = (size_t)2 * E + C + (C + 1) + 48 + 2 * cap;
+    size_t n = (size_t)2 * E + 4 * C + (C + 1) + 48 + 2 * cap;
     if (with_topk) n += (size_t)kRouteWaves * lg_stride(E) + kRouteWaves * kMaxK + 4;
     return n * sizeof(int);
 }
 
 constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before workgroup 0 gives up waiting
 
-// Small batches (T <= 32, one thread per assignment and per slot): the tokens of each slot as a
-// bit mask (a token names a slot at most once, the slot table being one-to-one), so counts,
-// offsets and list positions are population counts.  Same outputs as block_post.
+// Small batches (T <= 128, one thread per assignment and per slot): the tokens of each slot as a
+// bit mask of NW = ceil(T/32) words (a token names a slot at most once, the slot table being
+// one-to-one), so counts, offsets and list positions are population counts.  Same outputs as
+// block_post.
 __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, int E, int C, const RouteArgs &r,
                                  lds_i32 *hist_s, lds_i32 *mask_s, lds_i32 *scan_s, lds_i32 *off_s)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-    const int A = T * kk;
+    const int A = T * kk, NW = (T + 31) >> 5;
     const bool valid = tid < A;
     const int tok = valid ? tid / kk : 0;
     int c = -1;
@@ -274,7 +275,9 @@ __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, 
         __hip_atomic_fetch_add(&hist_s[e], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         c = tab_s[e];
         if ((unsigned)c >= (unsigned)C) c = -1;
-        if (c >= 0) __hip_atomic_fetch_or(&mask_s[c], 1 << tok, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (c >= 0)
+            __hip_atomic_fetch_or(&mask_s[c * NW + (tok >> 5)], 1 << (tok & 31), __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_WORKGROUP);
         r.slot_idx[tid] = c;
     }
     const bool miss = valid && c < 0;
@@ -283,7 +286,9 @@ __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, 
     if (lane == 0) scan_s[w] = __popcll(bal);
     __syncthreads();
     // slot `tid`: its token count; prefix sums of (count, count > 0) inside the wavefront
-    const int cntv = tid < C ? __popc((unsigned)mask_s[tid]) : 0;
+    int cntv = 0;
+    if (tid < C)
+        for (int wd = 0; wd < NW; ++wd) cntv += __popc((unsigned)mask_s[tid * NW + wd]);
     int inc_o = cntv, inc_a = cntv > 0 ? 1 : 0;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -335,7 +340,8 @@ __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, 
     if (valid) {
         int p = -1;
         if (c >= 0) {
-            p = off_s[c] + __popc((unsigned)mask_s[c] & ((1u << tok) - 1u));
+            p = off_s[c] + __popc((unsigned)mask_s[c * NW + (tok >> 5)] & ((1u << (tok & 31)) - 1u));
+            for (int wd = 0; wd < (tok >> 5); ++wd) p += __popc((unsigned)mask_s[c * NW + wd]);
             r.perm[p] = tid;
         }
         r.pos[tid] = p;
@@ -379,19 +385,22 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
             if (a.logits_opt) a.logits_opt[q] = acc;
         }
     }
-    if (b != 0) return;
-
-    // ---- workgroup 0: everything after the logits ----
+    // ---- ranking: workgroup b ranks tokens 16b .. 16b+15, one wavefront each ----
+    const int n_rank = (T + kRouteWaves - 1) / kRouteWaves;
+    const bool share_ids = n_rank > 1 && A <= kTagIdxEntries;   // ids handed to workgroup 0 as stamped entries
+    if (b >= (share_ids ? n_rank : 1)) return;
     PostLds L = carve_lds(dyn, E, a.C, A);
-    const bool small = a.slot_table && a.hist && T <= 32 && A <= kRouteThreads && a.C <= kRouteThreads;
-    if (a.slot_table && tid < E) L.tab_s[tid] = tab_v;
-    if (small) {
-        if (tid < E) L.hist_s[tid] = 0;
-        if (tid < a.C) L.cnt_s[tid] = 0;   // (the token masks)
+    const bool small = a.slot_table && a.hist && T <= 128 && A <= kRouteThreads && a.C <= kRouteThreads;
+    if (b == 0) {
+        if (a.slot_table && tid < E) L.tab_s[tid] = tab_v;
+        if (small) {
+            if (tid < E) L.hist_s[tid] = 0;
+            for (int i = tid; i < a.C * ((T + 31) >> 5); i += kRouteThreads) L.cnt_s[i] = 0;   // (the token masks)
+        }
     }
     const bool idx_in_lds = A <= kLdsCopy;
     lds_f32 *lg = L.lg_s + w * lg_stride(E);
-    for (int t = w; t < T; t += kRouteWaves) {
+    for (int t = share_ids ? b * kRouteWaves + w : w; t < T; t += share_ids ? T : kRouteWaves) {
         // wait (a bounded number of polls) until every logit of token t carries the tag
         const unsigned long long *src = a.tagged_logits + (size_t)t * E;
         for (int e0 = 0; e0 < E; e0 += kWave) {
@@ -416,8 +425,38 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
         __builtin_amdgcn_wave_barrier();
         wave_topk_gate(E, a.k, a.topk_idx + (size_t)t * a.k, idx_in_lds ? L.idx_s + t * a.k : nullptr,
                        a.topk_w + (size_t)t * a.k, lg, L.sel_s + w * kMaxK);
+        if (share_ids) {
+            // (LDS operations of one wavefront execute in order: the ids written above are visible)
+            __builtin_amdgcn_wave_barrier();
+            for (int j = lane; j < a.k; j += kWave)
+                __hip_atomic_store(a.tagged_idx + (size_t)t * a.k + j,
+                                   ((unsigned long long)tag << 32) | (unsigned)L.idx_s[t * a.k + j], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
+    if (b != 0) return;
+
+    // ---- workgroup 0: everything after the Top-k ----
     __syncthreads();
+    if (share_ids) {
+        // collect the ids the other workgroups ranked (its own come back the same way)
+        for (int i = tid; i < A; i += kRouteThreads) {
+            unsigned long long v = 0;
+            int polls = 0;
+            for (;;) {
+                v = __hip_atomic_load(a.tagged_idx + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((unsigned)(v >> 32) == tag) break;
+                if (++polls > kSpinLimit) {
+                    atomicOr(a.error_flag, 1u);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            const unsigned e = (unsigned)v;
+            L.idx_s[i] = e < (unsigned)E ? (int)e : 0;   // (a bound that ran out leaves garbage: stay in range)
+        }
+        __syncthreads();
+    }
 
     const int32_t *idx = idx_in_lds ? (const int32_t *)L.idx_s : a.topk_idx;
     if (small) {

@@ -27,9 +27,17 @@
  *     C <= 1024; H and F multiples of 32; H <= 4992; bf16 tensors and `out`
  *     16-byte aligned.
  *   - Two calls that share a workspace must not overlap in time.  A
- *     workspace holds state between calls (a call counter and a region whose
+ *     workspace holds state between calls (a call counter and regions whose
  *     entries are stamped with it): initialise it with moe_workspace_init
- *     over its full size, and again after anything else wrote into it.
+ *     over its full size, and again after anything else wrote into it or
+ *     before using it with a different shape.
+ *   - The routing kernel and the down kernel hand results from one workgroup
+ *     to another inside a launch (stamped entries in the workspace, bounded
+ *     polling).  They are sized to occupy the whole device.  Layer calls on
+ *     different streams of one device are legal, but if they really run at
+ *     the same time the bounded waits can run out (moe_workspace_status then
+ *     reports it, nothing hangs): issue the layer calls of one device in
+ *     stream order.
  *   - The slot table maps distinct resident experts to distinct slots (it is
  *     a cache directory); with two experts on one slot the per-slot lists are
  *     unspecified (every access still stays in bounds).
@@ -74,11 +82,13 @@ int moe_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Synchronous health check: waits for `stream`, then reads the control block.
  * Inside the routing launch one workgroup waits for the logits that the others
- * write to device memory; it polls a bounded number of times and, should that
- * bound ever run out, sets a flag in the control block and finishes with
- * unspecified results instead of waiting for ever.  Returns MOE_OK when no such flag is set,
- * MOE_ERR_LAUNCH when one is (the flag is cleared, the workspace stays usable)
- * or when the copy fails.  workspace: device pointer. */
+ * write to device memory, and at the end of the down launch every workgroup
+ * waits for the per-assignment outputs of the others; each wait polls a
+ * bounded number of times and, should that bound ever run out, sets a flag in
+ * the control block and finishes with unspecified results instead of waiting
+ * for ever.  Returns MOE_OK when no such flag is set, MOE_ERR_LAUNCH when one
+ * is (the flag is cleared, the workspace stays usable) or when the copy
+ * fails.  workspace: device pointer. */
 int moe_workspace_status(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Step 1 -- Sec. 2.2, lines one to three of the MoE equation.

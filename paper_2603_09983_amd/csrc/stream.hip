@@ -75,7 +75,7 @@ __device__ inline uint32_t f32_to_bf16_rne(float f)
 // (two groups); MODE 2: larger batches: two groups per pass, and experts with more than 32 tokens
 // take further passes over the parked tile.
 //
-// JOIN (down kernel, batches of one pass): the weighted sum back into token order (Sec. 2.2 last
+// JOIN (down kernel, batches of up to 32 tokens): the weighted sum back into token order (Sec. 2.2 last
 // line; the join of App. D when `accumulate` is set) rides at the end of the down kernel instead
 // of a launch of its own.  Every per-assignment output goes to memory as ONE 64-bit relaxed atomic
 // store (call number << 32 | fp32 bits); a workgroup that has finished its items takes a strip of 8
@@ -86,7 +86,7 @@ __device__ inline uint32_t f32_to_bf16_rne(float f)
 template <bool GATEUP, int NPI, int MODE, bool JOIN>
 __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes, JoinArgs jn)
 {
-    static_assert(!JOIN || (!GATEUP && MODE == 0), "the join rides on the down kernel of small batches");
+    static_assert(!JOIN || (!GATEUP && MODE < 2), "the join rides on the down kernel of batches up to 32 tokens");
     constexpr int NG = MODE == 0 ? 1 : 2;   // token groups of 16 multiplied per pass
     constexpr bool MULTIPASS = MODE == 2;
     constexpr int RPI = GATEUP ? 8 : 16;    // output rows per item
@@ -581,9 +581,10 @@ size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup)
 
 bool stream_can_join(const StreamArgs &d)
 {
-    // one pass of tokens; the strip's entries (T x 8 columns x sources) fit the tile buffer
+    // up to 32 tokens (measured at 128: polling T x 8 x sources entries per strip costs more than the
+    // combine launch it saves); the strip's entries fit the tile buffer
     const size_t tile = (size_t)16 * (2 * (d.KP > d.KP_sh ? d.KP : d.KP_sh) + kRowPad);
-    return d.T <= 16 && d.R % 8 == 0 && (size_t)d.T * 8 * (d.k + d.n_shared) * 4 <= tile;
+    return d.T <= 32 && d.R % 8 == 0 && (size_t)d.T * 8 * (d.k + d.n_shared) * 4 <= tile;
 }
 
 hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join, hipStream_t s)
@@ -601,16 +602,16 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join,
 #define MOE_STREAM_FN(GU, N)                                                                     \
     {(const void *)stream_kernel<GU, N, 0, false>, (const void *)stream_kernel<GU, N, 1, false>, \
      (const void *)stream_kernel<GU, N, 2, false>}
-    static const void *const join_fns[4] = {
-        (const void *)stream_kernel<false, 1, 0, true>, (const void *)stream_kernel<false, 2, 0, true>,
-        (const void *)stream_kernel<false, 3, 0, true>, (const void *)stream_kernel<false, 4, 0, true>};
+#define MOE_JOIN_FN(N) {(const void *)stream_kernel<false, N, 0, true>, (const void *)stream_kernel<false, N, 1, true>}
+    static const void *const join_fns[4][2] = {MOE_JOIN_FN(1), MOE_JOIN_FN(2), MOE_JOIN_FN(3), MOE_JOIN_FN(4)};
+#undef MOE_JOIN_FN
     static const void *const fns[2][4][3] = {
         {MOE_STREAM_FN(false, 1), MOE_STREAM_FN(false, 2), MOE_STREAM_FN(false, 3), MOE_STREAM_FN(false, 4)},
         {MOE_STREAM_FN(true, 1), MOE_STREAM_FN(true, 2), MOE_STREAM_FN(true, 3), MOE_STREAM_FN(true, 4)}};
 #undef MOE_STREAM_FN
-    const void *fn = join ? join_fns[npi - 1] : fns[gateup ? 1 : 0][npi - 1][mode];
-    static bool attr_done[28] = {};
-    const int which = join ? 24 + npi - 1 : ((gateup ? 4 : 0) + npi - 1) * 3 + mode;
+    const void *fn = join ? join_fns[npi - 1][mode] : fns[gateup ? 1 : 0][npi - 1][mode];
+    static bool attr_done[36] = {};
+    const int which = join ? 24 + (npi - 1) * 3 + mode : ((gateup ? 4 : 0) + npi - 1) * 3 + mode;
     if (!attr_done[which]) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;

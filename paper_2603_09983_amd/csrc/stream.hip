@@ -1,23 +1,25 @@
-// Weight-streaming kernels of the expert FFN for verification batches of up to
-// 16 tokens (the regime of a single request with gamma <= 15 draft tokens):
+// Weight-streaming kernels of the expert FFN of a verification batch (tuned
+// for the regime of a single request, gamma <= 15 draft tokens; larger batches
+// take variants of the same kernels):
 //      act = silu(W_gate x) * (W_up x)        (gate/up kernel)
 //      o   = W_down act                       (down kernel)
 // per (token, resident expert) pair -- Sec. 2.2 last line, experts as in App. D.
 //
 // Both kernels are bound by the bf16 weight bytes, which must come from HBM
 // once per layer call.  Measured on MI355X, only loads in which a wavefront
-// reads 1 KB of consecutive bytes and the eight wavefronts of a workgroup read
+// reads 1 KB of consecutive bytes and the wavefronts of a workgroup read
 // neighbouring kilobytes reach the HBM ceiling; the MFMA operand layout read
 // straight from row-major weights (16 rows x 64 B per instruction) gets about
 // two thirds of it.  So a workgroup streams a tile of 16 weight rows x up to
 // 2048 columns (contiguous 64 KB for H = 2048) as 1 KB pieces into registers,
 // parks it in LDS, and then every wavefront multiplies ITS share of the
 // contraction range (32-wide column blocks dealt round-robin) for all 16 rows
-// with MFMA 16x16x32 bf16; the eight partial 16x16 results are added through
-// LDS in a fixed order.  Tokens sit on the MFMA N axis (16 columns, zero beyond
-// the routed ones), so the arithmetic is free and nothing is read twice.
+// with MFMA 16x16x32 bf16; the sixteen partial 16x16 results are added through
+// LDS in a fixed order.  Tokens sit on the MFMA N axis (16 columns per group,
+// zero beyond the routed ones), so the arithmetic is free and nothing is read
+// twice.
 //
-// Work is a flat list of items (expert, pair of 16-row tiles) over the shared experts
+// Work is a flat list of items (expert, tile of 16 MFMA rows) over the shared experts
 // and the ACTIVE resident slots only; a fixed grid of one 16-wavefront workgroup per CU
 // takes equal contiguous runs of it, so all workgroups are resident at once,
 // share the HBM bandwidth evenly and finish together.

@@ -164,3 +164,64 @@ def test_full_control_loop_three_steps():
         assert fl[0, :len(o_fl)].cpu().tolist() == o_fl.tolist() and int(nf.item()) == len(o_fl)
         moved += len(o_fl) + len(o_ev)
     assert moved > 0   # the loop did move experts
+
+
+@pytest.mark.parametrize("gen,steps", [("sampled", 120), ("smooth", 120)])
+def test_closed_loop_long_trace(gen, steps):
+    """24 layers through 120 inference steps of the closed loop, the device's slot tables feeding its own
+    next step: frequencies -> utility update + n(tau) -> threshold -> cache plan (frozen flags, fetch
+    budget).  Utilities, boundaries, n(tau), tau, lists and tables bit-exact against the oracle's chain at
+    every step."""
+    from paper_2603_09983_amd import binding as B
+    import traces
+    L, N, C, K, gamma, k = 24, 64, 32, 4, 8, 6
+    rng = np.random.default_rng(77)
+    make = traces.sampled_trace if gen == "sampled" else traces.smooth_trace
+    f = make(rng, L, N, gamma + 1, k, steps, 0.1, 40)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    st = [torch.zeros((L, N), **i32) for _ in range(4)]
+    B.moe_utility_init(*st, L, N, gamma)
+    tab0 = np.full((L, N), -1, dtype=np.int32)
+    for l in range(L):
+        tab0[l, rng.permutation(N)[:C]] = rng.permutation(C)
+    d_tab = _dev(tab0)
+    d_n, d_tau = torch.zeros((L, K + 1), **i32), torch.zeros(L, **i32)
+    ev, fl, fs = torch.zeros((L, N), **i32), torch.zeros((L, C), **i32), torch.zeros((L, C), **i32)
+    ne, nf = torch.zeros(L, **i32), torch.zeros(L, **i32)
+    r_c = np.sort(rng.random((L, K + 1)), axis=1)
+    r_g = np.ascontiguousarray(np.sort(rng.random((L, K + 1)), axis=1)[:, ::-1])
+    p = dict(t_cpu=40.0, t_gpu=3.0, t_io=20.0, t_draft=600.0, l_target=24, w_expert=1000, vram_left=9000)
+    params = B.BalanceParams(p["t_cpu"], p["t_gpu"], p["t_io"], p["t_draft"], p["l_target"], p["w_expert"], p["vram_left"])
+    d_rc, d_rg = _dev(r_c), _dev(r_g)
+    z, th = np.zeros((L, N), dtype=np.int32), np.full((L, N), gamma // 2, dtype=np.int32)
+    o_st = [z.copy(), z.copy(), th.copy(), th.copy()]
+    o_tab = tab0.copy()
+    taus, moved = set(), 0
+    for t in range(steps):
+        in_use = ((rng.random((L, N)) < 0.1) & (o_tab >= 0)).astype(np.int32)
+        budget = rng.integers(0, 6, size=L).astype(np.int32)
+        d_f = _dev(f[t])
+        B.moe_utility_update(d_f, *st, d_tab, d_n, L, N, K, 1, 10)
+        B.moe_balance_threshold(d_f, d_n, d_rc, d_rg, L, N, K, gamma, k, params, d_tau)
+        B.moe_cache_plan(st[1], _dev(in_use), d_tab, d_tau, _dev(budget), L, N, C, K, ev, ne, fl, fs, nf)
+        torch.cuda.synchronize()
+        got = [x.cpu().numpy() for x in (*st, d_n, d_tau, d_tab, ev, ne, fl, fs, nf)]
+        for l in range(L):
+            o = oracle.utility_step(f[t, l], *(a[l] for a in o_st), K, 1, 10)
+            for a, v in zip(o_st, o):
+                a[l] = v
+            n_tau = oracle.prefetch_counts(o_st[1][l], o_tab[l], K)
+            tau = oracle.balance_threshold(f[t, l], n_tau, r_c[l], r_g[l], K, gamma, k, **p)[0]
+            new, o_ev, o_fl, o_fs = oracle.cache_plan(o_st[1][l], in_use[l], o_tab[l], C, K, tau, int(budget[l]))
+            o_tab[l] = new
+            where = (gen, t, l)
+            assert np.array_equal(got[4][l], n_tau) and got[5][l] == tau, where
+            assert got[8][l] == len(o_ev) and got[11][l] == len(o_fl), where
+            assert got[7][l, :len(o_ev)].tolist() == o_ev.tolist(), where
+            assert got[9][l, :len(o_fl)].tolist() == o_fl.tolist() and got[10][l, :len(o_fl)].tolist() == o_fs.tolist(), where
+            taus.add(tau)
+            moved += len(o_fl)
+        for i in range(4):
+            assert np.array_equal(got[i], o_st[i]), (gen, t, i)
+        assert np.array_equal(got[6], o_tab), (gen, t)
+    assert moved > 0 and len(taus) > 1   # the loop moved experts and the threshold did vary

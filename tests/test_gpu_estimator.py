@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import oracle
+import traces
 from paper_2603_09983_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -14,24 +15,6 @@ pytestmark = pytest.mark.gpu
 
 def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
-
-
-def _frequencies(rng, L, N, T, k, steps, drift):
-    """Per layer and step: a histogram of T*k assignments drawn from a slowly drifting Zipf-like
-    popularity (the smooth evolution Alg. 1 is built for), with a few abrupt shifts."""
-    out = np.zeros((steps, L, N), dtype=np.int32)
-    logit = rng.normal(0, 1.5, size=(L, N))
-    for t in range(steps):
-        logit += rng.normal(0, drift, size=(L, N))
-        if t % 11 == 10:
-            logit = np.roll(logit, 3, axis=1)
-        p = np.exp(logit - logit.max(axis=1, keepdims=True))
-        p /= p.sum(axis=1, keepdims=True)
-        for l in range(L):
-            for _ in range(T):
-                picks = rng.choice(N, size=k, replace=False, p=p[l])
-                out[t, l, picks] += 1
-    return out
 
 
 CASES = [
@@ -50,7 +33,7 @@ def test_estimator_parity(case):
     from paper_2603_09983_amd import binding as B
     name, L, N, gamma, K, k, (ln, ld), steps = case
     rng = np.random.default_rng(zlib.crc32(name.encode()))
-    freqs = _frequencies(rng, L, N, gamma + 1, k, steps, 0.15)
+    freqs = traces.sampled_trace(rng, L, N, gamma + 1, k, steps, 0.15)
     tab = np.where(rng.random((L, N)) < 0.5, 1, -1).astype(np.int32)
     tab[tab > 0] = np.arange(int((tab > 0).sum()), dtype=np.int32)   # any non-negative slot number will do
 

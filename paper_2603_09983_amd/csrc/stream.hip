@@ -206,13 +206,26 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     // st[1]); each remembers its own geometry.
     // (The two-group variants are short of registers: they keep row and column packed in one word
     // per piece and derive both offsets where they are used.)
+    // (The variant for the largest batches has none to spare at all: it works row and column out
+    // again at each use rather than let the compiler spill a register that a load is writing.)
     constexpr bool PACKED = NG == 2;
+    constexpr bool LEAN = MODE == 2;
     u32x4 st[2][NPI];
     unsigned goff[2][PACKED ? 1 : NPI];   // PACKED: unused
-    int loff[2][NPI];                     // PACKED: row << 16 | column
+    int loff[2][LEAN ? 1 : NPI];          // PACKED: row << 16 | column; LEAN: unused
     int st_rs[2] = {-1, -1}, st_K2[2] = {-1, -1};
+    auto geom = [&](int i, int rs) {      // row << 16 | column of piece i in a tile of rs-byte rows
+        const int np = rs / 64;
+        int pc = i * kWaves + w;
+        pc = pc < np ? pc : np - 1;
+        const int off = (pc << 10) + (lane << 4);
+        const int row = (int)(((float)(off >> 4) + 0.5f) * (16.0f / (float)rs));
+        return row << 16 | (off - row * rs);
+    };
     auto issue = [&](int s) {
-        if (prs != st_rs[s] || pK2 != st_K2[s]) {
+        if (LEAN) {
+            st_rs[s] = prs;
+        } else if (prs != st_rs[s] || pK2 != st_K2[s]) {
             st_rs[s] = prs;
             st_K2[s] = pK2;
             const float inv_d = 16.0f / (float)prs;
@@ -225,7 +238,7 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
                 int row = (int)(((float)(off >> 4) + 0.5f) * inv_d);
                 int col = off - row * prs;
                 if (PACKED) {
-                    loff[s][i] = row << 16 | col;
+                    loff[s][LEAN ? 0 : i] = row << 16 | col;
                 } else {
                     goff[s][i] = (unsigned)((row & 7) * pK2 + col);
                     loff[s][i] = row * (prs + kRowPad) + col;
@@ -239,8 +252,8 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
             int pc = i * kWaves + w;
             pc = pc < np ? pc : np - 1;
             const unsigned char *base = (pc << 10) < 8 * prs ? pw0 : pw1;   // uniform
-            const unsigned go = PACKED ? (unsigned)(((loff[s][i] >> 16) & 7) * pK2 + (loff[s][i] & 0xffff))
-                                       : goff[s][i];
+            const int rc = LEAN ? geom(i, prs) : loff[s][LEAN ? 0 : i];
+            const unsigned go = PACKED ? (unsigned)(((rc >> 16) & 7) * pK2 + (rc & 0xffff)) : goff[s][PACKED ? 0 : i];
             st[s][i] = ld_stream(base + (poff + go));
         }
     };
@@ -248,7 +261,8 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         // (a wavefront's re-read of the last piece lands on that piece's own bytes: same data, no test)
 #pragma unroll
         for (int i = 0; i < NPI; ++i) {
-            const int lo = PACKED ? (loff[s][i] >> 16) * (st_rs[s] + kRowPad) + (loff[s][i] & 0xffff) : loff[s][i];
+            const int rc = LEAN ? geom(i, st_rs[s]) : loff[s][LEAN ? 0 : i];
+            const int lo = PACKED ? (rc >> 16) * (st_rs[s] + kRowPad) + (rc & 0xffff) : rc;
             *(u32x4 *)(tile_s + lo) = st[s][i];
         }
     };

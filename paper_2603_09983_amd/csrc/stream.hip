@@ -206,10 +206,10 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     // st[1]); each remembers its own geometry.
     // (The two-group variants are short of registers: they keep row and column packed in one word
     // per piece and derive both offsets where they are used.)
-    // (The variant for the largest batches has none to spare at all: it works row and column out
-    // again at each use rather than let the compiler spill a register that a load is writing.)
+    // (The variant for the largest batches and the widest tiles has none to spare at all: it works row
+    // and column out again at each use rather than let the compiler spill a register that a load is writing.)
     constexpr bool PACKED = NG == 2;
-    constexpr bool LEAN = MODE == 2;
+    constexpr bool LEAN = MODE == 2 && NPI == 4;
     u32x4 st[2][NPI];
     unsigned goff[2][PACKED ? 1 : NPI];   // PACKED: unused
     int loff[2][LEAN ? 1 : NPI];          // PACKED: row << 16 | column; LEAN: unused

@@ -597,8 +597,10 @@ size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup)
 
 bool stream_can_join(const StreamArgs &d)
 {
-    // up to 32 tokens (measured at 128: polling T x 8 x sources entries per strip costs more than the
-    // combine launch it saves); the strip's entries fit the tile buffer
+    // up to 32 tokens: the 64-bit entries double the bytes of the per-assignment outputs (12.6 MB written
+    // and read back at 128 tokens, H = 2048).  Measured per layer against the separate launch, with the
+    // entries of a strip requested eight per thread at a time: no difference at 33 and 64 tokens, 4.6 us
+    // more at 128 (and that batched form cost the small batches 0.4-1 us).  The strip's entries fit the tile buffer.
     const size_t tile = (size_t)16 * (2 * (d.KP > d.KP_sh ? d.KP : d.KP_sh) + kRowPad);
     return d.T <= 32 && d.R % 8 == 0 && (size_t)d.T * 8 * (d.k + d.n_shared) * 4 <= tile;
 }

@@ -237,8 +237,9 @@ extern "C" int moe_slot_resolve(const int32_t *topk_idx, const int32_t *slot_tab
 namespace {
 
 // The expert FFN and the combine, given the per-slot lists in the workspace.
-// Batches of up to 16 tokens stream the weights with the LDS-staged kernels
-// (gate/up, down, combine); larger batches take the fused per-slice kernel.
+// Shapes the LDS-staged streaming kernels take (use_stream_kernels) run gate/up,
+// then down with the combine inside it (small batches) or followed by it; the
+// rest takes the fused per-slice kernel and its combine.
 int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const void *w_up, const void *w_down,
             const void *sh_gate, const void *sh_up, const void *sh_down, int T, int H, int F, int k, int C,
             int n_shared, int F_shared, const WsLayout &w, char *ws, void *out, int out_bf16, int accumulate,

@@ -253,7 +253,7 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
     c.T = T; c.H = H; c.F = F; c.k = k; c.n_shared = n_shared; c.F_shared = F_shared;
     c.out_bf16 = out_bf16; c.accumulate = accumulate;
     hipError_t e;
-    if (use_stream_kernels(T, H, F, n_shared, F_shared)) {
+    if (use_stream_kernels(T, k, C, H, F, n_shared, F_shared)) {
         StreamArgs g = {};
         g.w0 = (const uint16_t *)w_gate; g.w1 = (const uint16_t *)w_up;
         g.s0 = (const uint16_t *)sh_gate; g.s1 = (const uint16_t *)sh_up;

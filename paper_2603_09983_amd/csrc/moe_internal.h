@@ -18,14 +18,32 @@ constexpr int kCtrlBytes = 256;
 // contraction lengths up to this many columns are parked in LDS whole (one panel per item)
 constexpr int kPanelMax = 2048;
 
+int stream_panel_width(int K);     // columns of a contraction parked in LDS at a time; 0 when K has no panel split
+
+// LDS of one workgroup of a streaming kernel: the tile (16 rows of a panel of KP columns, padded), the
+// partial results, the per-slot lists and the token list, the output buffer with its records.
+constexpr int kStreamRowPad = 16;   // bytes of padding per LDS tile row
+constexpr int kStreamOutCap = 16;   // items whose results wait in LDS between two batches of stores
+static inline size_t stream_lds_need(int KP, int T, int k, int C, bool gateup)
+{
+    const size_t groups = T > 16 ? 2 : 1;
+    return (size_t)16 * (2 * (size_t)KP + kStreamRowPad) + groups * 16 * kWave * 16 +
+           ((size_t)3 * C + (size_t)T * k) * 4 + (size_t)kStreamOutCap * (groups * (gateup ? 128 : 256) + 8) * 4;
+}
+
 // The streaming kernels (stream.hip) take every batch of up to 32 tokens, and larger batches when
-// every item is a single panel; only wide matrices with large batches fall back to ffn.hip.
-static inline bool use_stream_kernels(int T, int H, int F, int n_shared, int F_shared)
+// every item is a single panel, as long as the lists fit their LDS; the rest (wide matrices with large
+// batches, ragged row lengths, very long lists) falls back to ffn.hip.
+static inline bool use_stream_kernels(int T, int k, int C, int H, int F, int n_shared, int F_shared)
 {
     // (their 1 KB pieces must not straddle the middle of a 16-row tile: row bytes a multiple of 128)
     if (H % 64 != 0 || F % 64 != 0 || (n_shared > 0 && F_shared % 64 != 0)) return false;
-    if (T <= 32) return true;
-    return H <= kPanelMax && F <= kPanelMax && (n_shared == 0 || F_shared <= kPanelMax);
+    if (T > 32 && !(H <= kPanelMax && F <= kPanelMax && (n_shared == 0 || F_shared <= kPanelMax))) return false;
+    const int kp_h = stream_panel_width(H), kp_f = stream_panel_width(F);
+    const int kp_s = n_shared > 0 ? stream_panel_width(F_shared) : 0;
+    if (kp_h == 0 || kp_f == 0 || (n_shared > 0 && kp_s == 0)) return false;
+    return stream_lds_need(kp_h, T, k, C, true) <= (size_t)kLdsBytes &&
+           stream_lds_need(kp_f > kp_s ? kp_f : kp_s, T, k, C, false) <= (size_t)kLdsBytes;
 }
 
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -65,7 +83,7 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
     w.slot_count = o;  o += align256((size_t)(C > 0 ? C : 1) * 4);
     w.slot_offset = o; o += align256((size_t)(C + 1) * 4);
     w.active = o;      o += align256((size_t)(C > 0 ? C : 1) * 4);
-    if (!use_stream_kernels(T, H, F, n_shared, F_shared)) {
+    if (!use_stream_kernels(T, k, C, H, F, n_shared, F_shared)) {
         // large batches: per-slice partial sums of the fused FFN kernel
         w.part = o;    o += align256((size_t)n_slices(F) * A * H * 4);
         w.part_sh = o; o += align256((size_t)n_shared * n_slices(F_shared) * T * H * 4);
@@ -168,8 +186,6 @@ hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_
 hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join, hipStream_t s);
 bool stream_can_join(const StreamArgs &d);
 hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s);
-int stream_panel_width(int K);     // 0 when K has no panel split
-size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup);
 hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
 // zero-fills the workspace (control block, stamped-entry regions and everything else)

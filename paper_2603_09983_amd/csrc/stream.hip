@@ -39,8 +39,8 @@ typedef __attribute__((address_space(1))) float g_f32;
 constexpr int kThreads = 1024;
 constexpr int kWaves = 16;
 constexpr int kPieces = 4;     // 1 KB pieces per wavefront per tile (64 KB tile / 16 wavefronts)
-constexpr int kRowPad = 16;    // bytes of padding per LDS tile row
-constexpr int kOutCap = 16;    // items whose results are kept in LDS between two batches of stores
+constexpr int kRowPad = kStreamRowPad;
+constexpr int kOutCap = kStreamOutCap;
 constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before a workgroup gives up waiting
 
 __device__ inline u32x4 ld_stream(const unsigned char *p)
@@ -583,16 +583,10 @@ int num_cus()
 int stream_panel_width(int K)
 {
     // equal panels, each a multiple of 32 and at most kPanelMax columns wide
+    if (K < 32) return 0;
     for (int np = (K + kPanelMax - 1) / kPanelMax; np <= K / 32; ++np)
         if (K % np == 0 && (K / np) % 32 == 0) return K / np;
     return 0;
-}
-
-size_t stream_lds_bytes(int KP_a, int KP_b, bool gateup)
-{
-    int kp = KP_a > KP_b ? KP_a : KP_b;
-    (void)gateup;
-    return (size_t)16 * (2 * kp + kRowPad) + (size_t)kWaves * kWave * 16;
 }
 
 bool stream_can_join(const StreamArgs &d)
@@ -608,13 +602,10 @@ bool stream_can_join(const StreamArgs &d)
 hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join, hipStream_t s)
 {
     if (join && (gateup || !stream_can_join(a))) return hipErrorInvalidValue;
-    const size_t tile = (size_t)16 * (2 * (a.KP > a.KP_sh ? a.KP : a.KP_sh) + kRowPad);
-    const int ngl = a.T > 16 ? 2 : 1;
-    const size_t lds = (size_t)16 * (2 * (a.KP > a.KP_sh ? a.KP : a.KP_sh) + kRowPad) +
-                       (size_t)ngl * kWaves * kWave * 16 + (size_t)(3 * a.C + a.T * a.k) * 4 +
-                       (size_t)kOutCap * (ngl * (gateup ? 128 : 256) + 8) * 4;
-    if (lds > (size_t)kLdsBytes) return hipErrorInvalidValue;
     const int kp_max = a.KP > a.KP_sh ? a.KP : a.KP_sh;
+    const size_t tile = (size_t)16 * (2 * kp_max + kRowPad);
+    const size_t lds = stream_lds_need(kp_max, a.T, a.k, a.C, gateup);
+    if (lds > (size_t)kLdsBytes) return hipErrorInvalidValue;
     const int npi = (kp_max / 32 + kWaves - 1) / kWaves;   // 1..4 pieces per wavefront and tile
     const int mode = a.T > 32 ? 2 : a.T > 16 ? 1 : 0;
 #define MOE_STREAM_FN(GU, N)                                                                     \

@@ -52,6 +52,9 @@ def test_workspace_bytes_and_status_strings(lib):
     wide = Shape(64, 4096, 8, 2, 14336, 8, 0, 0)       # large batch, wide matrices: per-slice partial sums
     assert lib.moe_workspace_bytes(ctypes.byref(wide), ctypes.byref(n)) == 0
     assert n.value >= 112 * 128 * 4096 * 4
+    long_lists = Shape(4096, 128, 16, 8, 128, 16, 0, 0)  # more assignments than the streaming kernels list in LDS
+    assert lib.moe_workspace_bytes(ctypes.byref(long_lists), ctypes.byref(n)) == 0
+    assert 32768 * 128 * 4 <= n.value < 32768 * 128 * 8  # per-slice partial sums, not the 8-byte entries
     assert lib.moe_workspace_bytes(None, ctypes.byref(n)) == -1
     bad = Shape(9, 2048, 64, 65, 1408, 32, 0, 0)       # k > E
     assert lib.moe_workspace_bytes(ctypes.byref(bad), ctypes.byref(n)) == -2

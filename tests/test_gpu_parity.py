@@ -42,6 +42,8 @@ SMALL_CASES = {
     "E130": dict(T=5, H=128, E=130, k=7, F=64, C=40, hidden="unit"),
     # the 128-expert / top-8 shape class (two logits per lane in the wavefront ranking)
     "E128_k8": dict(T=9, H=256, E=128, k=8, F=128, C=48, hidden="unit"),
+    # T*E at the supported maximum, and more assignments (32768) than the streaming kernels can list in LDS
+    "long_lists": dict(T=4096, H=128, E=16, k=8, F=128, C=16, residency="all"),
     # nothing resident: output is the shared expert alone, every assignment missed
     "cache_empty": dict(T=4, H=128, E=8, k=2, F=128, C=0, n_shared=1, Fs=128),
 }

@@ -42,6 +42,8 @@ SMALL_CASES = {
     "E130": dict(T=5, H=128, E=130, k=7, F=64, C=40, hidden="unit"),
     # the 128-expert / top-8 shape class (two logits per lane in the wavefront ranking)
     "E128_k8": dict(T=9, H=256, E=128, k=8, F=128, C=48, hidden="unit"),
+    # the largest expert count (eight logits per lane in the wavefront ranking), 300 cache slots
+    "max_experts": dict(T=8, H=128, E=512, k=8, F=64, C=300, hidden="unit"),
     # T*E at the supported maximum, and more assignments (32768) than the streaming kernels can list in LDS
     "long_lists": dict(T=4096, H=128, E=16, k=8, F=128, C=16, residency="all"),
     # nothing resident: output is the shared expert alone, every assignment missed

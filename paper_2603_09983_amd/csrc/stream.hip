@@ -85,9 +85,13 @@ __device__ inline uint32_t f32_to_bf16_rne(float f)
 // call's number (a bounded number of times: every other workgroup is resident and none of them
 // waits before it has stored), and adds them up in a fixed order.  No counter, no fence: an entry
 // with the right number IS the value.
-template <bool GATEUP, int NPI, int MODE, bool JOIN>
+//
+// WSPLIT (down kernel, shared experts whose items have another number of panels than the routed ones):
+// the item list is cut into runs of equal numbers of TILES instead of items.
+template <bool GATEUP, int NPI, int MODE, bool JOIN, bool WSPLIT = false>
 __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes, JoinArgs jn)
 {
+    static_assert(!WSPLIT || !GATEUP, "gate/up items all have the panels of the hidden size");
     static_assert(!JOIN || (!GATEUP && MODE < 2), "the join rides on the down kernel of batches up to 32 tokens");
     constexpr int NG = MODE == 0 ? 1 : 2;   // token groups of 16 multiplied per pass
     constexpr bool MULTIPASS = MODE == 2;
@@ -285,11 +289,26 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     __syncthreads();
 
     // equal runs of the whole item list; this workgroup's run = its shared items, then routed ones
-    {
+    if (!WSPLIT) {
         const int total = n_sh_items + n_act * tiles;
         const int per = total / G, rem = total % G;
         cnt = per + (b < rem ? 1 : 0);
         r_start = b * per + (b < rem ? b : rem) - s_start;
+    } else {
+        // Workgroup x starts at routed item max(0, x * total tiles / G - tiles of the shared items
+        // before x) / panels per routed item: that never decreases with x, is 0 for x = 0 and the
+        // number of routed items for x = G.
+        const int np_r = a.K / a.KP, np_sh = a.K_sh / a.KP_sh;
+        const int n_routed = n_act * tiles;
+        const long long total = (long long)n_sh_items * np_sh + (long long)n_routed * np_r;
+        auto routed_before = [&](int x) {
+            const long long sh = (long long)(x * sh_per + (x < sh_rem ? x : sh_rem)) * np_sh;
+            const long long rt = (long long)x * total / G - sh;
+            const long long r = rt > 0 ? rt / np_r : 0;
+            return (int)(r < n_routed ? r : n_routed);
+        };
+        r_start = routed_before(b);
+        cnt = s_cnt + routed_before(b + 1) - r_start;
     }
     const unsigned tag = JOIN ? *jn.epoch : 0u;   // number of this call (set by the routing / list kernel)
     auto join = [&]() {
@@ -614,13 +633,26 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join,
 #define MOE_JOIN_FN(N) {(const void *)stream_kernel<false, N, 0, true>, (const void *)stream_kernel<false, N, 1, true>}
     static const void *const join_fns[4][2] = {MOE_JOIN_FN(1), MOE_JOIN_FN(2), MOE_JOIN_FN(3), MOE_JOIN_FN(4)};
 #undef MOE_JOIN_FN
+    // down kernel, runs of equal numbers of tiles
+#define MOE_WSPLIT_FN(N)                                                                                       \
+    {(const void *)stream_kernel<false, N, 0, false, true>, (const void *)stream_kernel<false, N, 1, false, true>, \
+     (const void *)stream_kernel<false, N, 2, false, true>}
+#define MOE_WSPLIT_JOIN_FN(N) \
+    {(const void *)stream_kernel<false, N, 0, true, true>, (const void *)stream_kernel<false, N, 1, true, true>}
+    static const void *const wsplit_fns[4][3] = {MOE_WSPLIT_FN(1), MOE_WSPLIT_FN(2), MOE_WSPLIT_FN(3), MOE_WSPLIT_FN(4)};
+    static const void *const wsplit_join_fns[4][2] = {MOE_WSPLIT_JOIN_FN(1), MOE_WSPLIT_JOIN_FN(2), MOE_WSPLIT_JOIN_FN(3),
+                                                      MOE_WSPLIT_JOIN_FN(4)};
+#undef MOE_WSPLIT_FN
+#undef MOE_WSPLIT_JOIN_FN
     static const void *const fns[2][4][3] = {
         {MOE_STREAM_FN(false, 1), MOE_STREAM_FN(false, 2), MOE_STREAM_FN(false, 3), MOE_STREAM_FN(false, 4)},
         {MOE_STREAM_FN(true, 1), MOE_STREAM_FN(true, 2), MOE_STREAM_FN(true, 3), MOE_STREAM_FN(true, 4)}};
 #undef MOE_STREAM_FN
+    const bool wsplit = !gateup && a.n_shared > 0 && a.KP_sh > 0 && a.K_sh / a.KP_sh != a.K / a.KP;
     const void *fn = join ? join_fns[npi - 1][mode] : fns[gateup ? 1 : 0][npi - 1][mode];
-    static bool attr_done[36] = {};
-    const int which = join ? 24 + (npi - 1) * 3 + mode : ((gateup ? 4 : 0) + npi - 1) * 3 + mode;
+    if (wsplit) fn = join ? wsplit_join_fns[npi - 1][mode] : wsplit_fns[npi - 1][mode];
+    static bool attr_done[72] = {};
+    const int which = (wsplit ? 36 : 0) + (join ? 24 + (npi - 1) * 3 + mode : ((gateup ? 4 : 0) + npi - 1) * 3 + mode);
     if (!attr_done[which]) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;

@@ -46,6 +46,9 @@ def parse_args():
                    help="timed region 1 replays a captured HIP graph of one pass over the layers (lifts the "
                         "host's launch rate off small layers); steps must be a multiple of the layer count")
     p.add_argument("--cpu-seconds", type=float, default=10.0)
+    p.add_argument("--timeline", action="store_true",
+                   help="with a library built with the timeline stamps (build.py --trace, MOE_SPAC_LIB): print to "
+                        "stderr when the workgroups of the two streaming kernels reach each point of their life")
     p.add_argument("--calibration-copy", action="store_true",
                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling "
                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -75,6 +78,35 @@ def build_layers(workload: str, copies: int):
         desc = (f"{workload}: T={s.T} H={s.H} E={s.E} k={s.k} F={s.F} C={s.C} "
                 f"shared={s.n_shared}x{s.F_shared}, rotating over {n} independent layers")
     return layers, desc
+
+
+def print_timeline(B, torch, np, step, n_layers):
+    """Per streaming kernel of three consecutive layer calls: min / median / max over the workgroups of the
+    time (us after the first workgroup's start) at which they have the lists in LDS, have consumed their
+    first tile, leave their loop, have stored their results and end; the loop-end mean per XCD."""
+    for i in range(min(3, n_layers)):
+        step(i)
+        torch.cuda.synchronize()
+        words = B.moe_profile_stream_timeline()
+        if words is None:
+            print("[timeline] the loaded library has no timeline stamps (python paper_2603_09983_amd/build.py "
+                  "--trace; MOE_SPAC_LIB=paper_2603_09983_amd/libmoe_spac_trace.so)", file=sys.stderr)
+            return
+        for ki, name in enumerate(("gate/up", "down")):
+            t = words[ki].astype(np.int64)
+            t = t[t[:, 5] > 0]
+            if not len(t):
+                continue
+            us = (t[:, :6] - t[:, 0].min()) / 100.0
+
+            def q(x):
+                return "%5.1f/%5.1f/%5.1f" % (x.min(), np.median(x), x.max())
+            print(f"[timeline] layer {i} {name:7s} ({len(t)} workgroups, {t[:, 6].min()}-{t[:, 6].max()} items each): "
+                  f"start {q(us[:, 0])} | lists {q(us[:, 1])} | first tile {q(us[:, 2])} | loop end {q(us[:, 3])} | "
+                  f"stored {q(us[:, 4])} | end {q(us[:, 5])}", file=sys.stderr)
+            xcd = np.arange(len(t)) % 8
+            print("[timeline]     loop end, mean per XCD: " +
+                  " ".join("%.1f" % us[xcd == x, 3].mean() for x in range(8)), file=sys.stderr)
 
 
 def main():
@@ -317,6 +349,8 @@ def main():
                                         "mean_weight_bytes_per_layer": int(np.mean(layer_bytes))},
         "roofline": roofline, "cpu_baseline": cpu, "estimator": est,
     }
+    if args.timeline:
+        print_timeline(B, torch, np, step, len(layers))
     print(json.dumps(out))
 
 

@@ -251,6 +251,15 @@ const char *moe_profile_kernel_name(int kind);
  * much time that is not the kernel's.  Call after moe_profile_enable(1) and
  * after reading the records you need (it reuses the pairs of kind 0). */
 int moe_profile_event_overhead(void *stream, int pairs, double *avg_ms);
+/* Timeline of the last gate/up and down launches of the streaming kernels, for a
+ * library built with -DMOE_STREAM_TRACE (the product build returns
+ * MOE_ERR_SHAPE and writes nothing).  words: host buffer of
+ * 2 x 1024 x 8 64-bit words, [kernel: 0 gate/up, 1 down][workgroup][stamp]:
+ * ticks of the 100 MHz device wall clock at the workgroup's start, with the
+ * per-slot lists in LDS, after its first tile, at the end of its loop, after
+ * its results are stored and at its end; then its items and tiles.  Synchronous
+ * (a blocking copy from the device); call after synchronising the stream. */
+int moe_profile_stream_timeline(unsigned long long *words, size_t n_words);
 
 #ifdef __cplusplus
 }

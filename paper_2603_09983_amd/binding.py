@@ -15,7 +15,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmoe_spac.so")
+# (MOE_SPAC_LIB names another build of the same library, e.g. the one with the timeline stamps)
+LIB_PATH = os.environ.get("MOE_SPAC_LIB") or os.path.join(_HERE, "libmoe_spac.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -66,11 +67,13 @@ _lib.moe_profile_read.argtypes = [_i, ctypes.POINTER(ctypes.c_double), ctypes.PO
 _lib.moe_profile_read.restype = _i
 _lib.moe_profile_event_overhead.argtypes = [_vp, _i, ctypes.POINTER(ctypes.c_double)]
 _lib.moe_profile_event_overhead.restype = _i
+_lib.moe_profile_stream_timeline.argtypes = [ctypes.c_void_p, _sz]
+_lib.moe_profile_stream_timeline.restype = _i
 _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
 KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_BALANCER, KERNEL_CACHE_PLAN, KERNEL_POOL_LOAD, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
 
-EXPORTS = ("moe_cache_plan", "moe_pool_load", "moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
+EXPORTS = ("moe_profile_stream_timeline", "moe_cache_plan", "moe_pool_load", "moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
 
 
@@ -113,6 +116,17 @@ def moe_profile_read(kind: int):
     ms, n = ctypes.c_double(0.0), _i(0)
     _check(_lib.moe_profile_read(kind, ctypes.byref(ms), ctypes.byref(n)), "moe_profile_read", True)
     return float(ms.value), int(n.value)
+
+
+def moe_profile_stream_timeline():
+    """[2, 1024, 8] uint64 (numpy), or None when the loaded library is not a tracing build."""
+    import numpy as np
+    words = np.zeros((2, 1024, 8), dtype=np.uint64)
+    rc = _lib.moe_profile_stream_timeline(ctypes.c_void_p(words.ctypes.data), words.size)
+    if rc == ERR_SHAPE:
+        return None
+    _check(rc, "moe_profile_stream_timeline", True)
+    return words
 
 
 def moe_profile_event_overhead(pairs: int = 256, stream=None) -> float:

@@ -118,6 +118,15 @@ extern "C" int moe_profile_event_overhead(void *stream, int pairs, double *avg_m
     return MOE_OK;
 }
 
+extern "C" int moe_profile_stream_timeline(unsigned long long *words, size_t n_words)
+{
+    if (!words) return MOE_ERR_NULL;
+    if (n_words != (size_t)2 * kTimelineGroups * kTimelineWords) return MOE_ERR_SHAPE;
+    hipError_t e = read_stream_timeline(words, n_words * sizeof(unsigned long long));
+    if (e == hipErrorNotSupported) return MOE_ERR_SHAPE;   // not a tracing build
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
+}
+
 extern "C" const char *moe_profile_kernel_name(int kind)
 {
     switch (kind) {

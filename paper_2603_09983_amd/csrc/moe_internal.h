@@ -186,6 +186,11 @@ hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_
 hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join, hipStream_t s);
 bool stream_can_join(const StreamArgs &d);
 hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s);
+// Timeline stamps of the last gate/up and down launches: [2][kTimelineGroups][kTimelineWords] 64-bit words
+// (start, lists in LDS, first tile done, loop done, results stored, end: 100 MHz ticks; items, tiles).
+// hipErrorNotSupported unless the library was built with -DMOE_STREAM_TRACE.
+constexpr int kTimelineGroups = 1024, kTimelineWords = 8;
+hipError_t read_stream_timeline(void *dst, size_t bytes);
 hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
 // zero-fills the workspace (control block, stamped-entry regions and everything else)

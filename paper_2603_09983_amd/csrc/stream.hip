@@ -86,6 +86,16 @@ __device__ inline uint32_t f32_to_bf16_rne(float f)
 // waits before it has stored), and adds them up in a fixed order.  No counter, no fence: an entry
 // with the right number IS the value.
 //
+//
+// Built with -DMOE_STREAM_TRACE the kernel also stamps the 100 MHz wall clock at six points of every
+// workgroup's life (moe_profile_stream_timeline reads them back); the product build has none of that.
+#ifdef MOE_STREAM_TRACE
+__device__ unsigned long long g_timeline[2][kTimelineGroups][kTimelineWords];
+#define MOE_STAMP(var) var = wall_clock64()
+#else
+#define MOE_STAMP(var)
+#endif
+//
 // WSPLIT (down kernel, shared experts whose items have another number of panels than the routed ones):
 // the item list is cut into runs of equal numbers of TILES instead of items.
 template <bool GATEUP, int NPI, int MODE, bool JOIN, bool WSPLIT = false>
@@ -112,6 +122,10 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     int *odesc_s = (int *)(out_s + kOutCap * NG * kOutPerItem);       // [kOutCap][8]: shared?, row of token 0, column bytes, m, first token
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
+#ifdef MOE_STREAM_TRACE
+    unsigned long long tl_start, tl_lists = 0, tl_first = 0, tl_loop = 0, tl_flush = 0;
+#endif
+    MOE_STAMP(tl_start);
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wavefront id, known to be uniform
     const int n = lane & 15, g = lane >> 4;
 
@@ -310,6 +324,7 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         r_start = routed_before(b);
         cnt = s_cnt + routed_before(b + 1) - r_start;
     }
+    MOE_STAMP(tl_lists);
     const unsigned tag = JOIN ? *jn.epoch : 0u;   // number of this call (set by the routing / list kernel)
     auto join = [&]() {
         if (!JOIN) return;
@@ -540,15 +555,25 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     // (first tile peeled off so that the loop is always entered in the same state: the compiler then
     // counts the loads in flight exactly and each park waits for its own tile only)
     step(0);
+    MOE_STAMP(tl_first);
     int t = 1;
     for (; t + 1 < ntiles; t += 2) {
         step(1);
         step(0);
     }
     if (t < ntiles) step(1);
+    MOE_STAMP(tl_loop);
     __syncthreads();
     flush();
+    MOE_STAMP(tl_flush);
     join();
+#ifdef MOE_STREAM_TRACE
+    if (tid == 0 && blockIdx.x < kTimelineGroups) {
+        unsigned long long *tl = g_timeline[GATEUP ? 0 : 1][blockIdx.x];
+        tl[0] = tl_start; tl[1] = tl_lists; tl[2] = tl_first; tl[3] = tl_loop; tl[4] = tl_flush; tl[5] = wall_clock64();
+        tl[6] = (unsigned long long)cnt; tl[7] = (unsigned long long)ntiles;
+    }
+#endif
 }
 
 // out[t,:] (+)= sum_j w[t,j] * o[pos[t,j],:] + sum_i o_sh[i,t,:], in a fixed order
@@ -667,6 +692,17 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join,
     hipError_t le = launch_timed(fn, dim3(grid), dim3(kThreads), params, lds, s, gateup ? 2 : 4);
     if (le != hipSuccess) return le;
     return hipGetLastError();
+}
+
+hipError_t read_stream_timeline(void *dst, size_t bytes)
+{
+#ifdef MOE_STREAM_TRACE
+    if (bytes != sizeof(g_timeline)) return hipErrorInvalidValue;
+    return hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_timeline), sizeof(g_timeline));
+#else
+    (void)dst; (void)bytes;
+    return hipErrorNotSupported;
+#endif
 }
 
 hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s)

@@ -78,3 +78,14 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_grouped_ffn(p, p, p, p, p, p, 4, 64, 64, 2, 4, p, 0, 0, p, 64, None) == -4
     assert lib.moe_grouped_ffn(p, p, p, p, p, p, 4, 8192, 64, 2, 4, p, 0, 0, p, 1 << 30, None) == -2  # H too wide
     assert lib.moe_grouped_ffn(p, p, p, None, p, p, 4, 64, 64, 2, 4, p, 0, 0, p, 1 << 30, None) == -1
+
+
+def test_timeline_entry_point_of_the_product_build(lib):
+    """The product library carries no timeline stamps: the entry point says so and writes nothing."""
+    lib.moe_profile_stream_timeline.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    words = (ctypes.c_ulonglong * (2 * 1024 * 8))()
+    words[0] = 7
+    assert lib.moe_profile_stream_timeline(None, 2 * 1024 * 8) == -1
+    assert lib.moe_profile_stream_timeline(words, 5) == -2
+    assert lib.moe_profile_stream_timeline(words, 2 * 1024 * 8) == -2
+    assert words[0] == 7

@@ -42,6 +42,10 @@ SMALL_CASES = {
     "E130": dict(T=5, H=128, E=130, k=7, F=64, C=40, hidden="unit"),
     # the 128-expert / top-8 shape class (two logits per lane in the wavefront ranking)
     "E128_k8": dict(T=9, H=256, E=128, k=8, F=128, C=48, hidden="unit"),
+    # a shared expert whose down items have two panels against one for the routed experts (the down kernel then
+    # cuts its item list into runs of equal numbers of tiles), one and two token groups
+    "shared_wide_T9": dict(T=9, H=128, E=8, k=2, F=128, C=4, n_shared=1, Fs=4096),
+    "shared_wide_T24": dict(T=24, H=128, E=8, k=2, F=192, C=5, n_shared=2, Fs=4096),
     # the largest expert count (eight logits per lane in the wavefront ranking), 300 cache slots
     "max_experts": dict(T=8, H=128, E=512, k=8, F=64, C=300, hidden="unit"),
     # T*E at the supported maximum, and more assignments (32768) than the streaming kernels can list in LDS

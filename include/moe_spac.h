@@ -227,7 +227,9 @@ int moe_cache_plan(const int32_t *s, const int32_t *in_use, int32_t *slot_table,
  * layer's rows of moe_cache_plan's outputs (device).  max_fetch (host): upper
  * bound of *n_fetch used to size the launch (entries beyond *n_fetch do
  * nothing).  One launch on `stream`; launched on a stream of its own it
- * overlaps with other layers' verify steps.  F*H*2 a multiple of 16. */
+ * runs beside other layers' verify steps (a store in host memory gets a
+ * launch of few workgroups, so that the slow copy does not occupy the
+ * chip).  F*H*2 a multiple of 16. */
 int moe_pool_load(const void *store_gate, const void *store_up, const void *store_down, void *pool_gate,
                   void *pool_up, void *pool_down, const int32_t *fetch_list, const int32_t *fetch_slot,
                   const int32_t *n_fetch, int max_fetch, int H, int F, void *stream);

@@ -91,6 +91,14 @@ def _ptr(t: Optional[torch.Tensor]):
     return t.data_ptr()
 
 
+def _ptr_store(t: torch.Tensor):
+    """The expert store of moe_pool_load: device memory, or pinned host memory (which the runtime maps into
+    the device under the same address)."""
+    if not t.is_contiguous() or not (t.is_cuda or t.is_pinned()):
+        raise ValueError("the expert store must be a contiguous tensor in device memory or in pinned host memory")
+    return t.data_ptr()
+
+
 def _stream(stream) -> int:
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
@@ -238,7 +246,7 @@ def moe_cache_plan(s, in_use, slot_table, tau, budget, L, N, C, K, evict_list, n
 
 def moe_pool_load(store_gate, store_up, store_down, pool_gate, pool_up, pool_down, fetch_list, fetch_slot, n_fetch,
                   max_fetch, H, F, stream=None, check=True) -> int:
-    rc = _lib.moe_pool_load(_ptr(store_gate), _ptr(store_up), _ptr(store_down), _ptr(pool_gate), _ptr(pool_up),
+    rc = _lib.moe_pool_load(_ptr_store(store_gate), _ptr_store(store_up), _ptr_store(store_down), _ptr(pool_gate), _ptr(pool_up),
                             _ptr(pool_down), _ptr(fetch_list), _ptr(fetch_slot), _ptr(n_fetch), max_fetch, H, F,
                             _stream(stream))
     return _check(rc, "moe_pool_load", check)

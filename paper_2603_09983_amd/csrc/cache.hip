@@ -199,6 +199,23 @@ extern "C" int moe_pool_load(const void *store_gate, const void *store_up, const
     int chunks = (int)((a.words16 + 256 * 8 - 1) / (256 * 8));   // eight 16-byte words per thread and matrix
     if (chunks > 512) chunks = 512;
     if (chunks < 1) chunks = 1;
+    // A store in host memory is read at the rate of the link to the host, a hundred times below HBM's: a
+    // launch that fills every wavefront slot of the chip would then hold them for a millisecond and keep the
+    // verify steps' workgroups waiting.  Sixteen workgroups have enough reads in flight for 9/10 of the
+    // link's rate (51 of 56 GB/s measured) and disturb the verify steps least (measured per cfg2 layer with a
+    // copy always in flight: +5.7 us with 16 workgroups, +7.5 with 32, +11.5 with 64, +15 with 1024).
+    {
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, store_gate) == hipSuccess) {
+            if (attr.type == hipMemoryTypeHost) {
+                int narrow = 16 / (max_fetch < 16 ? max_fetch : 16);
+                if (narrow < 1) narrow = 1;
+                if (narrow < chunks) chunks = narrow;
+            }
+        } else {
+            (void)hipGetLastError();   // not a pointer the runtime knows: launch as for device memory
+        }
+    }
     hipError_t e = launch_timed((const void *)load_kernel, dim3(chunks, max_fetch), dim3(256), params, 0,
                                 (hipStream_t)stream, MOE_KERNEL_POOL_LOAD);
     if (e == hipSuccess) e = hipGetLastError();

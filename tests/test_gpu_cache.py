@@ -225,3 +225,39 @@ def test_closed_loop_long_trace(gen, steps):
             assert np.array_equal(got[i], o_st[i]), (gen, t, i)
         assert np.array_equal(got[6], o_tab), (gen, t)
     assert moved > 0 and len(taus) > 1   # the loop moved experts and the threshold did vary
+
+
+def _device_view_of_pinned(t):
+    """Device address under which the GPU sees a pinned host tensor, or None when it is not mapped."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    dptr = ctypes.c_void_p()
+    rc = hip.hipHostGetDevicePointer(ctypes.byref(dptr), ctypes.c_void_p(t.data_ptr()), 0)
+    return dptr.value if rc == 0 else None
+
+
+def test_pool_load_from_a_store_in_pinned_host_memory():
+    """The paper's store is host memory (Sec. 3.4): experts fetched straight from pinned, device-mapped host
+    memory land in their slots bit for bit; slots not named keep what they held."""
+    from paper_2603_09983_amd import binding as B
+    E, C, H, F = 12, 6, 128, 192
+    rng = np.random.default_rng(5)
+    host = [torch.from_numpy(rng.integers(-32768, 32767, size=shp, dtype=np.int16)).pin_memory()
+            for shp in ((E, F, H), (E, F, H), (E, H, F))]
+    for t in host:
+        dv = _device_view_of_pinned(t)
+        if dv is None or dv != t.data_ptr():
+            pytest.skip("pinned host memory is not mapped into the device under its own address on this box")
+    pools = [torch.full((C, *t.shape[1:]), 7, dtype=torch.int16, device="cuda") for t in host]
+    i32 = dict(dtype=torch.int32, device="cuda")
+    fetch = torch.tensor([9, 2, 11, 0, 0, 0], **i32)
+    slots = torch.tensor([4, 0, 3, 0, 0, 0], **i32)
+    n = torch.tensor([3], **i32)
+    B.moe_pool_load(*host, *pools, fetch, slots, n, C, H, F)
+    torch.cuda.synchronize()
+    for t, p in zip(host, pools):
+        got = p.cpu()
+        for e, c in ((9, 4), (2, 0), (11, 3)):
+            assert torch.equal(got[c], t[e]), (e, c)
+        for c in (1, 2, 5):
+            assert bool((got[c] == 7).all()), c

@@ -152,10 +152,40 @@ __global__ __launch_bounds__(256) void load_kernel(LoadArgs a)
                            (const u32x4 *)a.store_down + e * a.words16};
     u32x4 *dst[3] = {(u32x4 *)a.pool_gate + c * a.words16, (u32x4 *)a.pool_up + c * a.words16,
                      (u32x4 *)a.pool_down + c * a.words16};
+    // four 16-byte words per thread in flight (words i, i + 256, ..: a wavefront's accesses stay contiguous)
+    const size_t bd = blockDim.x, stride = (size_t)gridDim.x * bd * 4;
 #pragma unroll
-    for (int m = 0; m < 3; ++m)
-        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.words16; i += (size_t)gridDim.x * blockDim.x)
+    for (int m = 0; m < 3; ++m) {
+        size_t i = (size_t)blockIdx.x * bd * 4 + threadIdx.x;
+        for (; i + 3 * bd < a.words16; i += stride) {
+            const u32x4 v0 = __builtin_nontemporal_load(src[m] + i), v1 = __builtin_nontemporal_load(src[m] + i + bd);
+            const u32x4 v2 = __builtin_nontemporal_load(src[m] + i + 2 * bd), v3 = __builtin_nontemporal_load(src[m] + i + 3 * bd);
+            __builtin_nontemporal_store(v0, dst[m] + i);
+            __builtin_nontemporal_store(v1, dst[m] + i + bd);
+            __builtin_nontemporal_store(v2, dst[m] + i + 2 * bd);
+            __builtin_nontemporal_store(v3, dst[m] + i + 3 * bd);
+        }
+        for (; i < a.words16; i += bd)   // the last, partial group of four (only the workgroup that reaches it)
             __builtin_nontemporal_store(__builtin_nontemporal_load(src[m] + i), dst[m] + i);
+    }
+}
+
+// The same copy for a store in host memory: gridDim.x workgroups walk all fetch entries, one 16-byte word
+// per thread in flight.
+__global__ __launch_bounds__(256) void load_narrow_kernel(LoadArgs a)
+{
+    const int n_fetch = *a.n_fetch;
+    for (int j = 0; j < n_fetch; ++j) {
+        const size_t e = (size_t)a.fetch_list[j], c = (size_t)a.fetch_slot[j];
+        const u32x4 *src[3] = {(const u32x4 *)a.store_gate + e * a.words16, (const u32x4 *)a.store_up + e * a.words16,
+                               (const u32x4 *)a.store_down + e * a.words16};
+        u32x4 *dst[3] = {(u32x4 *)a.pool_gate + c * a.words16, (u32x4 *)a.pool_up + c * a.words16,
+                         (u32x4 *)a.pool_down + c * a.words16};
+#pragma unroll
+        for (int m = 0; m < 3; ++m)
+            for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.words16; i += (size_t)gridDim.x * blockDim.x)
+                __builtin_nontemporal_store(__builtin_nontemporal_load(src[m] + i), dst[m] + i);
+    }
 }
 
 }  // namespace
@@ -200,21 +230,24 @@ extern "C" int moe_pool_load(const void *store_gate, const void *store_up, const
     if (chunks > 512) chunks = 512;
     if (chunks < 1) chunks = 1;
     // A store in host memory is read at the rate of the link to the host, a hundred times below HBM's: a
-    // launch that fills every wavefront slot of the chip would then hold them for a millisecond and keep the
-    // verify steps' workgroups waiting.  Sixteen workgroups have enough reads in flight for 9/10 of the
-    // link's rate (51 of 56 GB/s measured) and disturb the verify steps least (measured per cfg2 layer with a
-    // copy always in flight: +5.7 us with 16 workgroups, +7.5 with 32, +11.5 with 64, +15 with 1024).
+    // chip-wide launch would hold every wavefront slot for a millisecond and keep the verify steps'
+    // workgroups waiting.  Sixteen workgroups with one 16-byte word per thread in flight (64 KB) reach 9/10
+    // of the link's rate (51 of 56 GB/s) and disturb the verify steps least.  Measured per cfg2 layer with a
+    // copy always in flight: +5.7 us; 32 workgroups +7.5, 64 +11.5, a chip-wide launch +15; four words per
+    // thread in flight +8 (4 workgroups) to +12 (16).
+    bool narrow = false;
     {
         hipPointerAttribute_t attr;
-        if (hipPointerGetAttributes(&attr, store_gate) == hipSuccess) {
-            if (attr.type == hipMemoryTypeHost) {
-                int narrow = 16 / (max_fetch < 16 ? max_fetch : 16);
-                if (narrow < 1) narrow = 1;
-                if (narrow < chunks) chunks = narrow;
-            }
-        } else {
+        if (hipPointerGetAttributes(&attr, store_gate) == hipSuccess)
+            narrow = attr.type == hipMemoryTypeHost;
+        else
             (void)hipGetLastError();   // not a pointer the runtime knows: launch as for device memory
-        }
+    }
+    if (narrow) {
+        hipError_t e = launch_timed((const void *)load_narrow_kernel, dim3(16), dim3(256), params, 0,
+                                    (hipStream_t)stream, MOE_KERNEL_POOL_LOAD);
+        if (e == hipSuccess) e = hipGetLastError();
+        return e == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH;
     }
     hipError_t e = launch_timed((const void *)load_kernel, dim3(chunks, max_fetch), dim3(256), params, 0,
                                 (hipStream_t)stream, MOE_KERNEL_POOL_LOAD);

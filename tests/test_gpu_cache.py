@@ -261,3 +261,23 @@ def test_pool_load_from_a_store_in_pinned_host_memory():
             assert torch.equal(got[c], t[e]), (e, c)
         for c in (1, 2, 5):
             assert bool((got[c] == 7).all()), c
+
+
+@pytest.mark.parametrize("H,F", [(128, 136), (8, 8), (64, 200), (256, 256), (40, 72)])
+def test_pool_load_sizes_with_partial_groups(H, F):
+    """Matrix sizes that are not a multiple of what a workgroup copies per round (4 x 256 words of 16 bytes),
+    down to one smaller than a single wavefront's share: every word arrives, nothing else is touched."""
+    from paper_2603_09983_amd import binding as B
+    E, C = 7, 5
+    rng = np.random.default_rng(H * 1000 + F)
+    store = [_dev(rng.integers(-32768, 32767, size=shp, dtype=np.int16)) for shp in ((E, F, H), (E, F, H), (E, H, F))]
+    pools = [torch.full((C + 1, *t.shape[1:]), 7, dtype=torch.int16, device="cuda") for t in store]   # one guard row
+    i32 = dict(dtype=torch.int32, device="cuda")
+    fetch, slots, n = torch.tensor([6, 0, 3, 0, 0], **i32), torch.tensor([2, 4, 0, 0, 0], **i32), torch.tensor([3], **i32)
+    B.moe_pool_load(*store, *pools, fetch, slots, n, C, H, F)
+    torch.cuda.synchronize()
+    for t, p in zip(store, pools):
+        for e, c in ((6, 2), (0, 4), (3, 0)):
+            assert torch.equal(p[c], t[e]), (H, F, e, c)
+        for c in (1, 3, 5):
+            assert bool((p[c] == 7).all()), (H, F, c)

@@ -67,6 +67,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a)
     const int l = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
     const int N = a.N, C = a.C, K = a.K;
     const int tau = a.tau[l];
+    // (asked for with the other inputs, not where it is needed: one trip to memory instead of two)
+    int bud = 0x7fffffff;
+    if (a.budget) {
+        bud = a.budget[l];
+        bud = bud < 0 ? 0 : bud;
+    }
     const size_t base = (size_t)l * N;
 
     int s = 0, slot = -1;
@@ -114,10 +120,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a)
         a.slot_table[base + tid] = -1;
     }
     int n_fetch = tot_s[1] < n_free ? tot_s[1] : n_free;
-    if (a.budget) {
-        const int bud = a.budget[l] < 0 ? 0 : a.budget[l];
-        n_fetch = n_fetch < bud ? n_fetch : bud;
-    }
+    n_fetch = n_fetch < bud ? n_fetch : bud;
     if (cand) {
         const int r = rank_below(fkey_s, N, (K - s) * N + tid);
         if (r < n_fetch) {

@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the gate/up stream kernel from rocprofv3 counters (FETCH_SIZE scaled by
 # 2.000 from a 1 GiB copy, plus WRITE_SIZE), mean over the dispatches of the default workload; the
 # two --pmc runs and the calibration are recorded in profiles/stream_kernels_cfg2.txt.
-MEASURED_TRAFFIC_BYTES = {"cfg2": int((222746.4 + 148.5) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"cfg2": int((222757.6 + 148.5) * 1024)}
 
 
 def parse_args():
@@ -46,6 +46,10 @@ def parse_args():
                    help="timed region 1 replays a captured HIP graph of one pass over the layers (lifts the "
                         "host's launch rate off small layers); steps must be a multiple of the layer count")
     p.add_argument("--cpu-seconds", type=float, default=10.0)
+    p.add_argument("--prefetch-overlap", action="store_true",
+                   help="also measure the verify steps with the cache manager's copy running beside them on a "
+                        "second stream (store in device memory, then in pinned host memory); off by default so "
+                        "that a profile of the default run holds no overlapped launches")
     p.add_argument("--timeline", action="store_true",
                    help="with a library built with the timeline stamps (build.py --trace, MOE_SPAC_LIB): print to "
                         "stderr when the workgroups of the two streaming kernels reach each point of their life")
@@ -299,67 +303,70 @@ def main():
                 w[:n_move].copy_(sv)           # the pools go back to what the layer needs
             load_us = load_ms * 1e3 / load_n - ev_us
             moved = n_move * 6 * shape.H * shape.F
-            # the paper's asynchronous prefetch (Sec. 3.4): the same copy, into a staging pool no layer reads,
-            # on a second stream (default priority) while the verify steps run; one copy per verify step
-            stage = [torch.empty_like(sv) for sv in saved]
-            side = torch.cuda.Stream()
-            n_ov = 120
+            overlap = None
+            if args.prefetch_overlap:
+                # the paper's asynchronous prefetch (Sec. 3.4): the same copy, into a staging pool no layer reads,
+                # on a second stream (default priority) while the verify steps run; one copy per verify step
+                stage = [torch.empty_like(sv) for sv in saved]
+                side = torch.cuda.Stream()
+                n_ov = 120
 
-            def chain(with_prefetch):
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                for i in range(n_ov):
-                    step(i)
-                    if with_prefetch:
-                        B.moe_pool_load(*store, *stage, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F, stream=side)
-                torch.cuda.synchronize()
-                return (time.perf_counter() - t0) / n_ov * 1e6
+                def chain(with_prefetch):
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for i in range(n_ov):
+                        step(i)
+                        if with_prefetch:
+                            B.moe_pool_load(*store, *stage, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F, stream=side)
+                    torch.cuda.synchronize()
+                    return (time.perf_counter() - t0) / n_ov * 1e6
 
-            chain(True)
-            us_alone, us_with = chain(False), chain(True)
-            # ... and with the store where the paper keeps it: pinned host memory the device reads directly
-            host_store = [w.cpu().pin_memory() for w in store]
-            dev_store, store = store, host_store
-            B.moe_pool_load(*store, *stage, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for t in range(5):
+                chain(True)
+                us_alone, us_with = chain(False), chain(True)
+                # ... and with the store where the paper keeps it: pinned host memory the device reads directly
+                host_store = [w.cpu().pin_memory() for w in store]
+                dev_store, store = store, host_store
                 B.moe_pool_load(*store, *stage, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F)
-            torch.cuda.synchronize()
-            host_load_us = (time.perf_counter() - t0) / 5 * 1e6
-            # the copy takes many verify steps: keep one in flight on the second stream all the time
-            def chain_host():
                 torch.cuda.synchronize()
-                done = torch.cuda.Event()
-                n_loads = 0
                 t0 = time.perf_counter()
-                for i in range(4 * n_ov):
-                    step(i)
-                    if n_loads == 0 or done.query():
-                        B.moe_pool_load(*store, *stage, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F, stream=side)
-                        done.record(side)
-                        n_loads += 1
-                torch.cuda.current_stream().synchronize()
-                us = (time.perf_counter() - t0) / (4 * n_ov) * 1e6
+                for t in range(5):
+                    B.moe_pool_load(*store, *stage, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F)
                 torch.cuda.synchronize()
-                return us, n_loads
-            us_with_host, host_loads = chain_host()
-            store = dev_store
+                host_load_us = (time.perf_counter() - t0) / 5 * 1e6
+                # the copy takes many verify steps: keep one in flight on the second stream all the time
+                def chain_host():
+                    torch.cuda.synchronize()
+                    done = torch.cuda.Event()
+                    n_loads = 0
+                    t0 = time.perf_counter()
+                    for i in range(4 * n_ov):
+                        step(i)
+                        if n_loads == 0 or done.query():
+                            B.moe_pool_load(*store, *stage, mv_list, mv_slot, mv_n, n_move, shape.H, shape.F, stream=side)
+                            done.record(side)
+                            n_loads += 1
+                    torch.cuda.current_stream().synchronize()
+                    us = (time.perf_counter() - t0) / (4 * n_ov) * 1e6
+                    torch.cuda.synchronize()
+                    return us, n_loads
+                us_with_host, host_loads = chain_host()
+                store = dev_store
+                overlap = {"us_per_layer_alone": round(us_alone, 2),
+                           "us_per_layer_with_one_load_per_step_on_a_second_stream": round(us_with, 2),
+                           "bytes_loaded_per_step": moved,
+                           "note": "the copy moves 2x its bytes through HBM; alone it takes load_kernel.avg_us",
+                           "store_in_pinned_host_memory": {
+                               "load_us_alone": round(host_load_us, 1),
+                               "load_GBs": round(moved / host_load_us / 1e3, 1),
+                               "us_per_layer_with_a_load_always_in_flight": round(us_with_host, 2),
+                               "loads_started_during_%d_steps" % (4 * n_ov): host_loads}}
             est["cache_manager"] = {
                 "plan_kernel": {"avg_us": round(plan_ms * 1e3 / plan_n - ev_us, 2), "layers": L_est, "bound": "latency"},
                 "load_kernel": {"avg_us": round(load_us, 2), "experts": n_move, "bytes_moved": moved,
                                 "bound": "hbm", "achieved_GBs_read_plus_write": round(2 * moved / load_us / 1e3, 1),
                                 "frac_of_8TBs": round(2 * moved / load_us / 1e3 / HBM_PEAK_GBS, 4),
                                 "store": "device memory"},
-                "prefetch_overlap": {"us_per_layer_alone": round(us_alone, 2),
-                                     "us_per_layer_with_one_load_per_step_on_a_second_stream": round(us_with, 2),
-                                     "bytes_loaded_per_step": moved,
-                                     "note": "the copy moves 2x its bytes through HBM; alone it takes load_kernel.avg_us",
-                                     "store_in_pinned_host_memory": {
-                                         "load_us_alone": round(host_load_us, 1),
-                                         "load_GBs": round(moved / host_load_us / 1e3, 1),
-                                         "us_per_layer_with_a_load_always_in_flight": round(us_with_host, 2),
-                                         "loads_started_during_%d_steps" % (4 * n_ov): host_loads}}}
+                "prefetch_overlap": overlap}
         if not args.no_cpu_baseline:
             import oracle
             z = np.zeros(shape.E, dtype=np.int32)

@@ -395,10 +395,22 @@ def main():
             if el >= args.cpu_seconds or n >= 5000:
                 break
         cpu_s = el / n
+        # ... and on a single thread (a few runs: one takes ~16 times as long)
+        oracle.set_threads(1)
+        n1, t1 = 0, time.perf_counter()
+        while True:
+            oracle.layer_from_inputs(li)
+            n1 += 1
+            el1 = time.perf_counter() - t1
+            if el1 >= args.cpu_seconds / 3 or n1 >= 5000:
+                break
+        oracle.set_threads(threads)
         cpu = {"value": round(layer_bytes[0] / cpu_s / 1e9, 3), "unit": "GB/s", "cores": threads,
                "kind": "oracle", "us_per_layer": round(cpu_s * 1e6, 1),
                "sample": f"{n} runs of the whole layer 0 of this workload ({el:.1f}s), fp64 scalar C, "
-                         f"OpenMP over output rows"}
+                         f"OpenMP over output rows",
+               "one_thread": {"value": round(layer_bytes[0] / (el1 / n1) / 1e9, 3), "us_per_layer": round(el1 / n1 * 1e6, 1),
+                              "runs": n1}}
 
     out = {
         "metric": "verify-step MoE layer: expert-weight HBM GB/s (us per layer = 1000*ms_per_step), 1xMI355X",

@@ -11,7 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_spac.so")
 LIB_TRACE = os.path.join(HERE, "libmoe_spac_trace.so")   # same sources with the timeline stamps compiled in
 SOURCES = ["api.hip", "route.hip", "ffn.hip", "stream.hip", "estimator.hip", "balancer.hip", "cache.hip"]
-HEADERS = [os.path.join(CSRC, "moe_internal.h"), os.path.join(ROOT, "include", "moe_spac.h")]
+HEADERS = [os.path.join(CSRC, "moe_internal.h"), os.path.join(CSRC, "route_device.h"),
+           os.path.join(ROOT, "include", "moe_spac.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-fp32 instruction selection is switched off for every kernel of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -132,7 +132,10 @@ int moe_grouped_ffn(const void *hidden, const float *topk_w, const int32_t *slot
                     int out_bf16, int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Steps 1-4 for one verification batch in three launches on `stream` (four
- * for batches above 32 tokens).
+ * for batches above 32 tokens; two for batches of up to 16 tokens and 128
+ * experts when the environment variable MOE_SPAC_FUSED_ROUTING is set to
+ * something other than 0 at the time of the call: the routing steps then run
+ * at the head of the first FFN kernel, same outputs).
  * shape: host pointer.  shared_gate/up [n_shared,F_shared,H] and shared_down
  * [n_shared,H,F_shared] bf16 (NULL when n_shared = 0) are added with weight 1
  * for every token.  All step outputs are produced: topk_idx, topk_w [T,k];

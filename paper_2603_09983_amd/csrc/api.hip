@@ -1,6 +1,7 @@
 // C-ABI of libmoe_spac.so: argument checks and launch sequencing only.
 #include "../../include/moe_spac.h"
 #include "moe_internal.h"
+#include <cstdlib>
 
 using namespace moe;
 
@@ -252,7 +253,7 @@ namespace {
 int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const void *w_up, const void *w_down,
             const void *sh_gate, const void *sh_up, const void *sh_down, int T, int H, int F, int k, int C,
             int n_shared, int F_shared, const WsLayout &w, char *ws, void *out, int out_bf16, int accumulate,
-            hipStream_t s)
+            hipStream_t s, const RouteArgs *routing = nullptr)
 {
     // (the caller's routing / list kernel has given this call its number in the control block)
     int32_t *slot_count = (int32_t *)(ws + w.slot_count), *slot_offset = (int32_t *)(ws + w.slot_offset);
@@ -274,7 +275,8 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
         g.T = T; g.k = k; g.C = C;
         g.R = F; g.K = H; g.R_sh = F_shared; g.K_sh = H; g.n_shared = n_shared;
         g.KP = g.KP_sh = stream_panel_width(H);
-        e = launch_stream(g, true, nullptr, s);
+        // (routing != null: the gate/up launch does the routing steps itself)
+        e = routing ? launch_stream_routed(g, *routing, s) : launch_stream(g, true, nullptr, s);
         if (e != hipSuccess) return launch_failed(e);
         StreamArgs d = g;
         d.w0 = (const uint16_t *)w_down; d.w1 = nullptr;
@@ -381,6 +383,18 @@ extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const
     r.slot_count = (int32_t *)(ws + w.slot_count); r.slot_offset = (int32_t *)(ws + w.slot_offset);
     r.perm = (int32_t *)(ws + w.perm); r.pos = (int32_t *)(ws + w.pos);
     r.active_slots = (int32_t *)(ws + w.active); r.n_active = (unsigned *)(ws + w.ctrl) + kCtrlNActive;
+    // Small batches, on request (environment variable MOE_SPAC_FUSED_ROUTING set, read at each call): steps 1-3
+    // ride in front of the gate/up kernel, two launches per layer instead of three.  Measured 1.2-1.9 us per
+    // layer faster (cfg2 75.3 against 77.2 us); not the default because the routing inside that launch takes
+    // 12 us where the routing kernel takes 8 (the XCDs start such a launch up to 4 us apart, and workgroup 0
+    // has to wait for the logits of the last one), so the gain is only the launch that is saved.
+    const char *fused_env = getenv("MOE_SPAC_FUSED_ROUTING");
+    if (w.lists_pub && fused_env && fused_env[0] != '\0' && fused_env[0] != '0') {
+        r.lists_pub = (unsigned long long *)(ws + w.lists_pub);
+        return run_ffn(hidden, topk_w, w_gate, w_up, w_down, shared_gate, shared_up, shared_down, sh->T, sh->H,
+                       sh->F, sh->k, sh->C, sh->n_shared, sh->n_shared ? sh->F_shared : 0, w, ws, out, out_bf16,
+                       accumulate, s, &r);
+    }
     hipError_t e = launch_route(r, s);
     if (e != hipSuccess) return launch_failed(e);
     return run_ffn(hidden, topk_w, w_gate, w_up, w_down, shared_gate, shared_up, shared_down, sh->T, sh->H,

@@ -48,6 +48,21 @@ static inline bool use_stream_kernels(int T, int k, int C, int H, int F, int n_s
 
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Small batches: the gate/up kernel does the routing itself (dot products by all workgroups, ranking and
+// lists by workgroup 0, which hands the lists to the others as stamped 64-bit words, kListReplicas copies
+// so that not all workgroups poll the same lines).  One copy: n_active | slot_count[C] | slot_offset[C] |
+// active_slots[C] | perm[T*k].
+constexpr int kListReplicas = 16;
+constexpr int kMaxGroups = 1024;   // workgroups of that launch (one stamped word each, behind the copies)
+__host__ __device__ static inline size_t list_pub_entries(int T, int k, int C) { return (size_t)1 + 3 * (size_t)C + (size_t)T * k; }
+size_t route_lds_bytes(int E, int C, int A);   // LDS of the routing steps of one batch (route.hip)
+static inline bool use_fused_route(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared)
+{
+    if (T > 16 || E < 1 || E > 2 * kWave || (size_t)T * k > 1024 || C < 1 || C > kMaxC) return false;
+    if (!use_stream_kernels(T, k, C, H, F, n_shared, F_shared)) return false;
+    return route_lds_bytes(E, C, T * k) <= (size_t)kLdsBytes - 1024;
+}
+
 // Inside the routing kernel the logits travel from the workgroups that compute them to the one
 // that ranks them as 64-bit (tag, value) entries, tag = number of the call on this workspace: an
 // entry that carries the call's tag holds the call's value, so no counter and no fence is needed.
@@ -61,6 +76,7 @@ constexpr int kTagIdxEntries = 4096;   // (at most as many as the routing kernel
 // Byte offsets of the scratch arrays inside the caller's workspace.
 struct WsLayout {
     size_t ctrl, tagged, tagged_idx, perm, pos, slot_count, slot_offset, active, part, part_sh, act, act_sh, o, o_sh, total;
+    size_t lists_pub;   // stamped copies of the per-slot lists (gate/up kernel that does the routing itself), or 0
 };
 
 // control block words
@@ -75,6 +91,7 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
     WsLayout w;
     size_t A = (size_t)T * k;
     size_t o = 0;
+    w.lists_pub = 0;
     w.ctrl = o;        o += kCtrlBytes;
     w.tagged = o;      o += (size_t)kTagEntries * 8;   // (same place whatever the entry point and shape)
     w.tagged_idx = o;  o += (size_t)kTagIdxEntries * 8;
@@ -96,6 +113,10 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
         // (8 bytes per element: small batches store (call number, value) entries, see JoinArgs)
         w.o = o;       o += align256(A * H * 8);
         w.o_sh = o;    o += align256((size_t)n_shared * T * H * 8);
+        if (use_fused_route(T, k, E, C, H, F, n_shared, F_shared)) {
+            w.lists_pub = o;
+            o += align256((list_pub_entries(T, k, C) * kListReplicas + kMaxGroups) * 8);
+        }
     }
     w.total = o;
     return w;
@@ -127,6 +148,7 @@ struct RouteArgs {
     unsigned long long *tagged_logits;   // [T*E] (tag << 32 | value bits)
     unsigned long long *tagged_idx;      // [T*k] (tag << 32 | expert id), batches above 16 tokens
     unsigned *epoch;           // control word: tag of the last completed call
+    unsigned long long *lists_pub;   // kListReplicas x list_pub_entries stamped words, or null (nothing published)
 };
 
 // Arguments of the streaming kernels (gate/up: R = F rows, K = H; down: R = H rows, K = F).
@@ -184,6 +206,8 @@ hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_
 // join != null (down kernel only, stream_can_join() true): outputs leave as stamped 64-bit entries
 // and the kernel ends with the weighted sum into `out`; no combine launch is needed then
 hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join, hipStream_t s);
+// gate/up kernel that first does the routing steps described by `r` (use_fused_route() true, r.lists_pub set)
+hipError_t launch_stream_routed(const StreamArgs &a, const RouteArgs &r, hipStream_t s);
 bool stream_can_join(const StreamArgs &d);
 hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s);
 // Timeline stamps of the last gate/up and down launches: [2][kTimelineGroups][kTimelineWords] 64-bit words

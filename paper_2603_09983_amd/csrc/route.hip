@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
 
     const int32_t *idx = idx_in_lds ? (const int32_t *)L.idx_s : a.topk_idx;
     if (small) {
-        block_post_small(L.idx_s, L.tab_s, T, a.k, E, a.C, a, L.hist_s, L.cnt_s, L.scan_s, L.off_s);
+        block_post_small<false>(L.idx_s, L.tab_s, T, a.k, E, a.C, a, L.hist_s, L.cnt_s, L.scan_s, L.off_s, tag);
     } else if (a.slot_table) {
         // ids and slot table are read through LDS-typed pointers when they are in LDS (the usual case)
         if (idx_in_lds)
@@ -219,6 +219,8 @@ int route_num_cus()
     return n_cus;
 }
 }  // namespace
+
+size_t route_lds_bytes(int E, int C, int A) { return post_lds_bytes(E, C, A, true); }
 
 hipError_t launch_route(const RouteArgs &a, hipStream_t s)
 {

@@ -249,9 +249,20 @@ constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before work
 // bit mask of NW = ceil(T/32) words (a token names a slot at most once, the slot table being
 // one-to-one), so counts, offsets and list positions are population counts.  Same outputs as
 // block_post.
+// PUBLISH: every word of the per-slot lists also goes, stamped with the call's number, into each of the
+// kListReplicas copies behind r.lists_pub (entries no expert fills are stamped too, with -1, so that a
+// reader can wait for all of them).
+template <bool PUBLISH>
 __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, int E, int C, const RouteArgs &r,
-                                 lds_i32 *hist_s, lds_i32 *mask_s, lds_i32 *scan_s, lds_i32 *off_s)
+                                 lds_i32 *hist_s, lds_i32 *mask_s, lds_i32 *scan_s, lds_i32 *off_s, unsigned tag)
 {
+    auto publish = [&](int word, int value) {
+        if (!PUBLISH) return;
+        const unsigned long long e = ((unsigned long long)tag << 32) | (unsigned)value;
+        const size_t stride = list_pub_entries(T, kk, C);
+        for (int rep = 0; rep < kListReplicas; ++rep)
+            __hip_atomic_store(r.lists_pub + rep * stride + word, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
     const int A = T * kk, NW = (T + 31) >> 5;
     const bool valid = tid < A;
@@ -317,10 +328,15 @@ __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, 
         r.slot_count[tid] = cntv;
         r.slot_offset[tid] = off;
         if (cntv > 0) r.active_slots[na] = tid;
+        publish(1 + tid, cntv);
+        publish(1 + C + tid, off);
+        if (cntv > 0) publish(1 + 2 * C + na, tid);
+        if (tid >= tot_a) publish(1 + 2 * C + tid, -1);
     }
     if (tid == 0) {
         r.slot_offset[C] = tot_o;
         *r.n_active = (unsigned)tot_a;
+        publish(0, tot_a);
     }
     __syncthreads();
     // position of an assignment = offset of its slot + number of earlier tokens of that slot
@@ -330,8 +346,10 @@ __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, 
             p = off_s[c] + __popc((unsigned)mask_s[c * NW + (tok >> 5)] & ((1u << (tok & 31)) - 1u));
             for (int wd = 0; wd < (tok >> 5); ++wd) p += __popc((unsigned)mask_s[c * NW + wd]);
             r.perm[p] = tid;
+            publish(1 + 3 * C + p, tid);
         }
         r.pos[tid] = p;
+        if (tid >= tot_o) publish(1 + 3 * C + tid, -1);
     }
 }
 

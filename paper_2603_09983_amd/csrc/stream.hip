@@ -24,6 +24,7 @@
 // takes equal contiguous runs of it, so all workgroups are resident at once,
 // share the HBM bandwidth evenly and finish together.
 #include "moe_internal.h"
+#include "route_device.h"
 
 namespace moe {
 
@@ -41,7 +42,6 @@ constexpr int kWaves = 16;
 constexpr int kPieces = 4;     // 1 KB pieces per wavefront per tile (64 KB tile / 16 wavefronts)
 constexpr int kRowPad = kStreamRowPad;
 constexpr int kOutCap = kStreamOutCap;
-constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before a workgroup gives up waiting
 
 __device__ inline u32x4 ld_stream(const unsigned char *p)
 {
@@ -98,10 +98,12 @@ __device__ unsigned long long g_timeline[2][kTimelineGroups][kTimelineWords];
 //
 // WSPLIT (down kernel, shared experts whose items have another number of panels than the routed ones):
 // the item list is cut into runs of equal numbers of TILES instead of items.
-template <bool GATEUP, int NPI, int MODE, bool JOIN, bool WSPLIT = false>
-__global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes, JoinArgs jn)
+template <bool GATEUP, int NPI, int MODE, bool JOIN, bool WSPLIT, bool FUSED>
+__device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_lds_bytes, const JoinArgs &jn,
+                                            const RouteArgs &ra)
 {
     static_assert(!WSPLIT || !GATEUP, "gate/up items all have the panels of the hidden size");
+    static_assert(!FUSED || (GATEUP && MODE == 0 && !JOIN && !WSPLIT), "the routing steps ride on the small-batch gate/up kernel");
     static_assert(!JOIN || (!GATEUP && MODE < 2), "the join rides on the down kernel of batches up to 32 tokens");
     constexpr int NG = MODE == 0 ? 1 : 2;   // token groups of 16 multiplied per pass
     constexpr bool MULTIPASS = MODE == 2;
@@ -135,8 +137,11 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
     const int tiles = a.R / RPI, tiles_sh = a.n_shared ? a.R_sh / RPI : 0;
     const int n_sh_items = a.n_shared * tiles_sh;
     const int sh_per = n_sh_items / G, sh_rem = n_sh_items % G;
-    const int s_cnt = sh_per + (b < sh_rem ? 1 : 0);
-    const int s_start = b * sh_per + (b < sh_rem ? b : sh_rem);
+    // (FUSED: workgroup 0 also ranks the logits and builds the lists, which the others wait for; it takes
+    // the last place in the split and, below, a shorter run)
+    const int rk = FUSED ? (b == 0 ? G - 1 : b - 1) : b;
+    const int s_cnt = sh_per + (rk < sh_rem ? 1 : 0);
+    const int s_start = rk * sh_per + (rk < sh_rem ? rk : sh_rem);
     int r_start = 0, cnt = s_cnt;   // completed once the routing results are in LDS
 
     // ---- the walk that loads: tile (item pp, panel ppan) is the next one to put in flight ----
@@ -285,6 +290,104 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         }
     };
 
+    // FUSED: the routing steps come first, while nothing of the streaming state is alive yet (they need
+    // many registers of their own); workgroups other than 0 then request their shared expert's first tile and
+    // wait for the lists with that tile in flight.
+    unsigned rtag = 0;
+    if (FUSED) {
+        // ---- steps 1-3 inside this launch (Sec. 2.2, 2.3, App. D), as in the routing kernel ----
+        // every workgroup: its share of the T*E dot products, one per wavefront, each logit stored with the
+        // call's number as one 64-bit word
+        const int T = ra.T, H = ra.H, E = ra.E, TE = T * E, A = T * ra.k, C = ra.C;
+        rtag = *ra.epoch + 1u;
+        const size_t n_pub = list_pub_entries(T, ra.k, C);
+        // (workgroup 0 gives the call its number in the control block only when every workgroup has read the
+        // old one: each says so with a stamped word of its own)
+        unsigned long long *const seen = ra.lists_pub + (size_t)kListReplicas * n_pub;
+        if (tid == 0)
+            __hip_atomic_store(seen + b, ((unsigned long long)rtag << 32) | 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int tab_v = -1;
+        if (b == 0 && tid < E) tab_v = ra.slot_table[tid];
+        const uint16_t *x = (const uint16_t *)ra.hidden;
+        for (int q = b + w * G; q < TE; q += G * kWaves) {
+            const int t = q / E, e = q - t * E;
+            const float *wrow = ra.router_w + (size_t)e * H;
+            const uint16_t *xr = x + (size_t)t * H;
+            const float bias = ra.router_bias ? ra.router_bias[e] : 0.f;
+            float dot = 0.f;
+#pragma unroll 8
+            for (int h = lane * 4; h < H; h += kWave * 4) {
+                const float4 wv = *(const float4 *)(wrow + h);
+                const uint2 xv = *(const uint2 *)(xr + h);
+                dot += wv.x * bf16_lo(xv.x) + wv.y * bf16_hi(xv.x) + wv.z * bf16_lo(xv.y) + wv.w * bf16_hi(xv.y);
+            }
+#pragma unroll
+            for (int m = kWave / 2; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, kWave);
+            dot += bias;
+            if (lane == 0) {
+                __hip_atomic_store(ra.tagged_logits + q, ((unsigned long long)rtag << 32) | __float_as_uint(dot),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (ra.logits_opt) ra.logits_opt[q] = dot;
+            }
+        }
+        if (b == 0) {
+            // workgroup 0: one wavefront per token ranks its logits; then histogram, slot lookup, miss list and
+            // per-slot lists out of LDS (which nothing else uses yet), every word of the lists published
+            PostLds L = carve_lds((int *)lds, E, C, A);
+            if (tid < E) {
+                L.tab_s[tid] = tab_v;
+                L.hist_s[tid] = 0;
+            }
+            for (int i = tid; i < C * ((T + 31) >> 5); i += kThreads) L.cnt_s[i] = 0;
+            lds_f32 *lg = L.lg_s + w * lg_stride(E);
+            if (w < T) {
+                const int t = w;
+                const unsigned long long *src = ra.tagged_logits + (size_t)t * E;
+                for (int e0 = 0; e0 < E; e0 += kWave) {
+                    const int e = e0 + lane;
+                    unsigned long long v = (unsigned long long)rtag << 32;
+                    int polls = 0;
+                    for (;;) {
+                        if (e < E) v = __hip_atomic_load(src + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (__ballot((unsigned)(v >> 32) != rtag) == 0ull) break;
+                        if (++polls > kSpinLimit) {   // cannot happen on a healthy device; never wait for ever
+                            if (lane == 0) atomicOr(ra.error_flag, 1u);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                    if (e < E) {
+                        const float f = __uint_as_float((unsigned)v);
+                        lg[e] = (f == f) ? f : -INFINITY;
+                    }
+                }
+                if (lane < 4) lg[E + lane] = -INFINITY;
+                __builtin_amdgcn_wave_barrier();
+                // (up to 128 experts here: the ranking of more needs so many registers that the whole
+                // kernel would be launched with scratch memory; those batches keep the routing kernel)
+                if (E <= kWave)
+                    wave_topk_gate_n<1>(E, ra.k, ra.topk_idx + (size_t)t * ra.k, L.idx_s + t * ra.k,
+                                        ra.topk_w + (size_t)t * ra.k, lg, L.sel_s + w * kMaxK);
+                else
+                    wave_topk_gate_n<2>(E, ra.k, ra.topk_idx + (size_t)t * ra.k, L.idx_s + t * ra.k,
+                                        ra.topk_w + (size_t)t * ra.k, lg, L.sel_s + w * kMaxK);
+            }
+            __syncthreads();
+            block_post_small<true>(L.idx_s, L.tab_s, T, ra.k, E, C, ra, L.hist_s, L.cnt_s, L.scan_s, L.off_s, rtag);
+            for (int i = tid; i < G; i += kThreads) {
+                int polls = 0;
+                while ((unsigned)(__hip_atomic_load(seen + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != rtag) {
+                    if (++polls > kSpinLimit) {
+                        atomicOr(ra.error_flag, 1u);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+            }
+            __syncthreads();   // (also: the LDS used above is free again)
+            if (tid == 0) *ra.epoch = rtag;
+        }
+    }
     if (s_cnt > 0) {
         const int e = s_start / tiles_sh;
         prod_set(true, e, s_start - e * tiles_sh);
@@ -292,22 +395,66 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
         pvalid = true;
         issue(0);
     }
-    // one trip to memory for everything the routing step left behind
-    for (int i = tid; i < a.C; i += kThreads) {
-        count_s[i] = a.slot_count[i];
-        offset_s[i] = a.slot_offset[i];
-        active_s[i] = a.active_slots[i];
+    int n_act;
+    if (FUSED) {
+        // every workgroup: the lists, from one of the published copies.  One lane watches the first word,
+        // gently (255 workgroups asking for all words all the time would be a load of its own on the few
+        // memory channels the copies live in); once it is there the workgroup reads them all.
+        const int C = ra.C;
+        const size_t n_pub = list_pub_entries(ra.T, ra.k, C);
+        const unsigned long long *pub = ra.lists_pub + (size_t)(b % kListReplicas) * n_pub;
+        if (tid == 0 && b != 0) {
+            int polls = 0;
+            while ((unsigned)(__hip_atomic_load(pub, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != rtag) {
+                if (++polls > kSpinLimit) break;   // (the loop below reports it)
+                __builtin_amdgcn_s_sleep(16);
+            }
+        }
+        __syncthreads();
+        for (int i = tid; i < (int)n_pub; i += kThreads) {
+            unsigned long long v = 0;
+            int polls = 0;
+            for (;;) {
+                v = __hip_atomic_load(pub + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((unsigned)(v >> 32) == rtag) break;
+                if (++polls > kSpinLimit) {
+                    atomicOr(ra.error_flag, 1u);
+                    v = 0;   // (stay inside every array below)
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+            }
+            const int val = (int)(unsigned)v;
+            if (i == 0) odesc_s[0] = val;                                   // n_active (read back below)
+            else if (i <= C) count_s[i - 1] = val;
+            else if (i <= 2 * C) offset_s[i - 1 - C] = val;
+            else if (i <= 3 * C) active_s[i - 1 - 2 * C] = val < 0 ? 0 : val;
+            else perm_s[i - 1 - 3 * C] = (val < 0 ? 0 : val) / a.k;         // token of each list entry
+        }
+        __syncthreads();
+        n_act = odesc_s[0];
+        n_act = n_act < 0 ? 0 : n_act > C ? C : n_act;
+    } else {
+        // one trip to memory for everything the routing step left behind
+        for (int i = tid; i < a.C; i += kThreads) {
+            count_s[i] = a.slot_count[i];
+            offset_s[i] = a.slot_offset[i];
+            active_s[i] = a.active_slots[i];
+        }
+        for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = a.perm[i] / a.k;   // token of each list entry
+        n_act = (int)(*a.n_active);
+        __syncthreads();
     }
-    for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = a.perm[i] / a.k;   // token of each list entry
-    const int n_act = (int)(*a.n_active);
-    __syncthreads();
 
     // equal runs of the whole item list; this workgroup's run = its shared items, then routed ones
     if (!WSPLIT) {
-        const int total = n_sh_items + n_act * tiles;
+        // (FUSED: workgroup 0 starts its run a few microseconds late: two items fewer for it)
+        const int late = FUSED && n_act * tiles >= 4 * G ? 2 : 0;
+        const int total = n_sh_items + n_act * tiles + late;
         const int per = total / G, rem = total % G;
-        cnt = per + (b < rem ? 1 : 0);
-        r_start = b * per + (b < rem ? b : rem) - s_start;
+        cnt = per + (rk < rem ? 1 : 0);
+        r_start = rk * per + (rk < rem ? rk : rem) - s_start;
+        if (rk == G - 1) cnt -= late;
     } else {
         // Workgroup x starts at routed item max(0, x * total tiles / G - tiles of the shared items
         // before x) / panels per routed item: that never decreases with x, is 0 for x = 0 and the
@@ -576,6 +723,22 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
 #endif
 }
 
+template <bool GATEUP, int NPI, int MODE, bool JOIN, bool WSPLIT = false>
+__global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile_lds_bytes, JoinArgs jn)
+{
+    const RouteArgs none = {};
+    stream_body<GATEUP, NPI, MODE, JOIN, WSPLIT, false>(a, tile_lds_bytes, jn, none);
+}
+
+// The small-batch gate/up kernel with steps 1-3 of the layer in front of it (one launch less per layer, and the
+// shared experts' weights stream while the routing runs).
+template <int NPI>
+__global__ __launch_bounds__(kThreads) void routed_stream_kernel(StreamArgs a, int tile_lds_bytes, RouteArgs ra)
+{
+    const JoinArgs none = {};
+    stream_body<true, NPI, 0, false, false, true>(a, tile_lds_bytes, none, ra);
+}
+
 // out[t,:] (+)= sum_j w[t,j] * o[pos[t,j],:] + sum_i o_sh[i,t,:], in a fixed order
 __global__ __launch_bounds__(128) void combine_rows_kernel(CombineArgs a, const float *o, const float *o_sh)
 {
@@ -690,6 +853,34 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join,
     if (join) jargs = *join;
     void *params[] = {&args, &tile_i, &jargs};
     hipError_t le = launch_timed(fn, dim3(grid), dim3(kThreads), params, lds, s, gateup ? 2 : 4);
+    if (le != hipSuccess) return le;
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_routed(const StreamArgs &a, const RouteArgs &r, hipStream_t s)
+{
+    if (!r.lists_pub || a.T > 16) return hipErrorInvalidValue;
+    const int kp_max = a.KP > a.KP_sh ? a.KP : a.KP_sh;
+    const size_t tile = (size_t)16 * (2 * kp_max + kRowPad);
+    size_t lds = stream_lds_need(kp_max, a.T, a.k, a.C, true);
+    const size_t lds_route = post_lds_bytes(r.E, r.C, r.T * r.k, true);
+    lds = lds > lds_route ? lds : lds_route;
+    if (lds > (size_t)kLdsBytes) return hipErrorInvalidValue;
+    const int npi = (kp_max / 32 + kWaves - 1) / kWaves;
+    static const void *const fns[4] = {(const void *)routed_stream_kernel<1>, (const void *)routed_stream_kernel<2>,
+                                       (const void *)routed_stream_kernel<3>, (const void *)routed_stream_kernel<4>};
+    const void *fn = fns[npi - 1];
+    static bool attr_done[4] = {};
+    if (!attr_done[npi - 1]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_done[npi - 1] = true;
+    }
+    int tile_i = (int)tile;
+    StreamArgs args = a;
+    RouteArgs rargs = r;
+    void *params[] = {&args, &tile_i, &rargs};
+    hipError_t le = launch_timed(fn, dim3(num_cus()), dim3(kThreads), params, lds, s, 2);
     if (le != hipSuccess) return le;
     return hipGetLastError();
 }

@@ -257,3 +257,20 @@ def test_runtime_errors_leave_outputs_untouched(G):
     assert rc == B.ERR_ALIGN
     with pytest.raises(B.MoeError):
         B.moe_grouped_ffn(x, w, si, pool, pool, pool, 4, 128, 128, 2, 2, out, 0, 0, ws[:64])
+
+
+@pytest.mark.parametrize("name", ["ragged_F", "T1_k1", "k_eq_E", "zipf_E60", "E128_k8", "shared_wide_T9"])
+def test_verify_layer_with_the_routing_inside_the_gate_up_launch(G, name, monkeypatch):
+    """The optional two-launch form of the layer (routing steps in front of the gate/up kernel, lists handed to
+    the other workgroups as stamped words): same outputs, to the same bar; then the default form again on the
+    same workspace."""
+    li = layer(100 + sorted(SMALL_CASES).index(name), **dict(SMALL_CASES[name]))
+    d = G.upload(li)
+    monkeypatch.setenv("MOE_SPAC_FUSED_ROUTING", "1")
+    buf = G.run_layer(d)
+    G.check_against_oracle(li, buf, tag=name + "/fused")
+    buf = G.run_layer(d, buf)
+    G.check_against_oracle(li, buf, tag=name + "/fused again")
+    monkeypatch.delenv("MOE_SPAC_FUSED_ROUTING")
+    buf = G.run_layer(d, buf)
+    G.check_against_oracle(li, buf, tag=name + "/separate")

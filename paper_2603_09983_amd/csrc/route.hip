@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
         if (lane < 4) lg[E + lane] = -INFINITY;
         __builtin_amdgcn_wave_barrier();
         wave_topk_gate(E, a.k, a.topk_idx + (size_t)t * a.k, idx_in_lds ? L.idx_s + t * a.k : nullptr,
-                       a.topk_w + (size_t)t * a.k, lg, L.sel_s + w * kMaxK);
+                       a.topk_w + (size_t)t * a.k, lg);
         if (share_ids) {
             // (LDS operations of one wavefront execute in order: the ids written above are visible)
             __builtin_amdgcn_wave_barrier();

@@ -26,69 +26,100 @@ typedef __attribute__((address_space(3))) const f32x4v lds_f32x4;
 typedef __attribute__((address_space(1))) int32_t g_i32;
 typedef __attribute__((address_space(1))) float g_f32;
 
-// One wavefront ranks the E logits of one token: rank(e) = number of experts
-// that beat e (larger logit, or equal logit and lower id).  The experts of
-// rank 0..k-1 are the Top-k in descending-logit order; their gate is
-// exp(s - s_max) normalised over those k, summed in rank order.  Lane l owns
-// experts l, l+64, ...; the caller has put the logits into `lg` (LDS private to
-// the wavefront: E floats, NaN replaced by -inf, four -inf entries behind the
-// E-th); `sel` (k floats) collects the selected ones.
+// Value of v in the lane n places further on inside the row of 16 lanes, wrapping round (register to
+// register, no trip through LDS): data-parallel-primitive control row_ror:n = 0x120 + n.
+template <int N>
+__device__ __forceinline__ unsigned row_rotate(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x120 + N, 0xf, 0xf, false);
+}
+
+// Maximum of x over the 64 lanes of a wavefront (all of them active), as a uniform value.  Four
+// rotations leave each row's maximum in every lane of the row; the four row results are then read
+// into scalar registers.
+__device__ __forceinline__ unsigned wave_max_u32(unsigned x)
+{
+    unsigned y;
+    y = row_rotate<1>(x); x = x > y ? x : y;
+    y = row_rotate<2>(x); x = x > y ? x : y;
+    y = row_rotate<4>(x); x = x > y ? x : y;
+    y = row_rotate<8>(x); x = x > y ? x : y;
+    const unsigned a = (unsigned)__builtin_amdgcn_readlane((int)x, 0), b = (unsigned)__builtin_amdgcn_readlane((int)x, 16);
+    const unsigned c = (unsigned)__builtin_amdgcn_readlane((int)x, 32), d = (unsigned)__builtin_amdgcn_readlane((int)x, 48);
+    const unsigned ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
+
+// One wavefront picks the Top-k of the E logits of one token, best first: k times the maximum over the
+// wavefront, ties to the lower expert id, the winner taken out.  Logits are compared as unsigned keys
+// that order like the floats (-0 counted as +0; key 0 = taken or no expert, below every float).  The
+// gate is exp(s - s_max) normalised over the k, summed in rank order.  Lane l owns experts l, l+64, ...;
+// the caller has put the logits into `lg` (LDS private to the wavefront: E floats, NaN replaced by -inf).
+// Lane j < k ends up with the j-th expert and writes it out.  Needs k <= E and all 64 lanes active.
 template <int NLOC>
 __device__ __forceinline__ void wave_topk_gate_n(int E, int k, int32_t *idx_out_, lds_i32 *idx_lds,
-                                                 float *w_out_, lds_f32 *lg, lds_f32 *sel)
+                                                 float *w_out_, lds_f32 *lg)
 {
     g_i32 *idx_out = (g_i32 *)(uintptr_t)idx_out_;
     g_f32 *w_out = (g_f32 *)(uintptr_t)w_out_;
     const int lane = threadIdx.x & (kWave - 1);
-    float v[NLOC];
-    int rank[NLOC];
+    unsigned key[NLOC];
 #pragma unroll
     for (int i = 0; i < NLOC; ++i) {
-        int e = lane + kWave * i;
-        v[i] = e < E ? lg[e] : -INFINITY;
-        rank[i] = 0;
+        const int e = lane + kWave * i;
+        float f = e < E ? lg[e] : 0.f;
+        f = f == 0.f ? 0.f : f;
+        const unsigned u = __float_as_uint(f);
+        key[i] = e < E ? ((u & 0x80000000u) ? ~u : (u | 0x80000000u)) : 0u;
     }
-#pragma unroll 4
-    for (int e2 = 0; e2 < E; e2 += 4) {
-        const f32x4v o4 = *(lds_f32x4 *)(lg + e2);   // same address in every lane: a broadcast read
-        const float o[4] = {o4[0], o4[1], o4[2], o4[3]};
+    unsigned my_key = 0x80000000u;   // (the key of 0.0f)
+    int my_e = 0;
+    for (int j = 0; j < k; ++j) {
+        unsigned m = key[0];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int i = 1; i < NLOC; ++i) m = m > key[i] ? m : key[i];
+        const unsigned best = wave_max_u32(m);
+        // lowest id among the experts that hold it: the lowest i that has one, then the lowest lane
+        int win_i = 0;
+        unsigned long long win_bal = 0ull;
 #pragma unroll
-            for (int i = 0; i < NLOC; ++i) {
-                int e = lane + kWave * i;
-                rank[i] += (o[u] > v[i] || (o[u] == v[i] && e2 + u < e)) ? 1 : 0;
+        for (int i = NLOC - 1; i >= 0; --i) {
+            const unsigned long long bal = __ballot(key[i] == best);
+            if (bal) {
+                win_bal = bal;
+                win_i = i;
             }
         }
-    }
-#pragma unroll
-    for (int i = 0; i < NLOC; ++i) {
-        int e = lane + kWave * i;
-        if (e < E && rank[i] < k) sel[rank[i]] = v[i];
-    }
-    // (LDS operations of one wavefront execute in order: the reads below see the writes above)
-    __builtin_amdgcn_wave_barrier();
-    const float smax = sel[0];
-    float den = 0.f;
-    for (int j = 0; j < k; ++j) den += __expf(sel[j] - smax);
-#pragma unroll
-    for (int i = 0; i < NLOC; ++i) {
-        int e = lane + kWave * i;
-        if (e < E && rank[i] < k) {
-            if (idx_lds) idx_lds[rank[i]] = e;
-            idx_out[rank[i]] = e;
-            w_out[rank[i]] = __expf(v[i] - smax) / den;
+        const int win_lane = win_bal ? __ffsll((long long)win_bal) - 1 : 0;
+        int e = win_lane + kWave * win_i;
+        e = e < E ? e : E - 1;   // (only if k > E: stay inside every table)
+        if (lane == j) {
+            my_key = best;
+            my_e = e;
         }
+#pragma unroll
+        for (int i = 0; i < NLOC; ++i)
+            if (i == win_i && lane == win_lane) key[i] = 0u;
+    }
+    const float my_s = __uint_as_float((my_key & 0x80000000u) ? (my_key ^ 0x80000000u) : ~my_key);
+    const float smax = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(my_s), 0));
+    const float ex = lane < k ? __expf(my_s - smax) : 0.f;
+    float den = 0.f;
+    for (int j = 0; j < k; ++j) den += __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(ex), j));
+    if (lane < k) {
+        if (idx_lds) idx_lds[lane] = my_e;
+        idx_out[lane] = my_e;
+        w_out[lane] = ex / den;
     }
 }
 
 __device__ __forceinline__ void wave_topk_gate(int E, int k, int32_t *idx_out, lds_i32 *idx_lds, float *w_out,
-                                               lds_f32 *lg, lds_f32 *sel)
+                                               lds_f32 *lg)
 {
-    if (E <= kWave) wave_topk_gate_n<1>(E, k, idx_out, idx_lds, w_out, lg, sel);
-    else if (E <= 2 * kWave) wave_topk_gate_n<2>(E, k, idx_out, idx_lds, w_out, lg, sel);
-    else if (E <= 4 * kWave) wave_topk_gate_n<4>(E, k, idx_out, idx_lds, w_out, lg, sel);
-    else wave_topk_gate_n<kMaxEPL>(E, k, idx_out, idx_lds, w_out, lg, sel);
+    if (E <= kWave) wave_topk_gate_n<1>(E, k, idx_out, idx_lds, w_out, lg);
+    else if (E <= 2 * kWave) wave_topk_gate_n<2>(E, k, idx_out, idx_lds, w_out, lg);
+    else if (E <= 4 * kWave) wave_topk_gate_n<4>(E, k, idx_out, idx_lds, w_out, lg);
+    else wave_topk_gate_n<kMaxEPL>(E, k, idx_out, idx_lds, w_out, lg);
 }
 
 // logits of one token in LDS: E rounded up to a multiple of four, plus four pad entries
@@ -283,26 +314,24 @@ __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, 
     const int before = __popcll(bal & ((1ull << lane) - 1ull));
     if (lane == 0) scan_s[w] = __popcll(bal);
     __syncthreads();
-    // slot `tid`: its token count; prefix sums of (count, count > 0) inside the wavefront
+    // slot `tid`: its token count; prefix sums of (count, count > 0) inside the wavefront, from ballots:
+    // of the flag, and of each bit of the count (a count is at most T <= 128)
     int cntv = 0;
     if (tid < C)
         for (int wd = 0; wd < NW; ++wd) cntv += __popc((unsigned)mask_s[tid * NW + wd]);
-    int inc_o = cntv, inc_a = cntv > 0 ? 1 : 0;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int to = __shfl_up(inc_o, d, kWave), ta = __shfl_up(inc_a, d, kWave);
-        if (lane >= d) {
-            inc_o += to;
-            inc_a += ta;
-        }
-    }
+    const unsigned long long upto = (2ull << lane) - 1ull;   // lanes 0..lane
+    const int inc_a = __popcll(__ballot(cntv > 0) & upto);
+    int inc_o = 0;
+    for (int bit = 0; (1 << bit) <= T; ++bit) inc_o += __popcll(__ballot((cntv >> bit) & 1) & upto) << bit;
     if (lane == kWave - 1) {
         scan_s[16 + w] = inc_o;
         scan_s[32 + w] = inc_a;
     }
+    // (only the wavefronts that hold an assignment or a slot have anything to add)
+    const int nwv = ((A > C ? A : C) + kWave - 1) / kWave;
     {
         int wave_base = 0, total = 0;
-        for (int i = 0; i < kRouteWaves; ++i) {
+        for (int i = 0; i < nwv; ++i) {
             const int v = scan_s[i];
             if (i < w) wave_base += v;
             total += v;
@@ -313,7 +342,7 @@ __device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, 
     }
     __syncthreads();
     int base_o = 0, base_a = 0, tot_o = 0, tot_a = 0;
-    for (int i = 0; i < kRouteWaves; ++i) {
+    for (int i = 0; i < nwv; ++i) {
         const int vo = scan_s[16 + i], va = scan_s[32 + i];
         if (i < w) {
             base_o += vo;

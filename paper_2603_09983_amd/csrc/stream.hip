@@ -367,10 +367,10 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                 // kernel would be launched with scratch memory; those batches keep the routing kernel)
                 if (E <= kWave)
                     wave_topk_gate_n<1>(E, ra.k, ra.topk_idx + (size_t)t * ra.k, L.idx_s + t * ra.k,
-                                        ra.topk_w + (size_t)t * ra.k, lg, L.sel_s + w * kMaxK);
+                                        ra.topk_w + (size_t)t * ra.k, lg);
                 else
                     wave_topk_gate_n<2>(E, ra.k, ra.topk_idx + (size_t)t * ra.k, L.idx_s + t * ra.k,
-                                        ra.topk_w + (size_t)t * ra.k, lg, L.sel_s + w * kMaxK);
+                                        ra.topk_w + (size_t)t * ra.k, lg);
             }
             __syncthreads();
             block_post_small<true>(L.idx_s, L.tab_s, T, ra.k, E, C, ra, L.hist_s, L.cnt_s, L.scan_s, L.off_s, rtag);

@@ -441,7 +441,11 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
             offset_s[i] = a.slot_offset[i];
             active_s[i] = a.active_slots[i];
         }
-        for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = a.perm[i] / a.k;   // token of each list entry
+        // token of each list entry (gate/up) | row of each assignment's output, -1 = not resident (join)
+        if (GATEUP)
+            for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = a.perm[i] / a.k;
+        else if (JOIN)
+            for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = jn.pos[i];
         n_act = (int)(*a.n_active);
         __syncthreads();
     }
@@ -478,13 +482,15 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         typedef unsigned long long u64;
         const int S = a.k + a.n_shared, nent = a.T * 8 * S;
         float *val_s = (float *)tile_s;   // [token][column of the strip][source]; the tile buffer is free by now
+        float *gw_s = red_s;              // gate weights, on their way while the entries are waited for
+        for (int i = tid; i < a.T * a.k; i += kThreads) gw_s[i] = jn.topk_w[i];
         for (int u = b; u < a.R / 8; u += G) {
             __syncthreads();
             for (int i = tid; i < nent; i += kThreads) {
                 const int tc = i / S, src = i - tc * S, t = tc >> 3, col = u * 8 + (tc & 7);
                 const u64 *p = nullptr;
                 if (src < a.k) {
-                    const int row = jn.pos[t * a.k + src];
+                    const int row = perm_s[t * a.k + src];
                     if (row >= 0) p = (const u64 *)a.out + (size_t)row * a.R + col;
                 } else {
                     p = (const u64 *)a.out_sh + ((size_t)(src - a.k) * a.T + t) * a.R_sh + col;
@@ -514,7 +520,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                 if (jn.accumulate)
                     acc = jn.out_bf16 ? __uint_as_float((uint32_t)((const uint16_t *)jn.out)[o] << 16)
                                       : ((const float *)jn.out)[o];
-                for (int jj = 0; jj < a.k; ++jj) acc += jn.topk_w[t * a.k + jj] * val_s[tid * S + jj];
+                for (int jj = 0; jj < a.k; ++jj) acc += gw_s[t * a.k + jj] * val_s[tid * S + jj];
                 for (int i = 0; i < a.n_shared; ++i) acc += val_s[tid * S + a.k + i];
                 if (jn.out_bf16) ((uint16_t *)jn.out)[o] = (uint16_t)f32_to_bf16_rne(acc);
                 else ((float *)jn.out)[o] = acc;
@@ -575,7 +581,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
 
     // Results wait in LDS and leave in batches: a store in the steady state would make every
     // later wait on the weight loads a wait for everything (loads and stores share one counter).
-    auto flush = [&]() {
+    auto flush = [&](bool resume = true) {
         // one wavefront per waiting record, so the whole batch leaves in one round of stores
         for (int r = flushed + w; r < orec; r += kWaves) {
             const int slot = r % kOutCap;
@@ -614,7 +620,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
             }
         }
         flushed = orec;
-        __builtin_amdgcn_s_waitcnt(0);   // every counter to zero: the stores are done before streaming resumes
+        if (resume) __builtin_amdgcn_s_waitcnt(0);   // every counter to zero: the stores are done before streaming resumes
     };
 
     // The sixteen partial 16x16 results of each token group (already posted in red_s, barrier passed),
@@ -711,7 +717,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
     if (t < ntiles) step(1);
     MOE_STAMP(tl_loop);
     __syncthreads();
-    flush();
+    flush(false);
     MOE_STAMP(tl_flush);
     join();
 #ifdef MOE_STREAM_TRACE

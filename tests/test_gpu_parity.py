@@ -190,6 +190,36 @@ def test_route_topk_ties_go_to_the_lower_expert(G):
     assert torch.all(w == 1.0 / k).item()
 
 
+@pytest.mark.parametrize("T,E,k", [(3, 12, 5), (9, 64, 6), (5, 100, 8), (17, 128, 8), (4, 200, 7), (6, 512, 8),
+                                   (33, 64, 6), (2, 70, 64)])
+def test_route_topk_many_ties_and_minus_infinity(G, T, E, k):
+    """Logits from a handful of exact values (so most comparisons are ties, which go to the lower id) and some
+    experts at minus infinity through the bias, in every width of the per-lane expert table; one case selects
+    more experts than have a finite logit."""
+    from paper_2603_09983_amd import binding as B
+    rng = np.random.default_rng(1000 * E + k)
+    H = 64
+    hid = np.zeros((T, H), dtype=np.float32)
+    hid[:, 0] = rng.choice([-2.0, -1.0, 1.0, 2.0], size=T)         # only column 0 counts: the dot products are exact
+    rw = rng.standard_normal((E, H)).astype(np.float32)
+    rw[:, 0] = rng.integers(-2, 3, size=E).astype(np.float32)
+    bias = np.zeros(E, dtype=np.float32)
+    n_inf = E - k // 2 if k == 64 else E // 4
+    bias[rng.choice(E, n_inf, replace=False)] = -np.inf
+    ws = B.new_workspace(B.make_shape(T, H, E, k, 32, 0))
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    logits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    B.moe_route_topk(torch.from_numpy(hid).cuda().to(torch.bfloat16), G.dev(rw), G.dev(bias), T, H, E, k, idx, w,
+                     logits, ws)
+    torch.cuda.synchronize()
+    ref_logits = hid[:, :1].astype(np.float64) * rw[:, 0].astype(np.float64)[None, :] + bias.astype(np.float64)[None, :]
+    assert np.array_equal(logits.cpu().numpy().astype(np.float64), ref_logits)
+    ridx, rg = oracle.topk_gate(ref_logits, k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    assert np.max(np.abs(w.cpu().numpy() - rg)) <= G.GATE_ATOL
+
+
 def test_histogram_entry_point_small_and_large(G):
     from paper_2603_09983_amd import binding as B
     rng = np.random.default_rng(3)

@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the gate/up stream kernel from rocprofv3 counters (FETCH_SIZE scaled by
 # 2.000 from a 1 GiB copy, plus WRITE_SIZE), mean over the dispatches of the default workload; the
 # two --pmc runs and the calibration are recorded in profiles/stream_kernels_cfg2.txt.
-MEASURED_TRAFFIC_BYTES = {"cfg2": int((222757.6 + 148.5) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"cfg2": int((222752.0 + 148.5) * 1024)}
 
 
 def parse_args():

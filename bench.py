@@ -42,6 +42,9 @@ def parse_args():
     p.add_argument("--copies", type=int, default=0, help="distinct layers to rotate over (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-estimator", action="store_true", help="skip the utility-estimator measurement")
+    p.add_argument("--no-fused-option", action="store_true",
+                   help="skip the extra timed region that runs the same steps with the routing inside the gate/up "
+                        "launch (MOE_SPAC_FUSED_ROUTING=1; batches of up to 16 tokens)")
     p.add_argument("--graph", action="store_true",
                    help="timed region 1 replays a captured HIP graph of one pass over the layers (lifts the "
                         "host's launch rate off small layers); steps must be a multiple of the layer count")
@@ -222,6 +225,28 @@ def main():
         d_s = down_ms * 1e-3 / down_n - ev_us * 1e-6
         roofline["down_kernel"] = {"achieved": round((bytes_total / args.steps / 3.0) / d_s / 1e9, 1),
                                    "avg_kernel_us": round(d_s * 1e6, 2)}
+
+    # The library's two-launch option (routing steps at the head of the gate/up kernel), timed like region 1.
+    # It is an option, not the default, so `value` above is not this number.
+    fused_opt = None
+    env_fused = os.environ.get("MOE_SPAC_FUSED_ROUTING", "") not in ("", "0")
+    if (not args.no_fused_option and not env_fused and not args.graph and shape.T <= 16 and shape.E <= 128
+            and shape.C >= 1):
+        os.environ["MOE_SPAC_FUSED_ROUTING"] = "1"
+        try:
+            for i in range(args.warmup):
+                step(i)
+            torch.cuda.synchronize()
+            tf0 = time.perf_counter()
+            for i in range(args.steps):
+                step(i)
+            torch.cuda.synchronize()
+            tf1 = time.perf_counter()
+        finally:
+            del os.environ["MOE_SPAC_FUSED_ROUTING"]
+        fused_opt = {"env": "MOE_SPAC_FUSED_ROUTING=1", "launches_per_layer": 2,
+                     "us_per_layer": round((tf1 - tf0) * 1e6 / args.steps, 2),
+                     "value": round(bytes_total / (tf1 - tf0) / 1e9, 1), "unit": "GB/s"}
 
     # NEXT row: the Speculative Utility Estimator consuming the histograms of 24 layers per inference
     # step (one launch for all layers); frequencies are synthetic histograms of T*k assignments.
@@ -421,8 +446,10 @@ def main():
         "data": "synthetic", "launch": "hip graph replay" if args.graph else "eager",
         "config": {"workload": desc, "layers": len(layers),
                                         "mean_weight_bytes_per_layer": int(np.mean(layer_bytes))},
-        "roofline": roofline, "cpu_baseline": cpu, "estimator": est,
+        "roofline": roofline, "cpu_baseline": cpu, "estimator": est, "fused_routing_option": fused_opt,
     }
+    if env_fused:
+        out["config"]["routing"] = "inside the gate/up launch (MOE_SPAC_FUSED_ROUTING set by the caller)"
     if args.timeline:
         print_timeline(B, torch, np, step, len(layers))
     print(json.dumps(out))

@@ -96,7 +96,6 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
                 lg[e] = (f == f) ? f : -INFINITY;   // NaN cannot win a comparison; rank it last
             }
         }
-        if (lane < 4) lg[E + lane] = -INFINITY;
         __builtin_amdgcn_wave_barrier();
         wave_topk_gate(E, a.k, a.topk_idx + (size_t)t * a.k, idx_in_lds ? L.idx_s + t * a.k : nullptr,
                        a.topk_w + (size_t)t * a.k, lg);

@@ -122,8 +122,8 @@ __device__ __forceinline__ void wave_topk_gate(int E, int k, int32_t *idx_out, l
     else wave_topk_gate_n<kMaxEPL>(E, k, idx_out, idx_lds, w_out, lg);
 }
 
-// logits of one token in LDS: E rounded up to a multiple of four, plus four pad entries
-__host__ __device__ inline int lg_stride(int E) { return ((E + 3) & ~3) + 4; }
+// logits of one token in LDS: E floats, each wavefront's row starting on a multiple of four
+__host__ __device__ inline int lg_stride(int E) { return (E + 3) & ~3; }
 
 
 // hist[e] = number of assignments naming expert e (LDS integer atomics).
@@ -243,10 +243,10 @@ __device__ void block_post(IdxPtr idx, TabPtr slot_table, int A, int E, int C, i
     }
 }
 
-// dynamic LDS: hist_s[E] tab_s[E] cnt_s[4C] off_s[C+1] scan_s[48] sidx_s[cap] idx_s[cap] lg_s[waves*E] sel_s[waves*64]
+// dynamic LDS: hist_s[E] tab_s[E] cnt_s[4C] off_s[C+1] scan_s[48] sidx_s[cap] idx_s[cap] lg_s[waves*E]
 struct PostLds {
     lds_i32 *hist_s, *tab_s, *cnt_s, *off_s, *scan_s, *sidx_s, *idx_s;
-    lds_f32 *lg_s, *sel_s;
+    lds_f32 *lg_s;
 };
 
 __device__ inline PostLds carve_lds(int *dyn_, int E, int C, int A)
@@ -262,7 +262,6 @@ __device__ inline PostLds carve_lds(int *dyn_, int E, int C, int A)
     p.sidx_s = p.scan_s + 48;
     p.idx_s = p.sidx_s + cap;
     p.lg_s = (lds_f32 *)(dyn + ((2 * E + 5 * C + 49 + 2 * cap + 3) & ~3));
-    p.sel_s = p.lg_s + kRouteWaves * lg_stride(E);
     return p;
 }
 
@@ -270,7 +269,7 @@ inline size_t post_lds_bytes(int E, int C, int A, bool with_topk)
 {
     const int cap = A < kLdsCopy ? A : kLdsCopy;
     size_t n = (size_t)2 * E + 4 * C + (C + 1) + 48 + 2 * cap;
-    if (with_topk) n += (size_t)kRouteWaves * lg_stride(E) + kRouteWaves * kMaxK + 4;
+    if (with_topk) n += (size_t)kRouteWaves * lg_stride(E) + 4;
     return n * sizeof(int);
 }
 

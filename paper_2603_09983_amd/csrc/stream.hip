@@ -361,7 +361,6 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                         lg[e] = (f == f) ? f : -INFINITY;
                     }
                 }
-                if (lane < 4) lg[E + lane] = -INFINITY;
                 __builtin_amdgcn_wave_barrier();
                 // (up to 128 experts here: the ranking of more needs so many registers that the whole
                 // kernel would be launched with scratch memory; those batches keep the routing kernel)

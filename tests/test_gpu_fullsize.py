@@ -42,6 +42,12 @@ def test_cfg2_small_moe(G):
     run_and_check(G, synth.make_layer(synth.RECIPES["cfg2"], experts="resident"), "cfg2")
 
 
+def test_cfg2_small_moe_two_launch_option(G, monkeypatch):
+    """The form bench.py times as `fused_routing_option` (routing steps inside the gate/up launch), at full size."""
+    monkeypatch.setenv("MOE_SPAC_FUSED_ROUTING", "1")
+    run_and_check(G, synth.make_layer(synth.RECIPES["cfg2"], experts="resident"), "cfg2/two launches")
+
+
 def test_cfg3_fine_grained_zipf(G):
     run_and_check(G, synth.make_layer(synth.RECIPES["cfg3"], experts="resident"), "cfg3")
 

@@ -13,9 +13,11 @@
 // number of the call as ONE 64-bit atomic store; workgroup 0, one wavefront
 // per token, reads the entries with atomic loads until they carry that number
 // (a bounded number of times), so the hand-over needs no counter, no fence and
-// no cache write-back.  It then runs the integer steps out of LDS: ranks the
-// logits, and produces histogram, slot counts, miss list and per-slot lists
-// with independent threads between a few barriers.
+// no cache write-back.  It then picks each token's Top-k out of registers (k
+// maxima over the wavefront) and produces histogram, slot counts, miss list and
+// per-slot lists out of LDS with independent threads between a few barriers.
+// On this one serial path every instruction counts: a wavefront issues one
+// about every four cycles.
 #include "moe_internal.h"
 #include "route_device.h"
 

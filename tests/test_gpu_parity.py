@@ -220,6 +220,44 @@ def test_route_topk_many_ties_and_minus_infinity(G, T, E, k):
     assert np.max(np.abs(w.cpu().numpy() - rg)) <= G.GATE_ATOL
 
 
+def test_route_topk_random_shapes(G):
+    """Sixty seeded shapes (experts 1..512, k 1..64, 1..128 tokens), logits with one, a few or a thousand distinct
+    values and a random number of experts at minus infinity: ids bit-exact and gates within tolerance against the
+    oracle's ranking of the logits the device computed (exact by construction: one non-zero column)."""
+    from paper_2603_09983_amd import binding as B
+    rng = np.random.default_rng(7)
+    done = 0
+    while done < 60:
+        E = int(rng.choice([1, 2, 3, 7, 12, 33, 60, 63, 64, 65, 100, 127, 128, 129, 200, 255, 256, 257, 384, 511, 512]))
+        k = int(rng.integers(1, min(E, 64) + 1))
+        T = int(rng.choice([1, 2, 5, 9, 15, 16, 17, 31, 32, 33, 64, 100, 128]))
+        if T * E > 65536:
+            continue
+        done += 1
+        H = 64
+        hid = np.zeros((T, H), dtype=np.float32)
+        hid[:, 0] = rng.choice([-2.0, -1.0, 1.0, 2.0], size=T)
+        rw = rng.standard_normal((E, H)).astype(np.float32)
+        levels = int(rng.choice([1, 2, 5, 1000]))
+        rw[:, 0] = rng.integers(-levels, levels + 1, size=E).astype(np.float32) * (0.001 if levels == 1000 else 1.0)
+        bias = np.zeros(E, dtype=np.float32)
+        n_inf = int(rng.integers(0, max(1, E - 1)))     # at least one finite logit is left
+        if n_inf:
+            bias[rng.choice(E, n_inf, replace=False)] = -np.inf
+        ws = B.new_workspace(B.make_shape(T, H, E, k, 32, 0))
+        idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+        w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+        logits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+        B.moe_route_topk(torch.from_numpy(hid).cuda().to(torch.bfloat16), G.dev(rw), G.dev(bias), T, H, E, k, idx, w,
+                         logits, ws)
+        torch.cuda.synchronize()
+        ref_logits = hid[:, :1].astype(np.float32) * rw[:, 0][None, :] + bias[None, :]
+        assert np.array_equal(logits.cpu().numpy(), ref_logits), (T, E, k)
+        ridx, rg = oracle.topk_gate(ref_logits.astype(np.float64), k)
+        assert np.array_equal(idx.cpu().numpy(), ridx), (T, E, k, levels, n_inf)
+        assert np.max(np.abs(w.cpu().numpy() - rg)) <= G.GATE_ATOL, (T, E, k)
+
+
 def test_histogram_entry_point_small_and_large(G):
     from paper_2603_09983_amd import binding as B
     rng = np.random.default_rng(3)

@@ -89,3 +89,14 @@ def test_timeline_entry_point_of_the_product_build(lib):
     assert lib.moe_profile_stream_timeline(words, 5) == -2
     assert lib.moe_profile_stream_timeline(words, 2 * 1024 * 8) == -2
     assert words[0] == 7
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits without touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)

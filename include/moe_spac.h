@@ -93,7 +93,8 @@ int moe_workspace_status(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Step 1 -- Sec. 2.2, lines one to three of the MoE equation.
  *   s = W_g h (+ bias), the k largest logits per token (listed by descending
- *   logit, ties to the lower expert id), g = softmax restricted to those k.
+ *   logit, ties to the lower expert id; -0 equals +0; a NaN logit ranks as
+ *   minus infinity), g = softmax restricted to those k.
  * hidden [T,H] bf16; router_w [E,H] fp32; router_bias [E] fp32 or NULL (NULL
  * is the paper's equation); topk_idx [T,k] int32 out; topk_w [T,k] fp32 out;
  * logits_opt [T,E] fp32 out or NULL. */

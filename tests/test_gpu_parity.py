@@ -258,6 +258,32 @@ def test_route_topk_random_shapes(G):
         assert np.max(np.abs(w.cpu().numpy() - rg)) <= G.GATE_ATOL, (T, E, k)
 
 
+def test_route_topk_nan_logits_rank_last(G):
+    """A NaN logit (here through the bias) is ranked as minus infinity: it is picked only when the finite ones run
+    out, lower ids first, with gate 0."""
+    from paper_2603_09983_amd import binding as B
+    T, H, E, k = 4, 64, 70, 8
+    rng = np.random.default_rng(5)
+    hid = np.zeros((T, H), dtype=np.float32)
+    hid[:, 0] = 1.0
+    rw = rng.standard_normal((E, H)).astype(np.float32)
+    rw[:, 0] = rng.permutation(E).astype(np.float32)
+    bias = np.zeros(E, dtype=np.float32)
+    nan_ids = np.sort(rng.choice(E, E - 5, replace=False))      # five finite logits are left, k = 8
+    bias[nan_ids] = np.nan
+    ws = B.new_workspace(B.make_shape(T, H, E, k, 32, 0))
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    B.moe_route_topk(torch.from_numpy(hid).cuda().to(torch.bfloat16), G.dev(rw), G.dev(bias), T, H, E, k, idx, w,
+                     None, ws)
+    torch.cuda.synchronize()
+    ref = rw[:, 0].astype(np.float64) + np.where(np.isnan(bias), -np.inf, 0.0)
+    ridx, rg = oracle.topk_gate(np.tile(ref, (T, 1)), k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    assert list(ridx[0][5:]) == list(nan_ids[:3])
+    assert np.max(np.abs(w.cpu().numpy() - rg)) <= G.GATE_ATOL and np.all(w.cpu().numpy()[:, 5:] == 0.0)
+
+
 def test_histogram_entry_point_small_and_large(G):
     from paper_2603_09983_amd import binding as B
     rng = np.random.default_rng(3)

@@ -58,7 +58,9 @@ enum {
     MOE_ERR_SHAPE = -2,     /* a size is out of the supported range                    */
     MOE_ERR_ALIGN = -3,     /* H or F not a multiple of 32, or a misaligned pointer     */
     MOE_ERR_WORKSPACE = -4, /* workspace_bytes is smaller than the call needs          */
-    MOE_ERR_LAUNCH = -5     /* the HIP runtime refused a launch or an attribute        */
+    MOE_ERR_LAUNCH = -5,    /* the HIP runtime refused a launch or an attribute        */
+    MOE_ERR_SCRATCH = -6    /* moe_verify_layer_static: the shape needs more scratch memory
+                               than MOE_STATIC_SCRATCH_BYTES                            */
 };
 
 /* Problem sizes of one layer call.  n_shared always-on experts of width
@@ -147,6 +149,33 @@ int moe_verify_layer(const moe_shape_t *shape, const void *hidden, const float *
                      const void *shared_down, int32_t *topk_idx, float *topk_w, int32_t *hist,
                      int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, void *out, int out_bf16,
                      int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
+/* moe_verify_layer for callers that cannot allocate device memory or hand a
+ * workspace over: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments (without the workspace), same steps,
+ * same kernels and the same results as moe_verify_layer; the scratch memory is
+ * an array of MOE_STATIC_SCRATCH_BYTES bytes inside the library's own device
+ * image, which every GPU the library runs on holds from the first call until
+ * the process ends.  The call allocates and frees nothing.
+ *   - A shape whose moe_workspace_bytes() exceeds MOE_STATIC_SCRATCH_BYTES is
+ *     rejected with MOE_ERR_SCRATCH before anything is launched (16 MiB holds
+ *     every shape up to 128 tokens x top-6 at H = 2048, F = 1408).
+ *   - The array keeps the last call's contents.  The first call on a device,
+ *     and every call whose shape differs from the previous call's on that
+ *     device, first zero-fills the part of the array the new layout uses (one
+ *     small fill kernel on `stream`); moe_workspace_init is not needed.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in
+ *     time on one GPU (different streams, or different host threads without
+ *     stream order between them) race on it and give unspecified results;
+ *     issue them in stream order.  The health flag of the bounded waits is not
+ *     readable for this array; use moe_verify_layer where it is needed. */
+#define MOE_STATIC_SCRATCH_BYTES (16u << 20)
+int moe_verify_layer_static(const moe_shape_t *shape, const void *hidden, const float *router_w,
+                            const float *router_bias, const int32_t *slot_table, const void *w_gate,
+                            const void *w_up, const void *w_down, const void *shared_gate,
+                            const void *shared_up, const void *shared_down, int32_t *topk_idx, float *topk_w,
+                            int32_t *hist, int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, void *out,
+                            int out_bf16, int accumulate, void *stream);
 
 /* NEXT STEP AFTER THE HISTOGRAM -- Sec. 3.2, Alg. 1 (Speculative Utility
  * Estimator) and the utility-transition equation; n(tau) as in the notation

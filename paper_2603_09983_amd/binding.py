@@ -25,7 +25,8 @@ if not os.path.exists(LIB_PATH):
 
 _lib = ctypes.CDLL(LIB_PATH)
 
-OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4, -5
+OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_WORKSPACE, ERR_LAUNCH, ERR_SCRATCH = 0, -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class MoeShape(ctypes.Structure):
@@ -43,6 +44,8 @@ _lib.moe_expert_histogram.argtypes = [_vp, _i, _i, _i, _vp, _vp]
 _lib.moe_slot_resolve.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moe_grouped_ffn.argtypes = [_vp] * 6 + [_i] * 5 + [_vp, _i, _i, _vp, _sz, _vp]
 _lib.moe_verify_layer.argtypes = [ctypes.POINTER(MoeShape)] + [_vp] * 17 + [_i, _i, _vp, _sz, _vp]
+_lib.moe_verify_layer_static.argtypes = [ctypes.POINTER(MoeShape)] + [_vp] * 17 + [_i, _i, _vp]
+_lib.moe_verify_layer_static.restype = _i
 class BalanceParams(ctypes.Structure):
     _fields_ = [("t_cpu", ctypes.c_double), ("t_gpu", ctypes.c_double), ("t_io", ctypes.c_double),
                 ("t_draft", ctypes.c_double), ("l_target", ctypes.c_int), ("w_expert_bytes", ctypes.c_int64),
@@ -74,7 +77,7 @@ _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
 KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_BALANCER, KERNEL_CACHE_PLAN, KERNEL_POOL_LOAD, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
 
 EXPORTS = ("moe_profile_stream_timeline", "moe_cache_plan", "moe_pool_load", "moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
-           "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer")
+           "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer", "moe_verify_layer_static")
 
 
 class MoeError(RuntimeError):
@@ -215,6 +218,17 @@ def moe_verify_layer(shape: MoeShape, hidden, router_w, router_bias, slot_table,
                                int(accumulate), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                _stream(stream))
     return _check(rc, "moe_verify_layer", check)
+
+
+def moe_verify_layer_static(shape: MoeShape, hidden, router_w, router_bias, slot_table, w_gate, w_up, w_down,
+                            shared_gate, shared_up, shared_down, topk_idx, topk_w, hist, slot_idx, miss_list,
+                            miss_count, out, out_bf16, accumulate, stream=None, check=True) -> int:
+    rc = _lib.moe_verify_layer_static(ctypes.byref(shape), _ptr(hidden), _ptr(router_w), _ptr(router_bias),
+                                      _ptr(slot_table), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(shared_gate),
+                                      _ptr(shared_up), _ptr(shared_down), _ptr(topk_idx), _ptr(topk_w), _ptr(hist),
+                                      _ptr(slot_idx), _ptr(miss_list), _ptr(miss_count), _ptr(out), int(out_bf16),
+                                      int(accumulate), _stream(stream))
+    return _check(rc, "moe_verify_layer_static", check)
 
 
 def moe_utility_init(f_prev, s, theta_up, theta_dn, L, N, gamma, stream=None, check=True) -> int:

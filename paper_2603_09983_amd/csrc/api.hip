@@ -2,6 +2,7 @@
 #include "../../include/moe_spac.h"
 #include "moe_internal.h"
 #include <cstdlib>
+#include <mutex>
 
 using namespace moe;
 
@@ -153,6 +154,7 @@ extern "C" const char *moe_status_string(int status)
     case MOE_ERR_ALIGN: return "H or F is not a multiple of 32 (8 for routing), or a pointer is not 16-byte aligned";
     case MOE_ERR_WORKSPACE: return "workspace is smaller than moe_workspace_bytes() asks for";
     case MOE_ERR_LAUNCH: return g_launch_msg;
+    case MOE_ERR_SCRATCH: return "the shape needs more scratch memory than the library's static array holds";
     default: return "unknown status";
     }
 }
@@ -342,16 +344,17 @@ extern "C" int moe_grouped_ffn(const void *hidden, const float *topk_w, const in
                    out, out_bf16, accumulate, s);
 }
 
-extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const float *router_w,
-                                const float *router_bias, const int32_t *slot_table, const void *w_gate,
-                                const void *w_up, const void *w_down, const void *shared_gate,
-                                const void *shared_up, const void *shared_down, int32_t *topk_idx,
-                                float *topk_w, int32_t *hist, int32_t *slot_idx, int32_t *miss_list,
-                                int32_t *miss_count, void *out, int out_bf16, int accumulate, void *workspace,
-                                size_t workspace_bytes, void *stream)
+namespace {
+
+// Argument checks of a whole-layer call that do not concern the workspace.
+int check_layer_args(const moe_shape_t *sh, const void *hidden, const float *router_w, const int32_t *slot_table,
+                     const void *w_gate, const void *w_up, const void *w_down, const void *shared_gate,
+                     const void *shared_up, const void *shared_down, const int32_t *topk_idx, const float *topk_w,
+                     const int32_t *hist, const int32_t *slot_idx, const int32_t *miss_list,
+                     const int32_t *miss_count, const void *out)
 {
     if (!sh || !hidden || !router_w || !slot_table || !topk_idx || !topk_w || !hist || !slot_idx ||
-        !miss_list || !miss_count || !out || !workspace)
+        !miss_list || !miss_count || !out)
         return MOE_ERR_NULL;
     if (sh->C > 0 && (!w_gate || !w_up || !w_down)) return MOE_ERR_NULL;
     if (sh->n_shared < 0 || (sh->n_shared > 0 && sh->F_shared < 1)) return MOE_ERR_SHAPE;
@@ -363,13 +366,18 @@ extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const
     if (sh->n_shared > 0 && sh->F_shared % 32 != 0) return MOE_ERR_ALIGN;
     if (!aligned16(hidden) || !aligned16(router_w) || !aligned16(w_gate) || !aligned16(w_up) ||
         !aligned16(w_down) || !aligned16(shared_gate) || !aligned16(shared_up) || !aligned16(shared_down) ||
-        !aligned16(out) || !aligned16(workspace))
+        !aligned16(out))
         return MOE_ERR_ALIGN;
-    WsLayout w = ws_layout(sh->T, sh->E, sh->k, sh->C, sh->H, sh->F, sh->n_shared, sh->F_shared);
-    if (workspace_bytes < w.total) return MOE_ERR_WORKSPACE;
-    char *ws = (char *)workspace;
-    hipStream_t s = (hipStream_t)stream;
+    return MOE_OK;
+}
 
+// Steps 1-4 on a workspace that has been checked (size, alignment) and initialised for this shape.
+int run_layer(const moe_shape_t *sh, const void *hidden, const float *router_w, const float *router_bias,
+              const int32_t *slot_table, const void *w_gate, const void *w_up, const void *w_down,
+              const void *shared_gate, const void *shared_up, const void *shared_down, int32_t *topk_idx,
+              float *topk_w, int32_t *hist, int32_t *slot_idx, int32_t *miss_list, int32_t *miss_count, void *out,
+              int out_bf16, int accumulate, const WsLayout &w, char *ws, hipStream_t s)
+{
     RouteArgs r = {};
     r.hidden = hidden; r.router_w = router_w; r.router_bias = router_bias;
     r.T = sh->T; r.H = sh->H; r.E = sh->E; r.k = sh->k;
@@ -400,4 +408,92 @@ extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const
     return run_ffn(hidden, topk_w, w_gate, w_up, w_down, shared_gate, shared_up, shared_down, sh->T, sh->H,
                    sh->F, sh->k, sh->C, sh->n_shared, sh->n_shared ? sh->F_shared : 0, w, ws, out, out_bf16,
                    accumulate, s);
+}
+
+}  // namespace
+
+extern "C" int moe_verify_layer(const moe_shape_t *sh, const void *hidden, const float *router_w,
+                                const float *router_bias, const int32_t *slot_table, const void *w_gate,
+                                const void *w_up, const void *w_down, const void *shared_gate,
+                                const void *shared_up, const void *shared_down, int32_t *topk_idx,
+                                float *topk_w, int32_t *hist, int32_t *slot_idx, int32_t *miss_list,
+                                int32_t *miss_count, void *out, int out_bf16, int accumulate, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return MOE_ERR_NULL;
+    int rc = check_layer_args(sh, hidden, router_w, slot_table, w_gate, w_up, w_down, shared_gate, shared_up,
+                              shared_down, topk_idx, topk_w, hist, slot_idx, miss_list, miss_count, out);
+    if (rc) return rc;
+    if (!aligned16(workspace)) return MOE_ERR_ALIGN;
+    WsLayout w = ws_layout(sh->T, sh->E, sh->k, sh->C, sh->H, sh->F, sh->n_shared, sh->F_shared);
+    if (workspace_bytes < w.total) return MOE_ERR_WORKSPACE;
+    return run_layer(sh, hidden, router_w, router_bias, slot_table, w_gate, w_up, w_down, shared_gate, shared_up,
+                     shared_down, topk_idx, topk_w, hist, slot_idx, miss_list, miss_count, out, out_bf16,
+                     accumulate, w, (char *)workspace, (hipStream_t)stream);
+}
+
+// ---- the whole layer for callers that cannot allocate ----
+// Same steps and kernels as moe_verify_layer, with the workspace in a device array that is part of the
+// library's image (every device that loads the library holds its own copy, at an address of its own).
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr size_t kScratchBytes = (size_t)MOE_STATIC_SCRATCH_BYTES;
+
+constexpr int kMaxDevices = 64;
+struct ScratchState {
+    void *ptr = nullptr;          // device address of `scratch` on this device
+    bool laid_out = false;        // the array has been cleared for `shape`
+    moe_shape_t shape = {};
+};
+ScratchState g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+bool same_shape(const moe_shape_t &a, const moe_shape_t &b)
+{
+    return a.T == b.T && a.H == b.H && a.E == b.E && a.k == b.k && a.F == b.F && a.C == b.C &&
+           a.n_shared == b.n_shared && a.F_shared == b.F_shared;
+}
+
+}  // namespace
+
+extern "C" int moe_verify_layer_static(const moe_shape_t *sh, const void *hidden, const float *router_w,
+                                       const float *router_bias, const int32_t *slot_table, const void *w_gate,
+                                       const void *w_up, const void *w_down, const void *shared_gate,
+                                       const void *shared_up, const void *shared_down, int32_t *topk_idx,
+                                       float *topk_w, int32_t *hist, int32_t *slot_idx, int32_t *miss_list,
+                                       int32_t *miss_count, void *out, int out_bf16, int accumulate, void *stream)
+{
+    int rc = check_layer_args(sh, hidden, router_w, slot_table, w_gate, w_up, w_down, shared_gate, shared_up,
+                              shared_down, topk_idx, topk_w, hist, slot_idx, miss_list, miss_count, out);
+    if (rc) return rc;
+    const WsLayout w = ws_layout(sh->T, sh->E, sh->k, sh->C, sh->H, sh->F, sh->n_shared, sh->F_shared);
+    if (w.total > kScratchBytes) return MOE_ERR_SCRATCH;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return launch_failed(e);
+    if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    ScratchState &st = g_scratch[dev];
+    if (!st.ptr) {
+        // (in host code the array's name is only a handle: the device address comes from the runtime)
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return launch_failed(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        st.ptr = p;
+    }
+    if (!st.laid_out || !same_shape(st.shape, *sh)) {
+        // another layout than the last call's (or the first call): no stale entry may carry a future
+        // call number, so everything this layout uses starts at zero (a fill kernel on the caller's stream)
+        st.laid_out = false;
+        e = launch_clear_ctrl(st.ptr, w.total, s);
+        if (e != hipSuccess) return launch_failed(e);
+        st.shape = *sh;
+        st.laid_out = true;
+    }
+    return run_layer(sh, hidden, router_w, router_bias, slot_table, w_gate, w_up, w_down, shared_gate, shared_up,
+                     shared_down, topk_idx, topk_w, hist, slot_idx, miss_list, miss_count, out, out_bf16,
+                     accumulate, w, (char *)st.ptr, s);
 }

@@ -40,6 +40,8 @@ def parse_args():
     p.add_argument("--workload", default="cfg2",
                    help="cfg2 | cfg3 | cfg4_c8 | cfg4_c4 | cfg5_T<n> (24-layer sweep at T=n)")
     p.add_argument("--copies", type=int, default=0, help="distinct layers to rotate over (0 = auto)")
+    p.add_argument("--form", default="auto", choices=["auto", "three", "two", "one", "route+one"],
+                   help="launch form of moe_verify_layer (moe_shape_t::launch_form)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-estimator", action="store_true", help="skip the utility-estimator measurement")
     p.add_argument("--no-fused-option", action="store_true",
@@ -94,11 +96,38 @@ def print_timeline(B, torch, np, step, n_layers):
     for i in range(min(3, n_layers)):
         step(i)
         torch.cuda.synchronize()
-        words = B.moe_profile_stream_timeline()
+        got = B.moe_profile_stream_timeline()
+        words, lwords = got if got is not None else (None, None)
         if words is None:
             print("[timeline] the loaded library has no timeline stamps (python paper_2603_09983_amd/build.py "
                   "--trace; MOE_SPAC_LIB=paper_2603_09983_amd/libmoe_spac_trace.so)", file=sys.stderr)
             return
+        tl = lwords.astype(np.int64)
+        tl = tl[tl[:, 5] > 0]
+        if len(tl) and tl[:, 0].min() > max(words[0][:, 0].max(), words[1][:, 0].max()):
+            # the one-launch layer kernel ran last: start | lists | first tile | enters the down part | loop end | end
+            us = (tl[:, :6] - tl[:, 0].min()) / 100.0
+            us[:, 3] = np.where(tl[:, 3] > 0, us[:, 3], np.nan)
+
+            def q(x):
+                return "%5.1f/%5.1f/%5.1f" % (np.nanmin(x), np.nanmedian(x), np.nanmax(x))
+            print(f"[timeline] layer {i} one launch ({len(tl)} workgroups, {(tl[:, 6] >> 32).min()}-{(tl[:, 6] >> 32).max()} gate/up and "
+                  f"{(tl[:, 6] & 0xffffffff).min()}-{(tl[:, 6] & 0xffffffff).max()} down items each): start {q(us[:, 0])} | "
+                  f"lists {q(us[:, 1])} | first tile {q(us[:, 2])} | down part {q(us[:, 3])} | loop end {q(us[:, 4])} | "
+                  f"end {q(us[:, 5])}", file=sys.stderr)
+            xcd = np.arange(len(tl)) % 8
+            print("[timeline]     down part entered, mean per XCD: " +
+                  " ".join("%.1f" % np.nanmean(us[xcd == x, 3]) for x in range(8)), file=sys.stderr)
+            print("[timeline]     loop end, mean per XCD: " +
+                  " ".join("%.1f" % us[xcd == x, 4].mean() for x in range(8)), file=sys.stderr)
+            names = ("wait", "park", "store", "request", "barrier1", "multiply", "barrier2", "walk")
+            steps = np.maximum(tl[:, 7] - 1, 1)
+            for wv, off in ((0, 8), (15, 16)):
+                cyc = tl[:, off:off + 8] / steps[:, None]
+                print(f"[timeline]     wavefront {wv:2d}, shader cycles per step (median over workgroups): " +
+                      " ".join(f"{nm} {np.median(cyc[:, j]):.0f}" for j, nm in enumerate(names)) +
+                      f" | sum {np.median(cyc.sum(axis=1)):.0f}", file=sys.stderr)
+            continue
         for ki, name in enumerate(("gate/up", "down")):
             t = words[ki].astype(np.int64)
             t = t[t[:, 5] > 0]
@@ -137,9 +166,13 @@ def main():
     buf = B.LayerBuffers.allocate(dev_layers[0].shape)
     print(f"[bench] {desc}; inputs built and uploaded in {time.time() - t_gen:.1f}s", file=sys.stderr, flush=True)
 
+    form = {"auto": B.LAUNCH_AUTO, "three": B.LAUNCH_THREE, "two": B.LAUNCH_TWO, "one": B.LAUNCH_ONE,
+            "route+one": B.LAUNCH_ROUTE_PLUS_ONE}[args.form]
+    call_shape = B.with_form(dev_layers[0].shape, form)
+
     def step(i):
         d = dev_layers[i % len(dev_layers)]
-        B.moe_verify_layer(d.shape, d.hidden, d.router_w, d.router_bias, d.slot_table, d.w_gate, d.w_up,
+        B.moe_verify_layer(call_shape, d.hidden, d.router_w, d.router_bias, d.slot_table, d.w_gate, d.w_up,
                            d.w_down, d.sh_gate, d.sh_up, d.sh_down, buf.topk_idx, buf.topk_w, buf.hist,
                            buf.slot_idx, buf.miss_list, buf.miss_count, buf.out, False, False, buf.workspace)
 
@@ -207,21 +240,26 @@ def main():
         if n:
             kernels[B.moe_profile_kernel_name(kind)] = {"launches": n, "avg_us": round(ms * 1e3 / n - ev_us, 2),
                                                         "avg_us_event_pair": round(ms * 1e3 / n, 2)}
-    # dominant kernel: the gate/up stream (2/3 of the expert-weight bytes); when the batch is large
-    # enough for the fused kernel it carries gate, up and down (all of them)
+    # dominant kernel: the one-launch layer kernel carries every expert-weight byte of the layer; in the
+    # forms with two streaming launches it is the gate/up stream (2/3 of the bytes)
+    layer_ms, layer_n = raw[B.KERNEL_LAYER]
     ffn_ms, ffn_n = raw[B.KERNEL_FFN]
     down_ms, down_n = raw[B.KERNEL_DOWN]
-    ffn_avg_s = ffn_ms * 1e-3 / ffn_n - ev_us * 1e-6
-    share = 2.0 / 3.0 if down_n else 1.0
+    if layer_n:
+        dom_name, dom_ms, dom_n, share = "layer_kernel (gate/up + down + final sum in one launch)", layer_ms, layer_n, 1.0
+    else:
+        dom_name = "stream_kernel<gate/up>" if down_n else "ffn_kernel (gate/up/down fused)"
+        dom_ms, dom_n, share = ffn_ms, ffn_n, (2.0 / 3.0 if down_n else 1.0)
+    dom_avg_s = dom_ms * 1e-3 / dom_n - ev_us * 1e-6
     bytes_per_launch = share * bytes_total / args.steps
-    achieved = bytes_per_launch / ffn_avg_s / 1e9
-    roofline = {"bound": "hbm", "kernel": "stream_kernel<gate/up>" if down_n else "ffn_kernel (gate/up/down fused)",
+    achieved = bytes_per_launch / dom_avg_s / 1e9
+    roofline = {"bound": "hbm", "kernel": dom_name,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if not args.copies else None,
-                "avg_kernel_us": round(ffn_avg_s * 1e6, 2), "event_pair_overhead_us": round(ev_us, 2),
+                "avg_kernel_us": round(dom_avg_s * 1e6, 2), "event_pair_overhead_us": round(ev_us, 2),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch), "kernels": kernels}
-    if down_n:
+    if down_n and not layer_n:
         d_s = down_ms * 1e-3 / down_n - ev_us * 1e-6
         roofline["down_kernel"] = {"achieved": round((bytes_total / args.steps / 3.0) / d_s / 1e9, 1),
                                    "avg_kernel_us": round(d_s * 1e6, 2)}

@@ -68,7 +68,20 @@ enum {
 typedef struct moe_shape {
     int T, H, E, k, F, C;
     int n_shared, F_shared;
+    int launch_form;   /* moe_verify_layer only: MOE_LAUNCH_* (0 = the library chooses) */
 } moe_shape_t;
+
+/* How moe_verify_layer cuts the layer into kernel launches (same results in
+ * every form).  A form that the shape does not allow is refused with
+ * MOE_ERR_SHAPE; MOE_LAUNCH_AUTO never is.  A workspace that has been used in
+ * one form must be initialised again before it is used in another. */
+enum {
+    MOE_LAUNCH_AUTO = 0,
+    MOE_LAUNCH_THREE = 1,         /* routing | gate/up stream | down stream + final sum (+ a combine launch above 32 tokens) */
+    MOE_LAUNCH_TWO = 2,           /* routing steps at the head of the gate/up kernel: T <= 16, E <= 128 */
+    MOE_LAUNCH_ONE = 3,           /* routing, gate/up, down and final sum as one kernel: T <= 16, E <= 128, H, F multiples of 64 */
+    MOE_LAUNCH_ROUTE_PLUS_ONE = 4 /* routing kernel, then gate/up, down and final sum as one kernel: T <= 16 */
+};
 
 /* Host-only, pure.  Static text for a status code (never NULL). */
 const char *moe_status_string(int status);
@@ -276,7 +289,8 @@ int moe_pool_load(const void *store_gate, const void *store_up, const void *stor
  * caller must have synchronised the stream.  total_ms, launches: host. */
 enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2 /* gate/up (and down when fused) */,
        MOE_KERNEL_COMBINE = 3, MOE_KERNEL_DOWN = 4, MOE_KERNEL_ESTIMATOR = 5, MOE_KERNEL_BALANCER = 6,
-       MOE_KERNEL_CACHE_PLAN = 7, MOE_KERNEL_POOL_LOAD = 8, MOE_KERNEL_KINDS = 9 };
+       MOE_KERNEL_CACHE_PLAN = 7, MOE_KERNEL_POOL_LOAD = 8, MOE_KERNEL_LAYER = 9 /* the one-launch layer kernel */,
+       MOE_KERNEL_KINDS = 10 };
 int moe_profile_enable(int on);
 int moe_profile_read(int kind, double *total_ms, int *launches);
 const char *moe_profile_kernel_name(int kind);
@@ -286,14 +300,21 @@ const char *moe_profile_kernel_name(int kind);
  * much time that is not the kernel's.  Call after moe_profile_enable(1) and
  * after reading the records you need (it reuses the pairs of kind 0). */
 int moe_profile_event_overhead(void *stream, int pairs, double *avg_ms);
-/* Timeline of the last gate/up and down launches of the streaming kernels, for a
- * library built with -DMOE_STREAM_TRACE (the product build returns
- * MOE_ERR_SHAPE and writes nothing).  words: host buffer of
- * 2 x 1024 x 8 64-bit words, [kernel: 0 gate/up, 1 down][workgroup][stamp]:
- * ticks of the 100 MHz device wall clock at the workgroup's start, with the
- * per-slot lists in LDS, after its first tile, at the end of its loop, after
- * its results are stored and at its end; then its items and tiles.  Synchronous
- * (a blocking copy from the device); call after synchronising the stream. */
+/* Timeline of the last launches of the streaming kernels, for a library built
+ * with -DMOE_STREAM_TRACE (the product build returns MOE_ERR_SHAPE and writes
+ * nothing).  words: host buffer of 2 x 1024 x 8 + 1024 x 24 64-bit words.
+ * First [kernel: 0 gate/up, 1 down][workgroup][8]: ticks of the 100 MHz device
+ * wall clock at the workgroup's start, with the per-slot lists in LDS, after
+ * its first tile, at the end of its loop, after its results are stored and at
+ * its end; then its items and tiles.  Then the one-launch layer kernel,
+ * [workgroup][24]: start, lists in LDS, after the first tile, when the walk
+ * that multiplies enters the down part, end of the loop, end; (gate/up items
+ * << 32 | down items); tiles; then for wavefront 0 and for wavefront 15 eight
+ * sums over the loop's steps, in shader clock cycles: waiting for the tile,
+ * parking it, storing the previous item's results, requesting a tile and
+ * stepping the request walk, first barrier, multiplying, second barrier,
+ * stepping the other walk.  Synchronous (a blocking copy from the device);
+ * call after synchronising the stream. */
 int moe_profile_stream_timeline(unsigned long long *words, size_t n_words);
 
 #ifdef __cplusplus

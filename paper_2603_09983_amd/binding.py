@@ -30,7 +30,7 @@ STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class MoeShape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "E", "k", "F", "C", "n_shared", "F_shared")]
+    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "E", "k", "F", "C", "n_shared", "F_shared", "launch_form")]
 
 
 _vp, _sz, _i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
@@ -74,7 +74,7 @@ _lib.moe_profile_stream_timeline.argtypes = [ctypes.c_void_p, _sz]
 _lib.moe_profile_stream_timeline.restype = _i
 _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
-KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_BALANCER, KERNEL_CACHE_PLAN, KERNEL_POOL_LOAD, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
+KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_BALANCER, KERNEL_CACHE_PLAN, KERNEL_POOL_LOAD, KERNEL_LAYER, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10
 
 EXPORTS = ("moe_profile_stream_timeline", "moe_cache_plan", "moe_pool_load", "moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer", "moe_verify_layer_static")
@@ -130,14 +130,15 @@ def moe_profile_read(kind: int):
 
 
 def moe_profile_stream_timeline():
-    """[2, 1024, 8] uint64 (numpy), or None when the loaded library is not a tracing build."""
+    """([2, 1024, 8], [1024, 24]) uint64 (numpy): the two streaming kernels' records and the one-launch layer
+    kernel's; None when the loaded library is not a tracing build."""
     import numpy as np
-    words = np.zeros((2, 1024, 8), dtype=np.uint64)
+    words = np.zeros(2 * 1024 * 8 + 1024 * 24, dtype=np.uint64)
     rc = _lib.moe_profile_stream_timeline(ctypes.c_void_p(words.ctypes.data), words.size)
     if rc == ERR_SHAPE:
         return None
     _check(rc, "moe_profile_stream_timeline", True)
-    return words
+    return words[:2 * 1024 * 8].reshape(2, 1024, 8), words[2 * 1024 * 8:].reshape(1024, 24)
 
 
 def moe_profile_event_overhead(pairs: int = 256, stream=None) -> float:
@@ -151,8 +152,15 @@ def moe_profile_kernel_name(kind: int) -> str:
     return _lib.moe_profile_kernel_name(kind).decode()
 
 
-def make_shape(T, H, E, k, F, C, n_shared=0, F_shared=0) -> MoeShape:
-    return MoeShape(T, H, E, k, F, C, n_shared, F_shared)
+LAUNCH_AUTO, LAUNCH_THREE, LAUNCH_TWO, LAUNCH_ONE, LAUNCH_ROUTE_PLUS_ONE = 0, 1, 2, 3, 4
+
+
+def make_shape(T, H, E, k, F, C, n_shared=0, F_shared=0, launch_form=LAUNCH_AUTO) -> MoeShape:
+    return MoeShape(T, H, E, k, F, C, n_shared, F_shared, launch_form)
+
+
+def with_form(shape: MoeShape, launch_form: int) -> MoeShape:
+    return MoeShape(shape.T, shape.H, shape.E, shape.k, shape.F, shape.C, shape.n_shared, shape.F_shared, launch_form)
 
 
 def moe_workspace_bytes(shape: MoeShape) -> int:

@@ -1,7 +1,6 @@
 // C-ABI of libmoe_spac.so: argument checks and launch sequencing only.
 #include "../../include/moe_spac.h"
 #include "moe_internal.h"
-#include <cstdlib>
 #include <mutex>
 
 using namespace moe;
@@ -123,9 +122,11 @@ extern "C" int moe_profile_event_overhead(void *stream, int pairs, double *avg_m
 extern "C" int moe_profile_stream_timeline(unsigned long long *words, size_t n_words)
 {
     if (!words) return MOE_ERR_NULL;
-    if (n_words != (size_t)2 * kTimelineGroups * kTimelineWords) return MOE_ERR_SHAPE;
-    hipError_t e = read_stream_timeline(words, n_words * sizeof(unsigned long long));
+    const size_t plane = (size_t)kTimelineGroups * kTimelineWords, lplane = (size_t)kTimelineGroups * kLayerTimelineWords;
+    if (n_words != 2 * plane + lplane) return MOE_ERR_SHAPE;
+    hipError_t e = read_stream_timeline(words, 2 * plane * sizeof(unsigned long long));
     if (e == hipErrorNotSupported) return MOE_ERR_SHAPE;   // not a tracing build
+    if (e == hipSuccess) e = read_layer_timeline(words + 2 * plane, lplane * sizeof(unsigned long long));
     return e == hipSuccess ? MOE_OK : launch_failed(e);
 }
 
@@ -141,6 +142,7 @@ extern "C" const char *moe_profile_kernel_name(int kind)
     case MOE_KERNEL_BALANCER: return "balance_kernel";
     case MOE_KERNEL_CACHE_PLAN: return "plan_kernel";
     case MOE_KERNEL_POOL_LOAD: return "load_kernel";
+    case MOE_KERNEL_LAYER: return "layer_kernel";
     default: return "?";
     }
 }
@@ -255,7 +257,7 @@ namespace {
 int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const void *w_up, const void *w_down,
             const void *sh_gate, const void *sh_up, const void *sh_down, int T, int H, int F, int k, int C,
             int n_shared, int F_shared, const WsLayout &w, char *ws, void *out, int out_bf16, int accumulate,
-            hipStream_t s, const RouteArgs *routing = nullptr)
+            hipStream_t s, const RouteArgs *routing = nullptr, bool one_launch = false, int32_t *miss_count = nullptr)
 {
     // (the caller's routing / list kernel has given this call its number in the control block)
     int32_t *slot_count = (int32_t *)(ws + w.slot_count), *slot_offset = (int32_t *)(ws + w.slot_offset);
@@ -265,6 +267,24 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
     c.T = T; c.H = H; c.F = F; c.k = k; c.n_shared = n_shared; c.F_shared = F_shared;
     c.out_bf16 = out_bf16; c.accumulate = accumulate;
     hipError_t e;
+    if (one_launch) {
+        // small batch: gate/up, down and the final sum as one weight stream (routing != null: the routing steps too)
+        LayerArgs l = {};
+        l.w_gate = (const uint16_t *)w_gate; l.w_up = (const uint16_t *)w_up; l.w_down = (const uint16_t *)w_down;
+        l.sh_gate = (const uint16_t *)sh_gate; l.sh_up = (const uint16_t *)sh_up; l.sh_down = (const uint16_t *)sh_down;
+        l.hidden = (const uint16_t *)hidden;
+        l.act = (unsigned long long *)(ws + w.act); l.act_sh = (unsigned long long *)(ws + w.act_sh);
+        l.o = (unsigned long long *)(ws + w.o); l.o_sh = (unsigned long long *)(ws + w.o_sh);
+        l.slot_count = slot_count; l.slot_offset = slot_offset; l.perm = perm; l.pos = pos;
+        l.active_slots = (const int32_t *)(ws + w.active);
+        l.n_active = (const unsigned *)(ws + w.ctrl) + kCtrlNActive;
+        l.topk_w = topk_w; l.out = out; l.miss_count = miss_count;
+        l.ctrl = (unsigned *)(ws + w.ctrl);
+        l.T = T; l.k = k; l.H = H; l.F = F; l.F_sh = F_shared; l.n_shared = n_shared; l.C = C;
+        l.out_bf16 = out_bf16; l.accumulate = accumulate;
+        e = launch_layer(l, routing, s);
+        return e == hipSuccess ? MOE_OK : launch_failed(e);
+    }
     if (use_stream_kernels(T, k, C, H, F, n_shared, F_shared)) {
         StreamArgs g = {};
         g.w0 = (const uint16_t *)w_gate; g.w1 = (const uint16_t *)w_up;
@@ -358,6 +378,7 @@ int check_layer_args(const moe_shape_t *sh, const void *hidden, const float *rou
         return MOE_ERR_NULL;
     if (sh->C > 0 && (!w_gate || !w_up || !w_down)) return MOE_ERR_NULL;
     if (sh->n_shared < 0 || (sh->n_shared > 0 && sh->F_shared < 1)) return MOE_ERR_SHAPE;
+    if (sh->launch_form < MOE_LAUNCH_AUTO || sh->launch_form > MOE_LAUNCH_ROUTE_PLUS_ONE) return MOE_ERR_SHAPE;
     if (sh->n_shared > 0 && (!shared_gate || !shared_up || !shared_down)) return MOE_ERR_NULL;
     int rc = check_route_shape(sh->T, sh->H, sh->E, sh->k);
     if (rc) return rc;
@@ -391,23 +412,28 @@ int run_layer(const moe_shape_t *sh, const void *hidden, const float *router_w, 
     r.slot_count = (int32_t *)(ws + w.slot_count); r.slot_offset = (int32_t *)(ws + w.slot_offset);
     r.perm = (int32_t *)(ws + w.perm); r.pos = (int32_t *)(ws + w.pos);
     r.active_slots = (int32_t *)(ws + w.active); r.n_active = (unsigned *)(ws + w.ctrl) + kCtrlNActive;
-    // Small batches, on request (environment variable MOE_SPAC_FUSED_ROUTING set, read at each call): steps 1-3
-    // ride in front of the gate/up kernel, two launches per layer instead of three.  Measured 1.2-1.9 us per
-    // layer faster (cfg2 75.3 against 77.2 us); not the default because the routing inside that launch takes
-    // 12 us where the routing kernel takes 8 (the XCDs start such a launch up to 4 us apart, and workgroup 0
-    // has to wait for the logits of the last one), so the gain is only the launch that is saved.
-    const char *fused_env = getenv("MOE_SPAC_FUSED_ROUTING");
-    if (w.lists_pub && fused_env && fused_env[0] != '\0' && fused_env[0] != '0') {
+    // The launch forms (moe_shape_t::launch_form): three launches (routing kernel, gate/up stream, down stream with
+    // the final sum), two (routing steps at the head of the gate/up kernel), one (routing, gate/up, down and the
+    // final sum in one kernel: batches of up to 16 tokens), or the routing kernel followed by the one-launch FFN.
+    const int n_sh = sh->n_shared, F_sh = sh->n_shared ? sh->F_shared : 0;
+    const bool can_layer = use_layer_kernel(sh->T, sh->k, sh->E, sh->C, sh->H, sh->F, n_sh, F_sh);
+    const bool can_route_inside = w.lists_pub != 0;
+    int form = sh->launch_form;
+    if (form == MOE_LAUNCH_AUTO) form = MOE_LAUNCH_THREE;
+    if (form == MOE_LAUNCH_ONE && !(can_layer && can_route_inside)) return MOE_ERR_SHAPE;
+    if (form == MOE_LAUNCH_ROUTE_PLUS_ONE && !can_layer) return MOE_ERR_SHAPE;
+    if (form == MOE_LAUNCH_TWO && !can_route_inside) return MOE_ERR_SHAPE;
+    if (form == MOE_LAUNCH_ONE || form == MOE_LAUNCH_TWO) {
         r.lists_pub = (unsigned long long *)(ws + w.lists_pub);
         return run_ffn(hidden, topk_w, w_gate, w_up, w_down, shared_gate, shared_up, shared_down, sh->T, sh->H,
-                       sh->F, sh->k, sh->C, sh->n_shared, sh->n_shared ? sh->F_shared : 0, w, ws, out, out_bf16,
-                       accumulate, s, &r);
+                       sh->F, sh->k, sh->C, n_sh, F_sh, w, ws, out, out_bf16, accumulate, s, &r,
+                       form == MOE_LAUNCH_ONE, miss_count);
     }
     hipError_t e = launch_route(r, s);
     if (e != hipSuccess) return launch_failed(e);
     return run_ffn(hidden, topk_w, w_gate, w_up, w_down, shared_gate, shared_up, shared_down, sh->T, sh->H,
-                   sh->F, sh->k, sh->C, sh->n_shared, sh->n_shared ? sh->F_shared : 0, w, ws, out, out_bf16,
-                   accumulate, s);
+                   sh->F, sh->k, sh->C, n_sh, F_sh, w, ws, out, out_bf16, accumulate, s, nullptr,
+                   form == MOE_LAUNCH_ROUTE_PLUS_ONE, miss_count);
 }
 
 }  // namespace
@@ -441,7 +467,6 @@ namespace {
 
 constexpr size_t kScratchBytes = (size_t)MOE_STATIC_SCRATCH_BYTES;
 
-constexpr int kMaxDevices = 64;
 struct ScratchState {
     void *ptr = nullptr;          // device address of `scratch` on this device
     bool laid_out = false;        // the array has been cleared for `shape`
@@ -453,7 +478,7 @@ std::mutex g_scratch_mutex;
 bool same_shape(const moe_shape_t &a, const moe_shape_t &b)
 {
     return a.T == b.T && a.H == b.H && a.E == b.E && a.k == b.k && a.F == b.F && a.C == b.C &&
-           a.n_shared == b.n_shared && a.F_shared == b.F_shared;
+           a.n_shared == b.n_shared && a.F_shared == b.F_shared && a.launch_form == b.launch_form;
 }
 
 }  // namespace

@@ -1,0 +1,1003 @@
+// The expert FFN of a small verification batch (up to 16 tokens: a single request with gamma <= 15 draft
+// tokens) as ONE weight stream per layer call:
+//      act = silu(W_gate x) * (W_up x)      per (token, resident expert) pair and per shared expert
+//      o   = W_down act
+//      y_t = sum_j g_{t,j} o_{t,j} + sum_shared o        -- Sec. 2.2 last line, experts as in App. D,
+// optionally with steps 1-3 of the layer (logits, Top-k, gate, histogram, slot lookup, miss list, per-slot
+// lists: Sec. 2.2 lines 1-3, Sec. 2.3, App. D) at its head.
+//
+// Why one launch: a launch that streams a few hundred megabytes pays about 5 us before the memory system
+// delivers at its steady rate, 2-4 us between its first and its last workgroup leaving the loop, and 1.4 us
+// until the next launch starts.  Here the gate/up tiles and the down tiles of a workgroup form ONE list; the
+// walk that requests tiles runs two tiles ahead of the walk that multiplies them and crosses from the gate/up
+// part into the down part without a pause, so the W_down tiles are in flight while the last gate/up tiles are
+// still being multiplied, and a workgroup that is early at the end of its gate/up part simply goes on.
+//
+// What the down part needs from OTHER workgroups is the activation of an expert.  Every activation leaves the
+// workgroup that computed it as ONE 64-bit relaxed atomic store at agent scope: (call number << 32 | two bf16
+// values).  An entry that carries the call's number IS the value, so the hand-over needs no counter, no
+// release fence (an L2 write-back) and no acquire fence (an L2 invalidate); the reader polls a bounded number
+// of times.  The per-assignment outputs go to the final sum the same way ((call number, fp32) entries), and
+// every workgroup ends by summing a strip of output columns in a fixed order (no float atomics: the result does
+// not depend on scheduling).
+//
+// Results are stored by the threads that reduce them, item by item.  The memory counter of a wavefront
+// counts loads and stores in order, so a store between two tile requests never holds back an older tile, and
+// the younger tile is only waited for two steps later, when the store has long been acknowledged.
+//
+// The tile mechanics are those of the two-launch streaming kernels (stream.hip): a workgroup of 16 wavefronts
+// reads a tile of 16 weight rows as 1 KB contiguous pieces into registers, two tiles in flight, parks it in
+// LDS, and every wavefront multiplies its 32-wide column blocks for all 16 rows with MFMA 16x16x32 bf16,
+// tokens on the N axis.  In the gate/up part column n is TOKEN n for every expert (the arithmetic is free), so
+// the B operand never changes there; the expert's own tokens are picked out when the results are stored.
+#include "moe_internal.h"
+#include "route_device.h"
+
+namespace moe {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef unsigned long long u64;
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = 16;
+constexpr int kPieces = 4;     // 1 KB pieces per wavefront per tile (64 KB tile / 16 wavefronts)
+constexpr int kRowPad = kStreamRowPad;
+
+// (explicitly a pointer to global memory: an address that has been through an integer, as the tile addresses in
+// the records have, would otherwise be loaded from with flat instructions, which count in both memory counters
+// and force every wait behind them to wait for everything)
+typedef __attribute__((address_space(1))) const unsigned char g_bytes;
+typedef __attribute__((address_space(1))) const u32x4 g_u32x4;
+
+__device__ inline u32x4 ld_stream(g_bytes *p)
+{
+    return __builtin_nontemporal_load((g_u32x4 *)p);
+}
+
+__device__ inline f32x4 mfma(u32x4 a, u32x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                   c, 0, 0, 0);
+}
+
+__device__ inline uint32_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ inline void store_entry(u64 *p, unsigned tag, unsigned value)
+{
+    __hip_atomic_store(p, ((u64)tag << 32) | value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline u64 load_entry(const u64 *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+#ifdef MOE_STREAM_TRACE
+__device__ unsigned long long g_layer_timeline[kTimelineGroups][kLayerTimelineWords];
+#define MOE_STAMP(var) var = wall_clock64()
+// (shader clock: what a wavefront spends in each part of a step, summed over the loop's steps)
+#define MOE_CYC_BEGIN() long long cyc_t = clock64()
+#define MOE_CYC(i) do { const long long cyc_n = clock64(); cyc_sum[i] += cyc_n - cyc_t; cyc_t = cyc_n; } while (0)
+#else
+#define MOE_STAMP(var)
+#define MOE_CYC_BEGIN()
+#define MOE_CYC(i)
+#endif
+
+// Item classes of a workgroup's list, in the order it walks them:
+//   0  gate/up, shared experts   item = (expert, 8 activations): gate rows f..f+7 stacked on up rows f..f+7
+//   1  gate/up, routed experts
+//   2  down, shared experts      item = (expert, 16 output rows)
+//   3  down, routed experts
+// An item is one tile per contraction panel (one panel up to 2048 columns).
+//
+// The loop is bound by how many instructions the sixteen wavefronts of a workgroup issue per tile, not only
+// by memory, so everything that can be worked out once is: before the loop the workgroup writes one 32-byte
+// record per tile of its list into LDS (thread j writes record j: where the tile's two row groups start in
+// memory, which class and panel it is, where its results go), and a step only reads two records, the one
+// of the tile it requests and the one of the tile it multiplies.
+constexpr int kTabWords = 8;            // words of a tile record
+constexpr int kRedStride = 1024 + 16;   // bytes between the partial results of two wavefronts in LDS
+constexpr int kDumpBytes = 1024;        // where pieces that a tile does not have are parked
+
+template <int NPI, bool ROUTE>
+__global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs ra)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int T = a.T, kk = a.k, H = a.H, F = a.F, Fs = a.F_sh, C = a.C, A = T * kk;
+    unsigned char *tile_s = lds;
+    unsigned char *red_s = lds + a.tile_lds_bytes + kDumpBytes;        // [wavefront] 1 KB of partial results each
+    int *ctl_s = (int *)(red_s + 2 * kWaves * kRedStride + 1024);   // (two halves of partial results, 256 finished values)
+    int *count_s = ctl_s, *offset_s = ctl_s + C, *active_s = ctl_s + 2 * C, *mask_s = ctl_s + 3 * C;
+    int *perm_s = ctl_s + 4 * C;     // token of each entry of the per-slot lists
+    int *pos_s = perm_s + A;         // row of each assignment's output, -1 = expert not resident
+    int *misc_s = pos_s + A;         // [0] active slots, [1] a bounded wait of this workgroup ran out
+    // per class: panels per item, items per expert, first item of this workgroup's share, contraction length,
+    // panel width, rows per expert (constants of the launch, looked up on the rare paths)
+    int *cls_s = misc_s + 8;         // [4][8]
+    int *geo_s = cls_s + 32;         // [4][2]: tile row bytes, weight row bytes of the four tile layouts
+    u64 *clsp_s = (u64 *)(geo_s + 8);   // [4][2]: where the class's weights start (rows 0..7 and 8..15 of a tile)
+    uint32_t *tab_s = (uint32_t *)(ctl_s + ((4 * C + 2 * A + 8 + 32 + 8 + 16 + 3) & ~3));   // [tiles + 2][kTabWords]
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+#ifdef MOE_STREAM_TRACE
+    unsigned long long tl_start, tl_lists = 0, tl_first = 0, tl_phase = 0, tl_loop = 0;
+    long long cyc_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+    MOE_STAMP(tl_start);
+    const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wavefront id, known to be uniform
+    const int n = lane & 15, g = lane >> 4;
+    const int G = gridDim.x, b = blockIdx.x;
+
+    // control block: call number, and the two words with which a test forces the bounded waits to run out
+    unsigned *const error_flag = a.ctrl + kCtrlError;
+    const unsigned epoch0 = a.ctrl[kCtrlEpoch];
+    const unsigned spin_w = a.ctrl[kCtrlSpin], skew = a.ctrl[kCtrlSkew];
+    const int spin = spin_w ? (int)spin_w : kSpinLimit;
+    const unsigned tag = ROUTE ? epoch0 + 1u : epoch0;   // number of this call
+    const unsigned wtag = tag + skew;                    // what this call's entries are stamped with (skew = 0)
+    auto give_up = [&]() __attribute__((always_inline)) {   // never wait for ever: say so in the control block and poison what this workgroup writes
+        atomicOr(error_flag, 1u);
+        misc_s[1] = 1;
+    };
+    // a kilobyte that is always there and always cached: what a wavefront reads for a piece its tile does not have
+    g_bytes *const dummy = (g_bytes *)(uintptr_t)((const unsigned char *)a.ctrl + kCtrlBytes);
+
+    const int tiles_g = F / 8, tiles_gs = a.n_shared ? Fs / 8 : 0, tiles_d = H / 16;
+    const int n_gs = a.n_shared * tiles_gs, n_ds = a.n_shared * tiles_d;
+    const int np_h = H / a.KP_h, np_f = F / a.KP_f, np_fs = a.n_shared ? Fs / a.KP_fs : 1;
+
+    // This workgroup's share of each class: items [sg_start, sg_start + sg_cnt) of the class's list.
+    // The shared experts' shares need nothing from the routing step.  (ROUTE: workgroup 0 also ranks the
+    // logits and builds the lists, which the others wait for; it takes the last place in the gate/up split.)
+    const int rk1 = ROUTE ? (b == 0 ? G - 1 : b - 1) : b;
+    const int rk2 = G - 1 - rk1;   // the down part is dealt the other way round: the odd items go elsewhere
+    int sg_start0, sg_cnt0, sg_start1 = 0, sg_cnt1 = 0, sg_start2, sg_cnt2, sg_start3 = 0, sg_cnt3 = 0;
+    {
+        const int per = n_gs / G, rem = n_gs % G;
+        sg_cnt0 = per + (rk1 < rem ? 1 : 0);
+        sg_start0 = rk1 * per + (rk1 < rem ? rk1 : rem);
+        const int per2 = n_ds / G, rem2 = n_ds % G;
+        sg_cnt2 = per2 + (rk2 < rem2 ? 1 : 0);
+        sg_start2 = rk2 * per2 + (rk2 < rem2 ? rk2 : rem2);
+    }
+    const int nt0 = sg_cnt0 * np_h;   // tiles of the first class: known at once
+    int ntiles = nt0;
+
+    // Record of tile j of this workgroup's list (by thread j):
+    //   words 0-1  address of tile rows 0..7 at the tile's panel (16-byte aligned; the two low bits say how the
+    //              tile is laid out: 0 gate/up, 1 down of a shared expert, 2 down of a routed expert, 3 no tile)
+    //   words 2-3  address of tile rows 8..15
+    //   word 4     class | first panel << 2 | last panel << 3 | (panel | B operand's identity << 8) << 4
+    //   word 5     first row of the item's results (list position of the expert's first token, or expert * T)
+    //   word 6     first column of the item's results
+    //   word 7     tokens of the expert | their bit mask << 8
+    auto write_record = [&](int j, int nt1, int nt2) __attribute__((always_inline)) {
+        int cls, r = j;
+        if (r < nt0) cls = 0;
+        else if ((r -= nt0) < nt1) cls = 1;
+        else if ((r -= nt1) < nt2) cls = 2;
+        else { r -= nt2; cls = 3; }
+        const int *cp = cls_s + cls * 8;
+        const int npan = cp[0], tl = cp[1], K = cp[3], KP = cp[4], rows = cp[5];
+        const int item = r / npan, pan = r - item * npan;
+        const int idx = cp[2] + item;
+        const int e = idx / tl, rt = idx - e * tl;
+        const bool shared = cls == 0 || cls == 2;
+        const int c = shared ? e : active_s[e];
+        const int rpi = cls < 2 ? 8 : 16;   // weight rows of an item per matrix
+        const size_t eoff = ((size_t)c * rows + (size_t)rt * rpi) * K + (size_t)pan * KP;   // (elements)
+        const u64 p0 = clsp_s[cls * 2] + 2 * eoff;
+        const u64 p1 = cls < 2 ? clsp_s[cls * 2 + 1] + 2 * eoff : p0 + (u64)16 * K;
+        const int key = cls < 2 ? 0 : cls == 2 ? 1 + e : 1 + a.n_shared + e;
+        int row0 = e * T, mm = T | (((1 << T) - 1) << 8);
+        if (!shared) {
+            row0 = offset_s[c];
+            mm = count_s[c] | (mask_s[c] << 8);
+        }
+        uint32_t *rec = tab_s + (size_t)j * kTabWords;
+        rec[0] = (uint32_t)p0 | (uint32_t)(cls < 2 ? 0 : cls - 1); rec[1] = (uint32_t)(p0 >> 32);
+        rec[2] = (uint32_t)p1; rec[3] = (uint32_t)(p1 >> 32);
+        rec[4] = (uint32_t)cls | (pan == 0 ? 4u : 0u) | (pan == npan - 1 ? 8u : 0u) | ((uint32_t)(pan | key << 8) << 4);
+        rec[5] = (uint32_t)row0;
+        rec[6] = (uint32_t)(rt * rpi);
+        rec[7] = (uint32_t)mm;
+    };
+    auto write_end_records = [&](int nt) __attribute__((always_inline)) {   // two records behind the last tile: nothing to load
+        if (tid < 2 * kTabWords) tab_s[(size_t)nt * kTabWords + tid] = (tid & 7) == 0 ? 3u : 0u;
+    };
+
+    // Piece i of this wavefront covers bytes [(16i+w) KB, +1 KB) of a tile seen as 16 rows of rs bytes (rs a
+    // multiple of 128, so a piece lies wholly in tile rows 0..7 or 8..15 and the choice between the two row
+    // pointers is uniform).  A tile of rs-byte rows has rs/64 pieces.  All NPI loads of a tile are issued
+    // unconditionally: for a piece beyond the tile the wavefront reads a kilobyte that is always cached and
+    // parks it beside the tile.  For each piece this lane keeps its global byte offset from the row group's
+    // first row and its LDS byte offset; both depend only on how the tile is laid out and are worked out again
+    // when that changes (three times per launch).  Two tiles are in flight per wavefront (st[0], st[1]).
+    u32x4 st[2][NPI];
+    unsigned goff[2][NPI];
+    int loff[2][NPI];
+    int st_geo[2] = {-1, -1};
+    unsigned st_hi[2] = {0, 0}, st_dm[2] = {0, 0};   // bit i: piece i lies in tile rows 8..15 | is no piece of the tile
+    auto geo_rs = [&](int gid) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(geo_s[gid * 2]); };
+    auto set_geo = [&](int s, int gid) __attribute__((always_inline)) {
+        st_geo[s] = gid;
+        const int rs = geo_rs(gid);
+        const int K2 = __builtin_amdgcn_readfirstlane(geo_s[gid * 2 + 1]);
+        const int np = rs / 64;
+        const float inv_d = rs ? 16.0f / (float)rs : 0.f;
+        unsigned hi = 0, dm = 0;
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) {
+            const int pc = i * kWaves + w;
+            if (pc < np) {
+                const int off = (pc << 10) + (lane << 4);
+                const int row = (int)(((float)(off >> 4) + 0.5f) * inv_d);
+                const int col = off - row * rs;
+                goff[s][i] = (unsigned)((row & 7) * K2 + col);
+                loff[s][i] = row * (rs + kRowPad) + col;
+                if ((pc << 10) >= 8 * rs) hi |= 1u << i;
+            } else {
+                goff[s][i] = (unsigned)(lane << 4);
+                loff[s][i] = a.tile_lds_bytes + (lane << 4);
+                dm |= 1u << i;
+            }
+        }
+        st_hi[s] = hi;
+        st_dm[s] = dm;
+    };
+    auto issue = [&](int s, int ti) __attribute__((always_inline)) {
+        const u32x4 r = *(const u32x4 *)(tab_s + (size_t)ti * kTabWords);
+        unsigned p0l = (unsigned)__builtin_amdgcn_readfirstlane((int)r.x);
+        const unsigned p0h = (unsigned)__builtin_amdgcn_readfirstlane((int)r.y);
+        const unsigned p1l = (unsigned)__builtin_amdgcn_readfirstlane((int)r.z);
+        const unsigned p1h = (unsigned)__builtin_amdgcn_readfirstlane((int)r.w);
+        const int gid = (int)(p0l & 3u);
+        p0l &= ~3u;
+        if (gid != st_geo[s]) set_geo(s, gid);
+        g_bytes *p0 = (g_bytes *)(uintptr_t)((u64)p0h << 32 | p0l);
+        g_bytes *p1 = (g_bytes *)(uintptr_t)((u64)p1h << 32 | p1l);
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) {
+            g_bytes *base = (st_dm[s] >> i) & 1u ? dummy : (st_hi[s] >> i) & 1u ? p1 : p0;   // uniform
+            st[s][i] = ld_stream(base + goff[s][i]);
+        }
+    };
+    auto park = [&](int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) *(u32x4 *)(tile_s + loff[s][i]) = st[s][i];
+    };
+
+    if (ROUTE) {
+        // ---- steps 1-3 inside this launch (Sec. 2.2, 2.3, App. D), as in the routing kernel ----
+        // every workgroup: its share of the T*E dot products, one per wavefront, each logit stored with the
+        // call's number as one 64-bit word
+        const int E = ra.E, TE = T * E;
+        const size_t n_pub = list_pub_entries(T, kk, C);
+        // (workgroup 0 gives the call its number in the control block, at its end, only when every workgroup
+        // has read the old one: each says so with a stamped word of its own)
+        u64 *const seen = ra.lists_pub + (size_t)kListReplicas * n_pub;
+        if (tid == 0) store_entry(seen + b, tag, 1u);
+        int tab_v = -1;
+        if (b == 0 && tid < E) tab_v = ra.slot_table[tid];
+        const uint16_t *x = (const uint16_t *)ra.hidden;
+        for (int q = b + w * G; q < TE; q += G * kWaves) {
+            const int t = q / E, e = q - t * E;
+            const float *wrow = ra.router_w + (size_t)e * H;
+            const uint16_t *xr = x + (size_t)t * H;
+            const float bias = ra.router_bias ? ra.router_bias[e] : 0.f;
+            float dot = 0.f;
+#pragma unroll 8
+            for (int h = lane * 4; h < H; h += kWave * 4) {
+                const float4 wv = *(const float4 *)(wrow + h);
+                const uint2 xv = *(const uint2 *)(xr + h);
+                dot += wv.x * bf16_lo(xv.x) + wv.y * bf16_hi(xv.x) + wv.z * bf16_lo(xv.y) + wv.w * bf16_hi(xv.y);
+            }
+#pragma unroll
+            for (int m = kWave / 2; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, kWave);
+            dot += bias;
+            if (lane == 0) {
+                store_entry(ra.tagged_logits + q, wtag, __float_as_uint(dot));
+                if (ra.logits_opt) ra.logits_opt[q] = dot;
+            }
+        }
+        if (b == 0) {
+            // workgroup 0: one wavefront per token ranks its logits; then histogram, slot lookup, miss list and
+            // per-slot lists out of LDS (which nothing else uses yet), every word of the lists published
+            PostLds L = carve_lds((int *)lds, E, C, A);
+            if (tid < E) {
+                L.tab_s[tid] = tab_v;
+                L.hist_s[tid] = 0;
+            }
+            for (int i = tid; i < C * ((T + 31) >> 5); i += kThreads) L.cnt_s[i] = 0;
+            lds_f32 *lg = L.lg_s + w * lg_stride(E);
+            if (w < T) {
+                const int t = w;
+                const u64 *src = ra.tagged_logits + (size_t)t * E;
+                for (int e0 = 0; e0 < E; e0 += kWave) {
+                    const int e = e0 + lane;
+                    u64 v = (u64)tag << 32;
+                    int polls = 0;
+                    for (;;) {
+                        if (e < E) v = load_entry(src + e);
+                        if (__ballot((unsigned)(v >> 32) != tag) == 0ull) break;
+                        if (++polls > spin) {
+                            if (lane == 0) atomicOr(error_flag, 1u);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                    if (e < E) {
+                        const float f = __uint_as_float((unsigned)v);
+                        lg[e] = (f == f) ? f : -INFINITY;   // NaN cannot win a comparison; rank it last
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+                // (up to 128 experts here: the ranking of more needs so many registers that the whole
+                // kernel would be launched with scratch memory; those batches keep the routing kernel)
+                float gate;
+                if (E <= kWave)
+                    gate = wave_topk_gate_n<1>(E, kk, ra.topk_idx + (size_t)t * kk, L.idx_s + t * kk,
+                                               ra.topk_w + (size_t)t * kk, lg);
+                else
+                    gate = wave_topk_gate_n<2>(E, kk, ra.topk_idx + (size_t)t * kk, L.idx_s + t * kk,
+                                               ra.topk_w + (size_t)t * kk, lg);
+                // the final sum of every workgroup needs the gate weights: plain stores of this workgroup are
+                // not visible to the others inside the launch, so they travel as stamped entries too
+                if (lane < kk) {
+                    u64 *gw_pub = seen + kMaxGroups;
+                    for (int rep = 0; rep < kListReplicas; ++rep)
+                        store_entry(gw_pub + (size_t)rep * A + t * kk + lane, wtag, __float_as_uint(gate));
+                }
+            }
+            __syncthreads();
+            block_post_small<true>(L.idx_s, L.tab_s, T, kk, E, C, ra, L.hist_s, L.cnt_s, L.scan_s, L.off_s, wtag);
+            __syncthreads();   // (the LDS used above is free again)
+        }
+    }
+    if (tid == 0) misc_s[1] = 0;   // (a barrier follows before anything can set it)
+    if (tid == 0) {
+        int *c0 = cls_s, *c1 = cls_s + 8, *c2 = cls_s + 16, *c3 = cls_s + 24;
+        c0[0] = np_h; c0[1] = tiles_gs; c0[2] = sg_start0; c0[3] = H; c0[4] = a.KP_h; c0[5] = Fs;
+        c1[0] = np_h; c1[1] = tiles_g; c1[2] = 0; c1[3] = H; c1[4] = a.KP_h; c1[5] = F;
+        c2[0] = np_fs; c2[1] = tiles_d; c2[2] = sg_start2; c2[3] = Fs; c2[4] = a.KP_fs; c2[5] = H;
+        c3[0] = np_f; c3[1] = tiles_d; c3[2] = 0; c3[3] = F; c3[4] = a.KP_f; c3[5] = H;
+        clsp_s[0] = (u64)(uintptr_t)a.sh_gate; clsp_s[1] = (u64)(uintptr_t)a.sh_up;
+        clsp_s[2] = (u64)(uintptr_t)a.w_gate; clsp_s[3] = (u64)(uintptr_t)a.w_up;
+        clsp_s[4] = (u64)(uintptr_t)a.sh_down; clsp_s[5] = 0;
+        clsp_s[6] = (u64)(uintptr_t)a.w_down; clsp_s[7] = 0;
+        geo_s[0] = 2 * a.KP_h; geo_s[1] = 2 * H;
+        geo_s[2] = 2 * a.KP_fs; geo_s[3] = 2 * Fs;
+        geo_s[4] = 2 * a.KP_f; geo_s[5] = 2 * F;
+        geo_s[6] = 0; geo_s[7] = 0;
+    }
+
+    u32x4 bx[kPieces];
+    unsigned bx_sig = 0xffffffffu;   // panel | identity << 8 of the B operand that the registers hold
+    int c_geo = -1, c_rs = 128;
+    unsigned avalid = 0;             // bit j: this wavefront's j-th column block exists in the parked tile
+    int aoff[kPieces];
+    auto set_cgeo = [&](int gid) __attribute__((always_inline)) {
+        c_geo = gid;
+        c_rs = geo_rs(gid);
+        const int nkb = c_rs / 64;
+        avalid = 0;
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) {
+            const int kb = w + kWaves * j;
+            if (kb < nkb) avalid |= 1u << j;
+            aoff[j] = n * (c_rs + kRowPad) + kb * 64 + g * 16;
+        }
+    };
+    // B operand of this wavefront's column blocks.  Gate/up part: the hidden states of tokens 0..T-1, token n
+    // on column n.  Down part: the activation rows of the expert's list, entry n on column n; they come as
+    // stamped entries from whichever workgroups computed them and are polled until they carry this call's number.
+    auto load_bx = [&](int cls, int pan, int row0, int m) __attribute__((always_inline)) {
+        const int cgid = cls < 2 ? 0 : cls - 1;
+        if (cgid != c_geo) set_cgeo(cgid);
+        if (cls < 2) {
+            const int boff = n < T ? n * H + pan * (c_rs / 2) : -1;
+#pragma unroll
+            for (int j = 0; j < kPieces; ++j) {
+                const int kb = w + kWaves * j;
+                bx[j] = (u32x4){0u, 0u, 0u, 0u};
+                if (((avalid >> j) & 1u) && boff >= 0) bx[j] = *(const u32x4 *)(a.hidden + (unsigned)(boff + kb * 32 + g * 8));
+            }
+            // (everything in flight is waited for here, on this rare path, so that behind it the compiler knows
+            // the operand to be there and the common path's waits stay exact)
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        } else {
+            const u64 *src = cls == 2 ? +a.act_sh : +a.act;
+            const int rowlen = (cls == 2 ? +Fs : +F) / 2;
+            const bool valid = n < m;
+            const u64 *base = src + (size_t)(row0 + (valid ? n : 0)) * rowlen + (size_t)pan * (c_rs / 4) + g * 4;
+            int polls = 0;
+            for (;;) {
+                bool ok = true;
+#pragma unroll
+                for (int j = 0; j < kPieces; ++j) {
+                    const int kb = w + kWaves * j;
+                    bx[j] = (u32x4){0u, 0u, 0u, 0u};
+                    if (((avalid >> j) & 1u) && valid) {
+                        const u64 *p = base + kb * 16;
+                        const u64 e0 = load_entry(p), e1 = load_entry(p + 1), e2 = load_entry(p + 2), e3 = load_entry(p + 3);
+                        ok = ok && (unsigned)(e0 >> 32) == tag && (unsigned)(e1 >> 32) == tag &&
+                             (unsigned)(e2 >> 32) == tag && (unsigned)(e3 >> 32) == tag;
+                        bx[j] = (u32x4){(unsigned)e0, (unsigned)e1, (unsigned)e2, (unsigned)e3};
+                    }
+                }
+                if (__ballot(!ok) == 0ull) break;
+                if (++polls > spin) {   // cannot happen with the whole grid resident
+                    give_up();
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(2);
+            }
+        }
+    };
+    auto load_bx_of = [&](int ti) __attribute__((always_inline)) {   // the B operand that tile ti needs
+        const uint32_t *rec = tab_s + (size_t)ti * kTabWords;
+        const unsigned fl = (unsigned)__builtin_amdgcn_readfirstlane((int)rec[4]);
+        const int row0 = __builtin_amdgcn_readfirstlane((int)rec[5]);
+        const int m = __builtin_amdgcn_readfirstlane((int)rec[7]) & 0xff;
+        load_bx((int)(fl & 3u), (int)((fl >> 4) & 0xffu), row0, m);
+        bx_sig = fl >> 4;
+    };
+
+    // the shared experts' first tiles need nothing from the routing step: their weights are in flight while
+    // the lists are on their way
+    int issued = 0;   // tiles requested so far (0, 1 or 2)
+    if (nt0 > 0) {
+        __syncthreads();   // (the class table)
+        for (int j = tid; j < nt0; j += kThreads) write_record(j, 0, 0);
+        write_end_records(nt0);
+        __syncthreads();
+        issue(0, 0);
+        issued = 1;
+        if (nt0 >= 2) {
+            load_bx_of(0);
+            issue(1, 1);
+            issued = 2;
+        }
+    }
+    int n_act;
+    if (ROUTE) {
+        // every workgroup: the lists, from one of the published copies.  One lane watches the first word,
+        // gently (255 workgroups asking for all words all the time would be a load of its own on the few
+        // memory channels the copies live in); once it is there the workgroup reads them all.
+        const size_t n_pub = list_pub_entries(T, kk, C);
+        const u64 *pub = ra.lists_pub + (size_t)(b % kListReplicas) * n_pub;
+        if (tid == 0 && b != 0) {
+            int polls = 0;
+            while ((unsigned)(load_entry(pub) >> 32) != tag) {
+                if (++polls > spin) break;   // (the loop below reports it)
+                __builtin_amdgcn_s_sleep(16);
+            }
+        }
+        for (int i = tid; i < A; i += kThreads) pos_s[i] = -1;
+        __syncthreads();
+        for (int i = tid; i < (int)n_pub; i += kThreads) {
+            u64 v = 0;
+            int polls = 0;
+            for (;;) {
+                v = load_entry(pub + i);
+                if ((unsigned)(v >> 32) == tag) break;
+                if (++polls > spin) {
+                    give_up();
+                    v = 0;   // (stay inside every array below)
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+            }
+            const int val = (int)(unsigned)v;
+            if (i == 0) misc_s[0] = val;
+            else if (i <= C) count_s[i - 1] = val < 0 ? 0 : val > T ? T : val;
+            else if (i <= 2 * C) offset_s[i - 1 - C] = val < 0 ? 0 : val > A ? A : val;
+            else if (i <= 3 * C) active_s[i - 1 - 2 * C] = val < 0 ? 0 : val >= C ? C - 1 : val;
+            else {
+                const int asg = val < 0 ? -1 : val >= A ? A - 1 : val;   // flat assignment id of list entry i - 1 - 3C
+                perm_s[i - 1 - 3 * C] = (asg < 0 ? 0 : asg) / kk;
+                if (asg >= 0) pos_s[asg] = i - 1 - 3 * C;
+            }
+        }
+        __syncthreads();
+        n_act = misc_s[0];
+    } else {
+        // one trip to memory for everything the routing step left behind
+        for (int i = tid; i < C; i += kThreads) {
+            count_s[i] = a.slot_count[i];
+            offset_s[i] = a.slot_offset[i];
+            active_s[i] = a.active_slots[i];
+        }
+        for (int i = tid; i < A; i += kThreads) {
+            perm_s[i] = a.perm[i] / kk;
+            pos_s[i] = a.pos[i];
+        }
+        n_act = (int)(*a.n_active);
+        __syncthreads();
+    }
+    n_act = n_act < 0 ? 0 : n_act > C ? C : n_act;
+    // the tokens of each slot as a bit mask (a token names a slot at most once)
+    for (int c = tid; c < C; c += kThreads) {
+        int m = 0;
+        const int cnt = count_s[c], off = offset_s[c];
+        for (int j = 0; j < cnt && off + j < A; ++j) m |= 1 << (perm_s[off + j] & 15);
+        mask_s[c] = m;
+    }
+
+    // routed shares: equal runs of the gate/up list (items all alike); the down list is cut into runs of equal
+    // numbers of TILES (a shared expert's item can have another number of panels than a routed one)
+    {
+        // (ROUTE: workgroup 0 starts its run a few microseconds late: two items fewer for it)
+        const int late = ROUTE && n_act * tiles_g >= 4 * G ? 2 : 0;
+        const int total = n_gs + n_act * tiles_g + late;
+        const int per = total / G, rem = total % G;
+        int cnt = per + (rk1 < rem ? 1 : 0);
+        sg_start1 = rk1 * per + (rk1 < rem ? rk1 : rem) - sg_start0;
+        if (rk1 == G - 1) cnt -= late;
+        sg_cnt1 = cnt - sg_cnt0;
+        if (sg_cnt1 < 0) sg_cnt1 = 0;
+        // Down part: workgroup of rank x starts at routed item max(0, x * total tiles / G - tiles of the shared
+        // items before x) / panels per routed item: never decreasing in x, 0 for x = 0, all for x = G.
+        const int n_routed = n_act * tiles_d;
+        const long long total2 = (long long)n_ds * np_fs + (long long)n_routed * np_f;
+        const int per2 = n_ds / G, rem2 = n_ds % G;
+        auto routed_before = [&](int x) __attribute__((always_inline)) {
+            const long long sh = (long long)(x * per2 + (x < rem2 ? x : rem2)) * np_fs;
+            const long long rt = (long long)x * total2 / G - sh;
+            const long long r = rt > 0 ? rt / np_f : 0;
+            return (int)(r < n_routed ? r : n_routed);
+        };
+        sg_start3 = routed_before(rk2);
+        sg_cnt3 = routed_before(rk2 + 1) - sg_start3;
+    }
+    int nt1 = sg_cnt1 * np_h, nt2 = sg_cnt2 * np_fs, nt3 = sg_cnt3 * np_f;
+    if (nt0 + nt1 + nt2 + nt3 > a.tab_cap) {   // cannot happen: the host sizes the table for the largest share
+        give_up();
+        nt3 = 0;
+        if (nt0 + nt1 + nt2 > a.tab_cap) nt2 = 0;
+        if (nt0 + nt1 > a.tab_cap) nt1 = 0;
+    }
+    ntiles = nt0 + nt1 + nt2 + nt3;
+    if (tid == 0) {
+        cls_s[8 + 2] = sg_start1;
+        cls_s[24 + 2] = sg_start3;
+    }
+    __syncthreads();   // (the masks, the class table)
+    for (int j = nt0 + tid; j < ntiles; j += kThreads) write_record(j, nt1, nt2);
+    write_end_records(ntiles);
+    __syncthreads();
+    MOE_STAMP(tl_lists);
+
+    // ---- the weighted sum back into token order (Sec. 2.2 last line; the join of App. D when `accumulate`) ----
+    auto join = [&]() __attribute__((always_inline)) {
+        const int S = kk + a.n_shared, nent = T * 8 * S;
+        float *val_s = (float *)tile_s;   // [token][column of the strip][source]; the tile buffer is free by now
+        float *gw_s = (float *)red_s;     // gate weights, on their way while the entries are waited for
+        if (ROUTE) {
+            // (written by workgroup 0 of this launch, long ago; stamped, so that what is read is what was written)
+            const size_t n_pub = list_pub_entries(T, kk, C);
+            const u64 *gw_pub = ra.lists_pub + (size_t)kListReplicas * n_pub + kMaxGroups + (size_t)(b % kListReplicas) * A;
+            for (int i = tid; i < A; i += kThreads) {
+                u64 x = 0;
+                int polls = 0;
+                for (;;) {
+                    x = load_entry(gw_pub + i);
+                    if ((unsigned)(x >> 32) == tag) break;
+                    if (++polls > spin) {
+                        give_up();
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                gw_s[i] = __uint_as_float((unsigned)x);
+            }
+        } else {
+            for (int i = tid; i < A; i += kThreads) gw_s[i] = a.topk_w[i];
+        }
+        for (int u = b; u < H / 8; u += G) {
+            __syncthreads();
+            for (int i = tid; i < nent; i += kThreads) {
+                const int tc = i / S, src = i - tc * S, t = tc >> 3, col = u * 8 + (tc & 7);
+                const u64 *p = nullptr;
+                if (src < kk) {
+                    const int row = pos_s[t * kk + src];
+                    if (row >= 0) p = a.o + (size_t)row * H + col;
+                } else {
+                    p = a.o_sh + ((size_t)(src - kk) * T + t) * H + col;
+                }
+                float v = 0.f;   // an assignment whose expert is not resident adds nothing here
+                if (p) {
+                    u64 x = 0;
+                    int polls = 0;
+                    for (;;) {
+                        x = load_entry(p);
+                        if ((unsigned)(x >> 32) == tag) break;
+                        if (++polls > spin) {   // cannot happen with the whole grid resident
+                            give_up();
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                    v = __uint_as_float((unsigned)x);
+                }
+                val_s[i] = v;
+            }
+            __syncthreads();
+            const bool poisoned = misc_s[1] != 0;
+            if (tid < T * 8) {
+                const int t = tid >> 3, col = u * 8 + (tid & 7);
+                const size_t o = (size_t)t * H + col;
+                float acc = 0.f;
+                if (a.accumulate)
+                    acc = a.out_bf16 ? __uint_as_float((uint32_t)((const uint16_t *)a.out)[o] << 16)
+                                     : ((const float *)a.out)[o];
+                for (int jj = 0; jj < kk; ++jj) acc += gw_s[t * kk + jj] * val_s[tid * S + jj];
+                for (int i = 0; i < a.n_shared; ++i) acc += val_s[tid * S + kk + i];
+                if (poisoned) acc = __uint_as_float(0x7fc00000u);   // a wait ran out: not a result
+                if (a.out_bf16) ((uint16_t *)a.out)[o] = (uint16_t)f32_to_bf16_rne(acc);
+                else ((float *)a.out)[o] = acc;
+            }
+        }
+    };
+    auto finish = [&]() __attribute__((always_inline)) {
+        join();
+        __syncthreads();
+        if (tid == 0 && misc_s[1] != 0 && a.miss_count)
+            __hip_atomic_store(a.miss_count, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (ROUTE && b == 0) {
+            // the call's number goes into the control block once every workgroup has read the old one
+            const size_t n_pub = list_pub_entries(T, kk, C);
+            const u64 *seen = ra.lists_pub + (size_t)kListReplicas * n_pub;
+            for (int i = tid; i < G; i += kThreads) {
+                int polls = 0;
+                while ((unsigned)(load_entry(seen + i) >> 32) != tag) {
+                    if (++polls > spin) {
+                        atomicOr(error_flag, 1u);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+            }
+            __syncthreads();
+            if (tid == 0) a.ctrl[kCtrlEpoch] = tag;
+        }
+    };
+
+    if (ntiles == 0) {
+        finish();
+        return;
+    }
+    if (issued == 0) {
+        issue(0, 0);
+        issued = 1;
+    }
+    if (issued == 1) {
+        // (the first B operand between the first two requests: its wait then covers the first tile only)
+        load_bx_of(0);
+        issue(1, 1);
+    }
+
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+
+    auto multiply = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) {
+            if ((avalid >> j) & 1u) {
+                u32x4 av = *(const u32x4 *)(tile_s + aoff[j]);
+                acc = mfma(av, bx[j], acc);
+            }
+        }
+    };
+    // Results leave in three stages, one step apart, so that nothing of it sits between the parking of a tile and
+    // the request for the next one except a handful of store instructions in four wavefronts:
+    //   post    (step t, behind the multiplication) every wavefront puts its partial 16x16 result into red_s;
+    //   reduce  (step t+1, behind the multiplication) all wavefronts add the sixteen partial results: element
+    //           q = lane*4 + j of the MFMA result layout is column (q/4)%16, tile row 4*(q/64) + q%4; wavefront r
+    //           takes elements 16r..16r+15, four lanes per element, each lane four partial results, then the four
+    //           lanes add up (fixed order: the result does not depend on scheduling).  Gate rows are tile rows
+    //           0..7 (elements 0..127) and the up row of the same activation sits 128 elements further on.  The
+    //           finished values (SiLU(gate) * up, or the down projection's sums) go to out_s;
+    //   store   (step t+2, between the parking and the request) wavefronts 12-15 send them to memory as stamped
+    //           entries.  A store placed there is older than every load that a later wait must leave in flight,
+    //           so whether a wavefront stored or not, no wait for a tile ever covers a younger tile (the memory
+    //           counter counts loads and stores in order).
+    // red_s has two halves used in turn, because a reduction reads one while the next item is posted.
+    float *out_s = (float *)(red_s + 2 * kWaves * kRedStride);   // [256] finished values of one item
+    int post_half = 0;
+    bool red_pending = false, st_pending = false;
+    int rd_cls = 0, rd_row0 = 0, rd_col = 0, rd_mm = 0, rd_half = 0;   // the item posted last
+    int sd_cls = 0, sd_row0 = 0, sd_col = 0, sd_mm = 0;                // the item reduced last
+    auto quad_sum = [&](float v) __attribute__((always_inline)) {
+        // (data-parallel-primitive control quad_perm: each lane reads lane 1,0,3,2, then 2,3,0,1, of its group of four)
+        v += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0xb1, 0xf, 0xf, false));
+        v += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0x4e, 0xf, 0xf, false));
+        return v;
+    };
+    auto partial4 = [&](const unsigned char *half, int q, int pg) __attribute__((always_inline)) {   // partial results 4pg..4pg+3 of element q
+        const unsigned char *p = half + (4 * pg) * kRedStride + q * 4;
+        const float x0 = *(const float *)p, x1 = *(const float *)(p + kRedStride);
+        const float x2 = *(const float *)(p + 2 * kRedStride), x3 = *(const float *)(p + 3 * kRedStride);
+        return (x0 + x1) + (x2 + x3);
+    };
+    auto reduce = [&]() __attribute__((always_inline)) {
+        const int ql = lane >> 2, pg = lane & 3;
+        const int q = w * 16 + ql;
+        const unsigned char *half = red_s + rd_half * (kWaves * kRedStride);
+        if (rd_cls < 2) {
+            if (w < 8) {
+                const float s0 = quad_sum(partial4(half, q, pg)), s1 = quad_sum(partial4(half, q + 128, pg));
+                // SiLU(s0) * s1 = s0 / (1 + 2^(-s0 log2 e)) * s1 (hardware exponential and reciprocal: the result is
+                // rounded to bf16 anyway)
+                const float v = s0 * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * s0)) * s1;
+                if (pg == 0) out_s[q] = v;
+            }
+        } else {
+            const float s0 = quad_sum(partial4(half, q, pg));
+            if (pg == 0) out_s[q] = s0;
+        }
+        sd_cls = rd_cls; sd_row0 = rd_row0; sd_col = rd_col; sd_mm = rd_mm;
+        st_pending = true;
+        red_pending = false;
+    };
+    auto store_results = [&]() __attribute__((always_inline)) {
+        if (w >= 12) {
+            const int m = sd_mm & 0xff, mask = sd_mm >> 8;
+            if (sd_cls < 2) {
+                if (w == 12) {
+                    // one 64-bit entry per (token, pair of activations): lane = token * 4 + pair
+                    const int tok = lane >> 2, pr = lane & 3;
+                    // element of (token, row): ((row / 4) * 16 + token) * 4 + row % 4, rows 2 pr and 2 pr + 1
+                    const int q = (((pr >> 1) * 16 + tok) << 2) + ((pr & 1) << 1);
+                    if ((mask >> tok) & 1) {
+                        // entry of the expert's list that token `tok` is: the number of its tokens below it
+                        const int li = __popc((unsigned)mask & ((1u << tok) - 1u));
+                        u64 *dst = (sd_cls == 0 ? a.act_sh : a.act) +
+                                   (size_t)(sd_row0 + li) * ((sd_cls == 0 ? Fs : F) / 2) + ((sd_col >> 1) + pr);
+                        store_entry(dst, wtag, f32_to_bf16_rne(out_s[q]) | (f32_to_bf16_rne(out_s[q + 1]) << 16));
+                    }
+                }
+            } else {
+                const int q = (w - 12) * 64 + lane;
+                const int ent = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3);
+                if (ent < m) {
+                    u64 *dst = (sd_cls == 2 ? a.o_sh : a.o) + (size_t)(sd_row0 + ent) * H + (sd_col + row);
+                    store_entry(dst, wtag, __float_as_uint(out_s[q]));
+                }
+            }
+        }
+        st_pending = false;
+    };
+    // everything this workgroup still holds back, out to memory (all wavefronts together: rare paths only)
+    auto drain_results = [&]() __attribute__((always_inline)) {
+        if (st_pending) store_results();
+        if (red_pending) {
+            __syncthreads();
+            reduce();
+            __syncthreads();
+            store_results();
+        }
+    };
+
+    // one tile: park it, send out the results reduced in the last step, refresh the B operand if the expert
+    // changed, put the tile two steps ahead in flight, multiply, reduce the item posted in the last step, and on
+    // the item's last panel post the partial result
+    auto step = [&](int s, int ti) __attribute__((always_inline)) {
+        MOE_CYC_BEGIN();
+        const u32x4 d = *(const u32x4 *)(tab_s + (size_t)ti * kTabWords + 4);
+        const unsigned fl = (unsigned)__builtin_amdgcn_readfirstlane((int)d.x);
+        MOE_CYC(7);
+#ifdef MOE_STREAM_TRACE
+        // (the wait for the tile alone: one register of its last piece is touched before the parking starts)
+        asm volatile("" :: "v"(st[s][NPI - 1]));
+#endif
+        MOE_CYC(0);
+        park(s);
+        MOE_CYC(1);
+        if (st_pending) store_results();
+        if ((fl >> 4) != bx_sig) {
+            // (first everything out that this workgroup still holds back: it may be what it, or a workgroup
+            // that it waits for, waits for)
+            drain_results();
+            const int row0 = __builtin_amdgcn_readfirstlane((int)d.y);
+            const int m = __builtin_amdgcn_readfirstlane((int)d.w) & 0xff;
+            load_bx((int)(fl & 3u), (int)((fl >> 4) & 0xffu), row0, m);
+            bx_sig = fl >> 4;
+        }
+        MOE_CYC(2);
+        issue(s, ti + 2);
+        MOE_CYC(3);
+        __syncthreads();
+        MOE_CYC(4);
+        if (fl & 4u) acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        multiply();
+        if (red_pending) reduce();   // (the item posted in the last step, or earlier)
+        if (fl & 8u) {
+            *(f32x4 *)(red_s + post_half * (kWaves * kRedStride) + w * kRedStride + lane * 16) = acc;
+            red_pending = true;
+            rd_half = post_half;
+            post_half ^= 1;
+            rd_cls = (int)(fl & 3u);
+            rd_row0 = __builtin_amdgcn_readfirstlane((int)d.y);
+            rd_col = __builtin_amdgcn_readfirstlane((int)d.z);
+            rd_mm = __builtin_amdgcn_readfirstlane((int)d.w);
+        }
+        MOE_CYC(5);
+        __syncthreads();   // every wavefront is done with the tile in LDS (and its partial result is posted)
+        MOE_CYC(6);
+#ifdef MOE_STREAM_TRACE
+        if ((fl & 3u) < 2u) MOE_STAMP(tl_phase);   // (the last gate/up tile leaves the stamp)
+        if (ti == 0) MOE_STAMP(tl_first);
+#endif
+    };
+
+    // (tiles alternate between the two register sets, so the loop body is two steps; leaving it between them
+    // does not come back, so the loop is always entered and re-entered with the same loads in flight and each
+    // park waits for its own tile only)
+    for (int t = 0; t < ntiles; t += 2) {
+        step(0, t);
+        if (t + 1 >= ntiles) break;
+        step(1, t + 1);
+    }
+    drain_results();
+    MOE_STAMP(tl_loop);
+    __syncthreads();   // (the last reduction has read red_s, which the join reuses)
+    finish();
+#ifdef MOE_STREAM_TRACE
+    if (tid == 0 && blockIdx.x < kTimelineGroups) {
+        unsigned long long *tl = g_layer_timeline[blockIdx.x];
+        tl[0] = tl_start; tl[1] = tl_lists; tl[2] = tl_first; tl[3] = tl_phase; tl[4] = tl_loop; tl[5] = wall_clock64();
+        tl[6] = (unsigned long long)(sg_cnt0 + sg_cnt1) << 32 | (unsigned long long)(sg_cnt2 + sg_cnt3);
+        tl[7] = (unsigned long long)ntiles;
+    }
+    if (lane == 0 && (w == 0 || w == kWaves - 1) && blockIdx.x < kTimelineGroups) {
+        unsigned long long *tl = g_layer_timeline[blockIdx.x] + (w == 0 ? 8 : 16);
+        for (int i = 0; i < 8; ++i) tl[i] = (unsigned long long)cyc_sum[i];
+    }
+#endif
+}
+
+struct DevInfo {
+    int n_cus = 0;
+    bool attr_done[8] = {};
+};
+DevInfo g_dev[kMaxDevices];
+std::mutex g_dev_mutex;
+
+}  // namespace
+
+namespace {
+
+// number of CUs of the current device = workgroups of the launch (0: the runtime would not say)
+int device_cus(hipError_t *err)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    int n = 0;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(g_dev_mutex);
+        DevInfo &d = g_dev[dev];
+        if (d.n_cus == 0) {
+            int nc = 0;
+            e = hipDeviceGetAttribute(&nc, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e == hipSuccess) d.n_cus = nc > 0 ? (nc < kMaxGroups ? nc : kMaxGroups) : 256;
+        }
+        n = d.n_cus;
+    }
+    if (err) *err = e;
+    return n;
+}
+
+int max_panel(int H, int F, int n_shared, int F_shared)
+{
+    const int kp_h = stream_panel_width(H), kp_f = stream_panel_width(F);
+    const int kp_s = n_shared > 0 ? stream_panel_width(F_shared) : 0;
+    int kp = kp_h > kp_f ? kp_h : kp_f;
+    return kp > kp_s ? kp : kp_s;
+}
+
+// upper bound of the tiles in one workgroup's list when G workgroups share the layer
+int layer_tab_cap(int T, int C, int H, int F, int n_shared, int F_shared, int G)
+{
+    const int np_h = H / stream_panel_width(H), np_f = F / stream_panel_width(F);
+    const int np_fs = n_shared > 0 ? F_shared / stream_panel_width(F_shared) : 1;
+    const long long n_gs = (long long)n_shared * (n_shared > 0 ? F_shared / 8 : 0), n_ds = (long long)n_shared * (H / 16);
+    const long long t0 = (n_gs / G + 1) * np_h;
+    const long long t1 = ((n_gs + (long long)C * (F / 8) + 2) / G + 1) * np_h;
+    const long long t2 = (n_ds / G + 1) * np_fs;
+    const long long t3 = ((n_ds * np_fs + (long long)C * (H / 16) * np_f) / G / np_f + 2) * np_f;
+    const long long cap = t0 + t1 + t2 + t3 + 4;
+    return cap > (1 << 20) ? (1 << 20) : (int)cap;
+}
+
+size_t layer_lds_bytes(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared, bool route, int tab_cap)
+{
+    const size_t tile = (size_t)16 * (2 * (size_t)max_panel(H, F, n_shared, F_shared) + kStreamRowPad);
+    size_t need = tile + kDumpBytes + (size_t)2 * kWaves * kRedStride + 1024 + (((size_t)4 * C + 2 * (size_t)T * k + 8 + 32 + 8 + 16 + 3) & ~(size_t)3) * 4 +
+                  ((size_t)tab_cap + 2) * kTabWords * 4;
+    if (route) {
+        const size_t r = post_lds_bytes(E, C, T * k, true);
+        need = need > r ? need : r;
+    }
+    return need;
+}
+
+}  // namespace
+
+bool use_layer_kernel(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared)
+{
+    if (T > 16 || C < 1 || C > kMaxC || H % 64 != 0 || F % 64 != 0 || (n_shared > 0 && F_shared % 64 != 0)) return false;
+    if (!use_stream_kernels(T, k, C, H, F, n_shared, F_shared)) return false;
+    const size_t tile = (size_t)16 * (2 * (size_t)max_panel(H, F, n_shared, F_shared) + kStreamRowPad);
+    if ((size_t)T * 8 * (k + n_shared) * 4 > tile) return false;   // the strip of the final sum sits in the tile buffer
+    const int G = device_cus(nullptr);
+    if (G <= 0) return false;
+    const int cap = layer_tab_cap(T, C, H, F, n_shared, F_shared, G);
+    return layer_lds_bytes(T, k, E, C, H, F, n_shared, F_shared, E > 0, cap) <= (size_t)kLdsBytes;
+}
+
+hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t s)
+{
+    hipError_t e = hipSuccess;
+    const int grid = device_cus(&e);
+    if (e != hipSuccess) return e;
+    LayerArgs args = a;
+    args.KP_h = stream_panel_width(a.H);
+    args.KP_f = stream_panel_width(a.F);
+    args.KP_fs = a.n_shared > 0 ? stream_panel_width(a.F_sh) : 0;
+    const int kp = max_panel(a.H, a.F, a.n_shared, a.F_sh);
+    args.tile_lds_bytes = 16 * (2 * kp + kRowPad);
+    args.tab_cap = layer_tab_cap(a.T, a.C, a.H, a.F, a.n_shared, a.F_sh, grid);
+    const int E = route ? route->E : 0;
+    const size_t lds = layer_lds_bytes(a.T, a.k, E, a.C, a.H, a.F, a.n_shared, a.F_sh, route != nullptr, args.tab_cap);
+    if (lds > (size_t)kLdsBytes) return hipErrorInvalidValue;
+    if (route && (!route->lists_pub || E > 2 * kWave)) return hipErrorInvalidValue;
+    const int npi = (kp / 32 + kWaves - 1) / kWaves;   // 1..4 pieces per wavefront and tile
+    static const void *const fns[2][4] = {
+        {(const void *)layer_kernel<1, false>, (const void *)layer_kernel<2, false>, (const void *)layer_kernel<3, false>,
+         (const void *)layer_kernel<4, false>},
+        {(const void *)layer_kernel<1, true>, (const void *)layer_kernel<2, true>, (const void *)layer_kernel<3, true>,
+         (const void *)layer_kernel<4, true>}};
+    const void *fn = fns[route ? 1 : 0][npi - 1];
+    {
+        int dev = 0;
+        e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        std::lock_guard<std::mutex> lock(g_dev_mutex);
+        DevInfo &d = g_dev[dev];
+        const int which = (route ? 4 : 0) + npi - 1;
+        if (!d.attr_done[which]) {
+            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+            if (e != hipSuccess) return e;
+            d.attr_done[which] = true;
+        }
+    }
+    RouteArgs rargs = {};
+    if (route) rargs = *route;
+    void *params[] = {&args, &rargs};
+    hipError_t le = launch_timed(fn, dim3(grid), dim3(kThreads), params, lds, s, kKindLayer);
+    if (le != hipSuccess) return le;
+    return hipGetLastError();
+}
+
+hipError_t read_layer_timeline(void *dst, size_t bytes)
+{
+#ifdef MOE_STREAM_TRACE
+    if (bytes != sizeof(g_layer_timeline)) return hipErrorInvalidValue;
+    return hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_layer_timeline), sizeof(g_layer_timeline));
+#else
+    (void)dst; (void)bytes;
+    return hipErrorNotSupported;
+#endif
+}
+
+}  // namespace moe

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <mutex>
 
 namespace moe {
 
@@ -83,6 +84,12 @@ struct WsLayout {
 constexpr int kCtrlNActive = 1;   // number of resident slots that received at least one token
 constexpr int kCtrlError = 2;     // non-zero once a bounded wait inside a kernel has run out
 constexpr int kCtrlEpoch = 3;     // routing calls completed on this workspace (the tag of the last one)
+// Two words that only a test sets (moe_workspace_init clears them): with them the host forces every bounded
+// wait inside a kernel to run out, so that the failure path can be exercised while every kernel still exits.
+constexpr int kCtrlSpin = 4;      // polls before a wait gives up (0 = the built-in bound)
+constexpr int kCtrlSkew = 5;      // added to the call number that producers stamp their entries with (0)
+constexpr int kMaxDevices = 64;   // devices the per-device launch state is kept for
+constexpr int kKindLayer = 9;     // measurement aid: the one-launch layer kernel (MOE_KERNEL_LAYER)
 
 static inline int n_slices(int F) { return (F + kSliceF - 1) / kSliceF; }
 
@@ -108,14 +115,16 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
     } else {
         // activations and per-assignment outputs of the streaming kernels
         w.part = w.part_sh = o;
-        w.act = o;     o += align256(A * F * 2);
-        w.act_sh = o;  o += align256((size_t)n_shared * T * F_shared * 2);
+        // (4 bytes per element: the one-launch kernel stores (call number, two bf16 values) entries)
+        w.act = o;     o += align256(A * F * 4);
+        w.act_sh = o;  o += align256((size_t)n_shared * T * F_shared * 4);
         // (8 bytes per element: small batches store (call number, value) entries, see JoinArgs)
         w.o = o;       o += align256(A * H * 8);
         w.o_sh = o;    o += align256((size_t)n_shared * T * H * 8);
         if (use_fused_route(T, k, E, C, H, F, n_shared, F_shared)) {
             w.lists_pub = o;
-            o += align256((list_pub_entries(T, k, C) * kListReplicas + kMaxGroups) * 8);
+            // (..., one stamped word per workgroup of the launch, and the gate weights, stamped, kListReplicas copies)
+            o += align256((list_pub_entries(T, k, C) * kListReplicas + kMaxGroups + A * kListReplicas) * 8);
         }
     }
     w.total = o;
@@ -175,6 +184,25 @@ struct JoinArgs {
     int out_bf16, accumulate;
 };
 
+// Arguments of the one-launch kernel of small batches (layer.hip): gate/up and down as one weight stream,
+// the final sum at its end, optionally the routing steps at its head.
+struct LayerArgs {
+    const uint16_t *w_gate, *w_up, *w_down;      // slot-major pools
+    const uint16_t *sh_gate, *sh_up, *sh_down;   // shared experts or null
+    const uint16_t *hidden;                      // [T,H] bf16
+    unsigned long long *act, *act_sh;            // [A][F/2], [n_shared][T][F_sh/2]: call number << 32 | two bf16
+    unsigned long long *o, *o_sh;                // [A][H], [n_shared][T][H]: call number << 32 | fp32
+    const int32_t *slot_count, *slot_offset, *perm, *pos, *active_slots;   // lists left by a routing / list kernel
+    const unsigned *n_active;                    // (unused when the kernel does the routing itself)
+    const float *topk_w;                         // [T,k]
+    void *out;                                   // [T,H] fp32 or bf16
+    int32_t *miss_count;                         // [1] or null: set to -1 when a bounded wait ran out
+    unsigned *ctrl;                              // control block of the workspace
+    int T, k, H, F, F_sh, n_shared, C;
+    int KP_h, KP_f, KP_fs, tile_lds_bytes, tab_cap;   // (filled in by launch_layer)
+    int out_bf16, accumulate;
+};
+
 struct FfnArgs {
     const void *hidden;        // [T,H] bf16
     const void *w_gate, *w_up, *w_down;        // slot-major pools
@@ -210,10 +238,16 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join,
 hipError_t launch_stream_routed(const StreamArgs &a, const RouteArgs &r, hipStream_t s);
 bool stream_can_join(const StreamArgs &d);
 hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float *o_sh, hipStream_t s);
+// one-launch form (batches of up to 16 tokens): use_layer_kernel() must hold; route != null: the kernel does
+// the routing steps itself (use_fused_route() true, route->lists_pub set)
+bool use_layer_kernel(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared);
+hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t s);
+hipError_t read_layer_timeline(void *dst, size_t bytes);   // [kTimelineGroups][kLayerTimelineWords], tracing builds only
 // Timeline stamps of the last gate/up and down launches: [2][kTimelineGroups][kTimelineWords] 64-bit words
 // (start, lists in LDS, first tile done, loop done, results stored, end: 100 MHz ticks; items, tiles).
 // hipErrorNotSupported unless the library was built with -DMOE_STREAM_TRACE.
 constexpr int kTimelineGroups = 1024, kTimelineWords = 8;
+constexpr int kLayerTimelineWords = 24;   // the one-launch kernel's record per workgroup
 hipError_t read_stream_timeline(void *dst, size_t bytes);
 hipError_t launch_ffn(const FfnArgs &a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);

@@ -56,9 +56,10 @@ __device__ __forceinline__ unsigned wave_max_u32(unsigned x)
 // gate is exp(s - s_max) normalised over the k, summed in rank order.  Lane l owns experts l, l+64, ...;
 // the caller has put the logits into `lg` (LDS private to the wavefront: E floats, NaN replaced by -inf).
 // Lane j < k ends up with the j-th expert and writes it out.  Needs k <= E and all 64 lanes active.
+// Returns the gate weight of the lane's pick (lanes >= k: unspecified).
 template <int NLOC>
-__device__ __forceinline__ void wave_topk_gate_n(int E, int k, int32_t *idx_out_, lds_i32 *idx_lds,
-                                                 float *w_out_, lds_f32 *lg)
+__device__ __forceinline__ float wave_topk_gate_n(int E, int k, int32_t *idx_out_, lds_i32 *idx_lds,
+                                                  float *w_out_, lds_f32 *lg)
 {
     g_i32 *idx_out = (g_i32 *)(uintptr_t)idx_out_;
     g_f32 *w_out = (g_f32 *)(uintptr_t)w_out_;
@@ -106,11 +107,13 @@ __device__ __forceinline__ void wave_topk_gate_n(int E, int k, int32_t *idx_out_
     const float ex = lane < k ? __expf(my_s - smax) : 0.f;
     float den = 0.f;
     for (int j = 0; j < k; ++j) den += __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(ex), j));
+    const float gate = ex / den;
     if (lane < k) {
         if (idx_lds) idx_lds[lane] = my_e;
         idx_out[lane] = my_e;
-        w_out[lane] = ex / den;
+        w_out[lane] = gate;
     }
+    return gate;
 }
 
 __device__ __forceinline__ void wave_topk_gate(int E, int k, int32_t *idx_out, lds_i32 *idx_lds, float *w_out,

@@ -54,9 +54,11 @@ def upload(li: synth.LayerInputs) -> DeviceLayer:
         None if li.sh_down is None else dev_bf16(li.sh_down))
 
 
-def run_layer(d: DeviceLayer, buf: B.LayerBuffers | None = None, out_bf16=False, accumulate=False):
+def run_layer(d: DeviceLayer, buf: B.LayerBuffers | None = None, out_bf16=False, accumulate=False,
+              form: int = B.LAUNCH_AUTO):
+    """One moe_verify_layer call in the given launch form (a fresh workspace unless `buf` is given)."""
     buf = buf or B.LayerBuffers.allocate(d.shape, out_bf16=out_bf16)
-    B.moe_verify_layer(d.shape, d.hidden, d.router_w, d.router_bias, d.slot_table, d.w_gate, d.w_up, d.w_down,
+    B.moe_verify_layer(B.with_form(d.shape, form), d.hidden, d.router_w, d.router_bias, d.slot_table, d.w_gate, d.w_up, d.w_down,
                        d.sh_gate, d.sh_up, d.sh_down, buf.topk_idx, buf.topk_w, buf.hist, buf.slot_idx,
                        buf.miss_list, buf.miss_count, buf.out, out_bf16, accumulate, buf.workspace)
     torch.cuda.synchronize()

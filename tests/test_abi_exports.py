@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(lib):
 
 
 class Shape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "E", "k", "F", "C", "n_shared", "F_shared")]
+    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "E", "k", "F", "C", "n_shared", "F_shared", "launch_form")]
 
 
 def test_workspace_bytes_and_status_strings(lib):
@@ -83,11 +83,11 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
 def test_timeline_entry_point_of_the_product_build(lib):
     """The product library carries no timeline stamps: the entry point says so and writes nothing."""
     lib.moe_profile_stream_timeline.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
-    words = (ctypes.c_ulonglong * (2 * 1024 * 8))()
+    words = (ctypes.c_ulonglong * (2 * 1024 * 8 + 1024 * 24))()
     words[0] = 7
-    assert lib.moe_profile_stream_timeline(None, 2 * 1024 * 8) == -1
+    assert lib.moe_profile_stream_timeline(None, 2 * 1024 * 8 + 1024 * 24) == -1
     assert lib.moe_profile_stream_timeline(words, 5) == -2
-    assert lib.moe_profile_stream_timeline(words, 2 * 1024 * 8) == -2
+    assert lib.moe_profile_stream_timeline(words, 2 * 1024 * 8 + 1024 * 24) == -2
     assert words[0] == 7
 
 

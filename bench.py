@@ -169,6 +169,8 @@ def main():
     form = {"auto": B.LAUNCH_AUTO, "three": B.LAUNCH_THREE, "two": B.LAUNCH_TWO, "one": B.LAUNCH_ONE,
             "route+one": B.LAUNCH_ROUTE_PLUS_ONE}[args.form]
     call_shape = B.with_form(dev_layers[0].shape, form)
+    if os.environ.get("MOE_LAYER_WAVES"):
+        B._lib.moe_debug_layer_waves(int(os.environ["MOE_LAYER_WAVES"]))
 
     def step(i):
         d = dev_layers[i % len(dev_layers)]

@@ -56,7 +56,7 @@ def build_hip(force: bool = True, verbose: bool = False, trace: bool = False, jo
     if not (force or trace or stale()):
         return out_path
     os.makedirs(OBJ_DIR, exist_ok=True)
-    extra = ["-DMOE_STREAM_TRACE"] if trace else []
+    extra = ["-DMOE_STREAM_TRACE=1"] if trace else []
     newest_header = max(os.path.getmtime(h) for h in _headers())
     objs, todo = [], []
     for s in _sources():

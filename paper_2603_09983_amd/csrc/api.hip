@@ -130,6 +130,12 @@ extern "C" int moe_profile_stream_timeline(unsigned long long *words, size_t n_w
     return e == hipSuccess ? MOE_OK : launch_failed(e);
 }
 
+extern "C" int moe_debug_layer_waves(int wv)
+{
+    set_layer_waves(wv);
+    return MOE_OK;
+}
+
 extern "C" const char *moe_profile_kernel_name(int kind)
 {
     switch (kind) {

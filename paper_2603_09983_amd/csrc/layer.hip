@@ -42,9 +42,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef unsigned long long u64;
 
-constexpr int kThreads = 1024;
-constexpr int kWaves = 16;
-constexpr int kPieces = 4;     // 1 KB pieces per wavefront per tile (64 KB tile / 16 wavefronts)
+constexpr int kMaxWaves = 16;
 constexpr int kRowPad = kStreamRowPad;
 
 // (explicitly a pointer to global memory: an address that has been through an integer, as the tile addresses in
@@ -80,12 +78,23 @@ __device__ inline u64 load_entry(const u64 *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+#ifndef MOE_EXP
+#define MOE_EXP 0
+#endif
+// (timing experiments produce no results, so they take every entry as this call's)
+#define TAG_IS(x) (MOE_EXP ? true : (unsigned)((x) >> 32) == tag)
 #ifdef MOE_STREAM_TRACE
 __device__ unsigned long long g_layer_timeline[kTimelineGroups][kLayerTimelineWords];
 #define MOE_STAMP(var) var = wall_clock64()
-// (shader clock: what a wavefront spends in each part of a step, summed over the loop's steps)
+// (shader clock: what a wavefront spends in each part of a step, summed over the loop's steps; reading the
+// clock waits for the wavefront's LDS operations, so these probes are a build of their own: -DMOE_STREAM_TRACE=2)
+#if MOE_STREAM_TRACE > 1
 #define MOE_CYC_BEGIN() long long cyc_t = clock64()
 #define MOE_CYC(i) do { const long long cyc_n = clock64(); cyc_sum[i] += cyc_n - cyc_t; cyc_t = cyc_n; } while (0)
+#else
+#define MOE_CYC_BEGIN()
+#define MOE_CYC(i)
+#endif
 #else
 #define MOE_STAMP(var)
 #define MOE_CYC_BEGIN()
@@ -105,27 +114,35 @@ __device__ unsigned long long g_layer_timeline[kTimelineGroups][kLayerTimelineWo
 // memory, which class and panel it is, where its results go), and a step only reads two records, the one
 // of the tile it requests and the one of the tile it multiplies.
 constexpr int kTabWords = 8;            // words of a tile record
-constexpr int kRedStride = 1024 + 16;   // bytes between the partial results of two wavefronts in LDS
+constexpr int kRedStride = 2 * 1024 + 16;   // bytes between the partial results (two 16x16 blocks) of two wavefronts in LDS
 constexpr int kDumpBytes = 1024;        // where pieces that a tile does not have are parked
 
-template <int NPI, bool ROUTE>
-__global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs ra)
+// WV wavefronts per workgroup, NPI = 64 / WV 1 KB pieces per wavefront and tile.  What a step does apart from
+// moving data (reading the records, addresses, barriers, the reduction's bookkeeping) is done by every
+// wavefront, and sixteen of them issuing it are what bounds the step; fewer wavefronts with more pieces each
+// move the same bytes with less of it.
+template <int WV, int NPI, bool ROUTE>
+__global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs ra)
 {
+    constexpr int kWaves = WV, kThreads = WV * 64, kPieces = NPI;
+    static_assert(WV == 16 || WV == 8 || WV == 4, "four lanes, two or one per result element");
+    constexpr int LPE = WV / 4;   // lanes that share the reduction of one result element
     extern __shared__ __align__(16) unsigned char lds[];
     const int T = a.T, kk = a.k, H = a.H, F = a.F, Fs = a.F_sh, C = a.C, A = T * kk;
     unsigned char *tile_s = lds;
-    unsigned char *red_s = lds + a.tile_lds_bytes + kDumpBytes;        // [wavefront] 1 KB of partial results each
-    int *ctl_s = (int *)(red_s + 2 * kWaves * kRedStride + 1024);   // (two halves of partial results, 256 finished values)
+    unsigned char *red_s = lds + a.tile_lds_bytes + kDumpBytes;        // [wavefront] 2 KB of partial results each
+    int *ctl_s = (int *)(red_s + 2 * kWaves * kRedStride);   // (two halves of partial results)
     int *count_s = ctl_s, *offset_s = ctl_s + C, *active_s = ctl_s + 2 * C, *mask_s = ctl_s + 3 * C;
     int *perm_s = ctl_s + 4 * C;     // token of each entry of the per-slot lists
     int *pos_s = perm_s + A;         // row of each assignment's output, -1 = expert not resident
     int *misc_s = pos_s + A;         // [0] active slots, [1] a bounded wait of this workgroup ran out
     // per class: panels per item, items per expert, first item of this workgroup's share, contraction length,
     // panel width, rows per expert (constants of the launch, looked up on the rare paths)
+    // ... rows per item)
     int *cls_s = misc_s + 8;         // [4][8]
-    int *geo_s = cls_s + 32;         // [4][2]: tile row bytes, weight row bytes of the four tile layouts
-    u64 *clsp_s = (u64 *)(geo_s + 8);   // [4][2]: where the class's weights start (rows 0..7 and 8..15 of a tile)
-    uint32_t *tab_s = (uint32_t *)(ctl_s + ((4 * C + 2 * A + 8 + 32 + 8 + 16 + 3) & ~3));   // [tiles + 2][kTabWords]
+    int *geo_s = cls_s + 32;         // [6][4]: tile row bytes, weight row bytes, rows of the six tile layouts
+    u64 *clsp_s = (u64 *)(geo_s + 24);   // [4][2]: where the class's weights start (rows 0..7 and 8..15 of a gate/up tile)
+    uint32_t *tab_s = (uint32_t *)(ctl_s + ((4 * C + 2 * A + 8 + 32 + 24 + 16 + 3) & ~3));   // [tiles + 2][kTabWords]
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
 #ifdef MOE_STREAM_TRACE
@@ -148,11 +165,17 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         atomicOr(error_flag, 1u);
         misc_s[1] = 1;
     };
-    // a kilobyte that is always there and always cached: what a wavefront reads for a piece its tile does not have
-    g_bytes *const dummy = (g_bytes *)(uintptr_t)((const unsigned char *)a.ctrl + kCtrlBytes);
+    // a kilobyte that is always there and soon cached: what a wavefront reads for a piece its tile does not have
+    // (one of 512 places in the fixed region behind the control block, so that these reads do not all fall on
+    // the same cache lines of one memory channel)
+    g_bytes *const dummy = (g_bytes *)(uintptr_t)((const unsigned char *)a.ctrl + kCtrlBytes) + (size_t)((b * kWaves + w) & 511) * 1024;
 
-    const int tiles_g = F / 8, tiles_gs = a.n_shared ? Fs / 8 : 0, tiles_d = H / 16;
-    const int n_gs = a.n_shared * tiles_gs, n_ds = a.n_shared * tiles_d;
+    // A down item is RD rows (16..32: as many as make its tile about as large as a gate/up tile, so that two
+    // tiles in flight cover the memory latency in the down part too), the last item of an expert the rest.
+    const int RD = a.RD, RDS = a.n_shared ? a.RDS : 16;
+    const int tiles_g = F / 8, tiles_gs = a.n_shared ? Fs / 8 : 0;
+    const int tiles_d = (H + RD - 1) / RD, tiles_ds = (H + RDS - 1) / RDS;
+    const int n_gs = a.n_shared * tiles_gs, n_ds = a.n_shared * tiles_ds;
     const int np_h = H / a.KP_h, np_f = F / a.KP_f, np_fs = a.n_shared ? Fs / a.KP_fs : 1;
 
     // This workgroup's share of each class: items [sg_start, sg_start + sg_cnt) of the class's list.
@@ -173,12 +196,12 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
     int ntiles = nt0;
 
     // Record of tile j of this workgroup's list (by thread j):
-    //   words 0-1  address of tile rows 0..7 at the tile's panel (16-byte aligned; the two low bits say how the
-    //              tile is laid out: 0 gate/up, 1 down of a shared expert, 2 down of a routed expert, 3 no tile)
-    //   words 2-3  address of tile rows 8..15
+    //   words 0-1  address of the tile's first row at the tile's panel (16-byte aligned; the four low bits say
+    //              how the tile is laid out)
+    //   words 2-3  gate/up: address of tile rows 8..15 (the up rows)
     //   word 4     class | first panel << 2 | last panel << 3 | (panel | B operand's identity << 8) << 4
     //   word 5     first row of the item's results (list position of the expert's first token, or expert * T)
-    //   word 6     first column of the item's results
+    //   word 6     first column of the item's results | rows of the item << 16
     //   word 7     tokens of the expert | their bit mask << 8
     auto write_record = [&](int j, int nt1, int nt2) __attribute__((always_inline)) {
         int cls, r = j;
@@ -193,26 +216,29 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         const int e = idx / tl, rt = idx - e * tl;
         const bool shared = cls == 0 || cls == 2;
         const int c = shared ? e : active_s[e];
-        const int rpi = cls < 2 ? 8 : 16;   // weight rows of an item per matrix
+        const int rpi = cp[6];   // weight rows of an item per matrix (the last item of an expert may have fewer)
         const size_t eoff = ((size_t)c * rows + (size_t)rt * rpi) * K + (size_t)pan * KP;   // (elements)
         const u64 p0 = clsp_s[cls * 2] + 2 * eoff;
-        const u64 p1 = cls < 2 ? clsp_s[cls * 2 + 1] + 2 * eoff : p0 + (u64)16 * K;
+        const u64 p1 = cls < 2 ? clsp_s[cls * 2 + 1] + 2 * eoff : p0;
         const int key = cls < 2 ? 0 : cls == 2 ? 1 + e : 1 + a.n_shared + e;
         int row0 = e * T, mm = T | (((1 << T) - 1) << 8);
         if (!shared) {
             row0 = offset_s[c];
             mm = count_s[c] | (mask_s[c] << 8);
         }
+        const bool last_item = cls >= 2 && rt == tl - 1;
+        const int item_rows = last_item ? rows - rt * rpi : rpi;
+        const int gid = cls < 2 ? 0 : cls - 1 + (last_item ? 2 : 0);
         uint32_t *rec = tab_s + (size_t)j * kTabWords;
-        rec[0] = (uint32_t)p0 | (uint32_t)(cls < 2 ? 0 : cls - 1); rec[1] = (uint32_t)(p0 >> 32);
+        rec[0] = (uint32_t)p0 | (uint32_t)gid; rec[1] = (uint32_t)(p0 >> 32);
         rec[2] = (uint32_t)p1; rec[3] = (uint32_t)(p1 >> 32);
         rec[4] = (uint32_t)cls | (pan == 0 ? 4u : 0u) | (pan == npan - 1 ? 8u : 0u) | ((uint32_t)(pan | key << 8) << 4);
         rec[5] = (uint32_t)row0;
-        rec[6] = (uint32_t)(rt * rpi);
+        rec[6] = (uint32_t)(rt * rpi) | ((uint32_t)item_rows << 16);
         rec[7] = (uint32_t)mm;
     };
     auto write_end_records = [&](int nt) __attribute__((always_inline)) {   // two records behind the last tile: nothing to load
-        if (tid < 2 * kTabWords) tab_s[(size_t)nt * kTabWords + tid] = (tid & 7) == 0 ? 3u : 0u;
+        if (tid < 2 * kTabWords) tab_s[(size_t)nt * kTabWords + tid] = (tid & 7) == 0 ? 5u : 0u;
     };
 
     // Piece i of this wavefront covers bytes [(16i+w) KB, +1 KB) of a tile seen as 16 rows of rs bytes (rs a
@@ -227,24 +253,29 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
     int loff[2][NPI];
     int st_geo[2] = {-1, -1};
     unsigned st_hi[2] = {0, 0}, st_dm[2] = {0, 0};   // bit i: piece i lies in tile rows 8..15 | is no piece of the tile
-    auto geo_rs = [&](int gid) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(geo_s[gid * 2]); };
     auto set_geo = [&](int s, int gid) __attribute__((always_inline)) {
         st_geo[s] = gid;
-        const int rs = geo_rs(gid);
-        const int K2 = __builtin_amdgcn_readfirstlane(geo_s[gid * 2 + 1]);
-        const int np = rs / 64;
-        const float inv_d = rs ? 16.0f / (float)rs : 0.f;
+        const int rs = __builtin_amdgcn_readfirstlane(geo_s[gid * 4]);
+        const int K2 = __builtin_amdgcn_readfirstlane(geo_s[gid * 4 + 1]);
+        const int end = __builtin_amdgcn_readfirstlane(geo_s[gid * 4 + 2]) * rs;   // bytes of the tile
+        const int np = (end + 1023) >> 10;
+        const float inv_rs = rs ? 1.0f / (float)rs : 0.f;
         unsigned hi = 0, dm = 0;
 #pragma unroll
         for (int i = 0; i < NPI; ++i) {
             const int pc = i * kWaves + w;
             if (pc < np) {
                 const int off = (pc << 10) + (lane << 4);
-                const int row = (int)(((float)(off >> 4) + 0.5f) * inv_d);
-                const int col = off - row * rs;
-                goff[s][i] = (unsigned)((row & 7) * K2 + col);
-                loff[s][i] = row * (rs + kRowPad) + col;
-                if ((pc << 10) >= 8 * rs) hi |= 1u << i;
+                if (off < end) {
+                    int row = (int)(((float)off + 8.0f) * inv_rs);   // (off + 8 is never within 4 of a multiple of rs)
+                    const int col = off - row * rs;
+                    goff[s][i] = (unsigned)((gid == 0 ? row & 7 : row) * K2 + col);
+                    loff[s][i] = row * (rs + kRowPad) + col;
+                } else {   // a piece that straddles the tile's end: these lanes read the tile's last 16 bytes again
+                    goff[s][i] = (unsigned)((end / rs - 1) * K2 + rs - 16);
+                    loff[s][i] = a.tile_lds_bytes + (lane << 4);
+                }
+                if (gid == 0 && (pc << 10) >= 8 * rs) hi |= 1u << i;
             } else {
                 goff[s][i] = (unsigned)(lane << 4);
                 loff[s][i] = a.tile_lds_bytes + (lane << 4);
@@ -260,8 +291,8 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         const unsigned p0h = (unsigned)__builtin_amdgcn_readfirstlane((int)r.y);
         const unsigned p1l = (unsigned)__builtin_amdgcn_readfirstlane((int)r.z);
         const unsigned p1h = (unsigned)__builtin_amdgcn_readfirstlane((int)r.w);
-        const int gid = (int)(p0l & 3u);
-        p0l &= ~3u;
+        const int gid = (int)(p0l & 15u);
+        p0l &= ~15u;
         if (gid != st_geo[s]) set_geo(s, gid);
         g_bytes *p0 = (g_bytes *)(uintptr_t)((u64)p0h << 32 | p0l);
         g_bytes *p1 = (g_bytes *)(uintptr_t)((u64)p1h << 32 | p1l);
@@ -319,8 +350,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
             }
             for (int i = tid; i < C * ((T + 31) >> 5); i += kThreads) L.cnt_s[i] = 0;
             lds_f32 *lg = L.lg_s + w * lg_stride(E);
-            if (w < T) {
-                const int t = w;
+            for (int t = w; t < T; t += kWaves) {
                 const u64 *src = ra.tagged_logits + (size_t)t * E;
                 for (int e0 = 0; e0 < E; e0 += kWave) {
                     const int e = e0 + lane;
@@ -328,7 +358,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
                     int polls = 0;
                     for (;;) {
                         if (e < E) v = load_entry(src + e);
-                        if (__ballot((unsigned)(v >> 32) != tag) == 0ull) break;
+                        if (__ballot(!TAG_IS(v)) == 0ull) break;
                         if (++polls > spin) {
                             if (lane == 0) atomicOr(error_flag, 1u);
                             break;
@@ -368,26 +398,33 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         int *c0 = cls_s, *c1 = cls_s + 8, *c2 = cls_s + 16, *c3 = cls_s + 24;
         c0[0] = np_h; c0[1] = tiles_gs; c0[2] = sg_start0; c0[3] = H; c0[4] = a.KP_h; c0[5] = Fs;
         c1[0] = np_h; c1[1] = tiles_g; c1[2] = 0; c1[3] = H; c1[4] = a.KP_h; c1[5] = F;
-        c2[0] = np_fs; c2[1] = tiles_d; c2[2] = sg_start2; c2[3] = Fs; c2[4] = a.KP_fs; c2[5] = H;
-        c3[0] = np_f; c3[1] = tiles_d; c3[2] = 0; c3[3] = F; c3[4] = a.KP_f; c3[5] = H;
+        c2[0] = np_fs; c2[1] = tiles_ds; c2[2] = sg_start2; c2[3] = Fs; c2[4] = a.KP_fs; c2[5] = H; c2[6] = RDS;
+        c3[0] = np_f; c3[1] = tiles_d; c3[2] = 0; c3[3] = F; c3[4] = a.KP_f; c3[5] = H; c3[6] = RD;
+        c0[6] = 8; c1[6] = 8;
         clsp_s[0] = (u64)(uintptr_t)a.sh_gate; clsp_s[1] = (u64)(uintptr_t)a.sh_up;
         clsp_s[2] = (u64)(uintptr_t)a.w_gate; clsp_s[3] = (u64)(uintptr_t)a.w_up;
         clsp_s[4] = (u64)(uintptr_t)a.sh_down; clsp_s[5] = 0;
         clsp_s[6] = (u64)(uintptr_t)a.w_down; clsp_s[7] = 0;
-        geo_s[0] = 2 * a.KP_h; geo_s[1] = 2 * H;
-        geo_s[2] = 2 * a.KP_fs; geo_s[3] = 2 * Fs;
-        geo_s[4] = 2 * a.KP_f; geo_s[5] = 2 * F;
-        geo_s[6] = 0; geo_s[7] = 0;
+        // tile layouts: 0 gate/up | 1, 2 down of a shared, a routed expert | 3, 4 the same, last item of an
+        // expert (fewer rows) | 5 no tile
+        geo_s[0] = 2 * a.KP_h; geo_s[1] = 2 * H; geo_s[2] = 16;
+        geo_s[4] = 2 * a.KP_fs; geo_s[5] = 2 * Fs; geo_s[6] = RDS;
+        geo_s[8] = 2 * a.KP_f; geo_s[9] = 2 * F; geo_s[10] = RD;
+        geo_s[12] = 2 * a.KP_fs; geo_s[13] = 2 * Fs; geo_s[14] = H - (tiles_ds - 1) * RDS;
+        geo_s[16] = 2 * a.KP_f; geo_s[17] = 2 * F; geo_s[18] = H - (tiles_d - 1) * RD;
+        geo_s[20] = 0; geo_s[21] = 0; geo_s[22] = 0;
     }
 
     u32x4 bx[kPieces];
     unsigned bx_sig = 0xffffffffu;   // panel | identity << 8 of the B operand that the registers hold
     int c_geo = -1, c_rs = 128;
+    bool c_two = false;              // the parked tile has more than 16 rows: two blocks of 16 MFMA rows
     unsigned avalid = 0;             // bit j: this wavefront's j-th column block exists in the parked tile
     int aoff[kPieces];
     auto set_cgeo = [&](int gid) __attribute__((always_inline)) {
         c_geo = gid;
-        c_rs = geo_rs(gid);
+        c_rs = __builtin_amdgcn_readfirstlane(geo_s[gid * 4]);
+        c_two = __builtin_amdgcn_readfirstlane(geo_s[gid * 4 + 2]) > 16;
         const int nkb = c_rs / 64;
         avalid = 0;
 #pragma unroll
@@ -429,8 +466,8 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
                     if (((avalid >> j) & 1u) && valid) {
                         const u64 *p = base + kb * 16;
                         const u64 e0 = load_entry(p), e1 = load_entry(p + 1), e2 = load_entry(p + 2), e3 = load_entry(p + 3);
-                        ok = ok && (unsigned)(e0 >> 32) == tag && (unsigned)(e1 >> 32) == tag &&
-                             (unsigned)(e2 >> 32) == tag && (unsigned)(e3 >> 32) == tag;
+                        ok = ok && TAG_IS(e0) && TAG_IS(e1) &&
+                             TAG_IS(e2) && TAG_IS(e3);
                         bx[j] = (u32x4){(unsigned)e0, (unsigned)e1, (unsigned)e2, (unsigned)e3};
                     }
                 }
@@ -477,7 +514,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         const u64 *pub = ra.lists_pub + (size_t)(b % kListReplicas) * n_pub;
         if (tid == 0 && b != 0) {
             int polls = 0;
-            while ((unsigned)(load_entry(pub) >> 32) != tag) {
+            while (!TAG_IS(load_entry(pub))) {
                 if (++polls > spin) break;   // (the loop below reports it)
                 __builtin_amdgcn_s_sleep(16);
             }
@@ -489,7 +526,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
             int polls = 0;
             for (;;) {
                 v = load_entry(pub + i);
-                if ((unsigned)(v >> 32) == tag) break;
+                if (TAG_IS(v)) break;
                 if (++polls > spin) {
                     give_up();
                     v = 0;   // (stay inside every array below)
@@ -591,7 +628,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
                 int polls = 0;
                 for (;;) {
                     x = load_entry(gw_pub + i);
-                    if ((unsigned)(x >> 32) == tag) break;
+                    if (TAG_IS(x)) break;
                     if (++polls > spin) {
                         give_up();
                         break;
@@ -620,7 +657,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
                     int polls = 0;
                     for (;;) {
                         x = load_entry(p);
-                        if ((unsigned)(x >> 32) == tag) break;
+                        if (TAG_IS(x)) break;
                         if (++polls > spin) {   // cannot happen with the whole grid resident
                             give_up();
                             break;
@@ -659,7 +696,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
             const u64 *seen = ra.lists_pub + (size_t)kListReplicas * n_pub;
             for (int i = tid; i < G; i += kThreads) {
                 int polls = 0;
-                while ((unsigned)(load_entry(seen + i) >> 32) != tag) {
+                while (!TAG_IS(load_entry(seen + i))) {
                     if (++polls > spin) {
                         atomicOr(error_flag, 1u);
                         break;
@@ -686,7 +723,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         issue(1, 1);
     }
 
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // tile rows 0..15 and 16..31
 
     auto multiply = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -694,32 +731,40 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
             if ((avalid >> j) & 1u) {
                 u32x4 av = *(const u32x4 *)(tile_s + aoff[j]);
                 acc = mfma(av, bx[j], acc);
+                if (c_two) {
+                    // (rows beyond the item's last one hold whatever the buffer held: their results are not stored)
+                    u32x4 av1 = *(const u32x4 *)(tile_s + aoff[j] + 16 * (c_rs + kRowPad));
+                    acc1 = mfma(av1, bx[j], acc1);
+                }
             }
         }
     };
     // Results leave in three stages, one step apart, so that nothing of it sits between the parking of a tile and
-    // the request for the next one except a handful of store instructions in four wavefronts:
+    // the request for the next one except one store instruction:
     //   post    (step t, behind the multiplication) every wavefront puts its partial 16x16 result into red_s;
     //   reduce  (step t+1, behind the multiplication) all wavefronts add the sixteen partial results: element
     //           q = lane*4 + j of the MFMA result layout is column (q/4)%16, tile row 4*(q/64) + q%4; wavefront r
     //           takes elements 16r..16r+15, four lanes per element, each lane four partial results, then the four
     //           lanes add up (fixed order: the result does not depend on scheduling).  Gate rows are tile rows
     //           0..7 (elements 0..127) and the up row of the same activation sits 128 elements further on.  The
-    //           finished values (SiLU(gate) * up, or the down projection's sums) go to out_s;
-    //   store   (step t+2, between the parking and the request) wavefronts 12-15 send them to memory as stamped
-    //           entries.  A store placed there is older than every load that a later wait must leave in flight,
-    //           so whether a wavefront stored or not, no wait for a tile ever covers a younger tile (the memory
-    //           counter counts loads and stores in order).
+    //           lane that holds a finished value (SiLU(gate) * up, or the down projection's sum) also works out
+    //           where it goes and keeps address and value in registers;
+    //   store   (step t+2, between the parking and the request) that lane sends it to memory as a stamped entry.
+    //           A store placed there is older than every load that a later wait must leave in flight, so
+    //           whether a wavefront stored or not, no wait for a tile ever covers a younger tile (the memory
+    //           counter counts loads and stores in order); and it delays the request by one instruction only.
     // red_s has two halves used in turn, because a reduction reads one while the next item is posted.
-    float *out_s = (float *)(red_s + 2 * kWaves * kRedStride);   // [256] finished values of one item
     int post_half = 0;
     bool red_pending = false, st_pending = false;
     int rd_cls = 0, rd_row0 = 0, rd_col = 0, rd_mm = 0, rd_half = 0;   // the item posted last
-    int sd_cls = 0, sd_row0 = 0, sd_col = 0, sd_mm = 0;                // the item reduced last
-    auto quad_sum = [&](float v) __attribute__((always_inline)) {
+    bool rd_two = false;
+    u64 *sv_dst = nullptr;   // where this lane's finished value goes (null: it has none)
+    unsigned sv_val = 0, sv_val1 = 0;   // ... and the one 16 rows further on
+    bool sv_one = false, sv_two = false;
+    auto lanes_sum = [&](float v) __attribute__((always_inline)) {   // over the LPE neighbouring lanes of an element
         // (data-parallel-primitive control quad_perm: each lane reads lane 1,0,3,2, then 2,3,0,1, of its group of four)
-        v += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0xb1, 0xf, 0xf, false));
-        v += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0x4e, 0xf, 0xf, false));
+        if (LPE >= 2) v += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0xb1, 0xf, 0xf, false));
+        if (LPE >= 4) v += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0x4e, 0xf, 0xf, false));
         return v;
     };
     auto partial4 = [&](const unsigned char *half, int q, int pg) __attribute__((always_inline)) {   // partial results 4pg..4pg+3 of element q
@@ -729,60 +774,59 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         return (x0 + x1) + (x2 + x3);
     };
     auto reduce = [&]() __attribute__((always_inline)) {
-        const int ql = lane >> 2, pg = lane & 3;
-        const int q = w * 16 + ql;
+        const int pg = lane % LPE;
+        const int q = w * (kWave / LPE) + lane / LPE;   // (the wavefronts cover the 256 elements of a 16x16 block)
         const unsigned char *half = red_s + rd_half * (kWaves * kRedStride);
+        const int m = rd_mm & 0xff, mask = rd_mm >> 8;
+        const int col = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3);   // (gate/up: q < 128, rows 0..7)
+        const int first_col = rd_col & 0xffff, item_rows = rd_col >> 16;
+        sv_one = sv_two = false;
         if (rd_cls < 2) {
-            if (w < 8) {
-                const float s0 = quad_sum(partial4(half, q, pg)), s1 = quad_sum(partial4(half, q + 128, pg));
+            if (q < 128) {   // (uniform over the wavefront)
+                const float s0 = lanes_sum(partial4(half, q, pg)), s1 = lanes_sum(partial4(half, q + 128, pg));
                 // SiLU(s0) * s1 = s0 / (1 + 2^(-s0 log2 e)) * s1 (hardware exponential and reciprocal: the result is
                 // rounded to bf16 anyway)
                 const float v = s0 * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * s0)) * s1;
-                if (pg == 0) out_s[q] = v;
+                const float vn = __shfl_down(v, LPE, kWave);   // activation row + 1 of the same token (element q + 1)
+                // one 64-bit entry per (token, pair of activations); column `col` is token `col`, and the entry
+                // of the expert's list that this token is = the number of the expert's tokens below it
+                if (pg == 0 && (q & 1) == 0 && ((mask >> col) & 1)) {
+                    const int li = __popc((unsigned)mask & ((1u << col) - 1u));
+                    sv_dst = (rd_cls == 0 ? a.act_sh : a.act) +
+                             (size_t)(rd_row0 + li) * ((rd_cls == 0 ? Fs : F) / 2) + ((first_col + row) >> 1);
+                    sv_val = f32_to_bf16_rne(v) | (f32_to_bf16_rne(vn) << 16);
+                    sv_one = true;
+                }
             }
         } else {
-            const float s0 = quad_sum(partial4(half, q, pg));
-            if (pg == 0) out_s[q] = s0;
+            const float s0 = lanes_sum(partial4(half, q, pg));
+            float s1 = 0.f;
+            if (rd_two) s1 = lanes_sum(partial4(half + 1024, q, pg));
+            if (pg == 0 && col < m) {   // (column `col` is entry `col` of the expert's list)
+                sv_dst = (rd_cls == 2 ? a.o_sh : a.o) + (size_t)(rd_row0 + col) * H + (first_col + row);
+                sv_val = __float_as_uint(s0);
+                sv_val1 = __float_as_uint(s1);
+                sv_one = row < item_rows;
+                sv_two = rd_two && row + 16 < item_rows;
+            }
         }
-        sd_cls = rd_cls; sd_row0 = rd_row0; sd_col = rd_col; sd_mm = rd_mm;
         st_pending = true;
         red_pending = false;
     };
     auto store_results = [&]() __attribute__((always_inline)) {
-        if (w >= 12) {
-            const int m = sd_mm & 0xff, mask = sd_mm >> 8;
-            if (sd_cls < 2) {
-                if (w == 12) {
-                    // one 64-bit entry per (token, pair of activations): lane = token * 4 + pair
-                    const int tok = lane >> 2, pr = lane & 3;
-                    // element of (token, row): ((row / 4) * 16 + token) * 4 + row % 4, rows 2 pr and 2 pr + 1
-                    const int q = (((pr >> 1) * 16 + tok) << 2) + ((pr & 1) << 1);
-                    if ((mask >> tok) & 1) {
-                        // entry of the expert's list that token `tok` is: the number of its tokens below it
-                        const int li = __popc((unsigned)mask & ((1u << tok) - 1u));
-                        u64 *dst = (sd_cls == 0 ? a.act_sh : a.act) +
-                                   (size_t)(sd_row0 + li) * ((sd_cls == 0 ? Fs : F) / 2) + ((sd_col >> 1) + pr);
-                        store_entry(dst, wtag, f32_to_bf16_rne(out_s[q]) | (f32_to_bf16_rne(out_s[q + 1]) << 16));
-                    }
-                }
-            } else {
-                const int q = (w - 12) * 64 + lane;
-                const int ent = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3);
-                if (ent < m) {
-                    u64 *dst = (sd_cls == 2 ? a.o_sh : a.o) + (size_t)(sd_row0 + ent) * H + (sd_col + row);
-                    store_entry(dst, wtag, __float_as_uint(out_s[q]));
-                }
-            }
-        }
+#if !(MOE_EXP & 8)
+        if (sv_one) store_entry(sv_dst, wtag, sv_val);
+        if (sv_two) store_entry(sv_dst + 16, wtag, sv_val1);
+#else
+        asm volatile("" :: "v"(sv_dst), "v"(sv_val), "v"(sv_val1), "v"(sv_one), "v"(sv_two));
+#endif
         st_pending = false;
     };
     // everything this workgroup still holds back, out to memory (all wavefronts together: rare paths only)
     auto drain_results = [&]() __attribute__((always_inline)) {
         if (st_pending) store_results();
         if (red_pending) {
-            __syncthreads();
             reduce();
-            __syncthreads();
             store_results();
         }
     };
@@ -795,14 +839,21 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         const u32x4 d = *(const u32x4 *)(tab_s + (size_t)ti * kTabWords + 4);
         const unsigned fl = (unsigned)__builtin_amdgcn_readfirstlane((int)d.x);
         MOE_CYC(7);
-#ifdef MOE_STREAM_TRACE
+#if defined(MOE_STREAM_TRACE) && MOE_STREAM_TRACE > 1
         // (the wait for the tile alone: one register of its last piece is touched before the parking starts)
         asm volatile("" :: "v"(st[s][NPI - 1]));
 #endif
         MOE_CYC(0);
+#if !(MOE_EXP & 4)
         park(s);
+#else
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) asm volatile("" :: "v"(st[s][i]));   // (the loads stay; nothing is written to LDS)
+#endif
         MOE_CYC(1);
+#if !(MOE_EXP & 1)
         if (st_pending) store_results();
+#endif
         if ((fl >> 4) != bx_sig) {
             // (first everything out that this workgroup still holds back: it may be what it, or a workgroup
             // that it waits for, waits for)
@@ -817,11 +868,20 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
         MOE_CYC(3);
         __syncthreads();
         MOE_CYC(4);
-        if (fl & 4u) acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (fl & 4u) {
+            acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+            acc1 = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+#if !(MOE_EXP & 2)
         multiply();
+#endif
+#if !(MOE_EXP & 1)
         if (red_pending) reduce();   // (the item posted in the last step, or earlier)
+#endif
         if (fl & 8u) {
             *(f32x4 *)(red_s + post_half * (kWaves * kRedStride) + w * kRedStride + lane * 16) = acc;
+            if (c_two) *(f32x4 *)(red_s + post_half * (kWaves * kRedStride) + w * kRedStride + 1024 + lane * 16) = acc1;
+            rd_two = c_two;
             red_pending = true;
             rd_half = post_half;
             post_half ^= 1;
@@ -839,14 +899,16 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(LayerArgs a, RouteArgs 
 #endif
     };
 
-    // (tiles alternate between the two register sets, so the loop body is two steps; leaving it between them
-    // does not come back, so the loop is always entered and re-entered with the same loads in flight and each
-    // park waits for its own tile only)
-    for (int t = 0; t < ntiles; t += 2) {
-        step(0, t);
-        if (t + 1 >= ntiles) break;
-        step(1, t + 1);
+    // (tiles alternate between the two register sets, so the loop body is two steps; the first tile is peeled
+    // off so that the loop is always entered in the same state: the compiler then counts the loads in flight
+    // exactly and each park waits for its own tile only)
+    step(0, 0);
+    int t = 1;
+    for (; t + 1 < ntiles; t += 2) {
+        step(1, t);
+        step(0, t + 1);
     }
+    if (t < ntiles) step(1, t);
     drain_results();
     MOE_STAMP(tl_loop);
     __syncthreads();   // (the last reduction has read red_s, which the join reuses)
@@ -871,6 +933,7 @@ struct DevInfo {
 };
 DevInfo g_dev[kMaxDevices];
 std::mutex g_dev_mutex;
+int g_layer_waves = 0;
 
 }  // namespace
 
@@ -897,32 +960,60 @@ int device_cus(hipError_t *err)
     return n;
 }
 
-int max_panel(int H, int F, int n_shared, int F_shared)
+// rows of a down item whose panel is KP columns wide: as many as fit 64 pieces of 1 KB, 16..32
+int down_rows(int KP)
 {
-    const int kp_h = stream_panel_width(H), kp_f = stream_panel_width(F);
-    const int kp_s = n_shared > 0 ? stream_panel_width(F_shared) : 0;
-    int kp = kp_h > kp_f ? kp_h : kp_f;
-    return kp > kp_s ? kp : kp_s;
+    int r = 65536 / (2 * KP);
+    return r < 16 ? 16 : r > 32 ? 32 : r;
+}
+
+struct LayerGeom {
+    int KP_h, KP_f, KP_fs, RD, RDS, tile_bytes, npi;
+};
+
+LayerGeom layer_geom(int H, int F, int n_shared, int F_shared)
+{
+    LayerGeom g;
+    g.KP_h = stream_panel_width(H);
+    g.KP_f = stream_panel_width(F);
+    g.KP_fs = n_shared > 0 ? stream_panel_width(F_shared) : 0;
+    g.RD = down_rows(g.KP_f);
+    g.RDS = n_shared > 0 ? down_rows(g.KP_fs) : 16;
+    int tile = 16 * (2 * g.KP_h + kRowPad), pieces = 16 * 2 * g.KP_h / 1024;
+    const int t_d = g.RD * (2 * g.KP_f + kRowPad), p_d = (g.RD * 2 * g.KP_f + 1023) / 1024;
+    tile = tile > t_d ? tile : t_d;
+    pieces = pieces > p_d ? pieces : p_d;
+    if (n_shared > 0) {
+        const int t_s = g.RDS * (2 * g.KP_fs + kRowPad), p_s = (g.RDS * 2 * g.KP_fs + 1023) / 1024;
+        tile = tile > t_s ? tile : t_s;
+        pieces = pieces > p_s ? pieces : p_s;
+    }
+    g.tile_bytes = (tile + 15) & ~15;
+    g.npi = (pieces + 15) / 16;   // (at sixteen wavefronts)
+    return g;
 }
 
 // upper bound of the tiles in one workgroup's list when G workgroups share the layer
 int layer_tab_cap(int T, int C, int H, int F, int n_shared, int F_shared, int G)
 {
-    const int np_h = H / stream_panel_width(H), np_f = F / stream_panel_width(F);
-    const int np_fs = n_shared > 0 ? F_shared / stream_panel_width(F_shared) : 1;
-    const long long n_gs = (long long)n_shared * (n_shared > 0 ? F_shared / 8 : 0), n_ds = (long long)n_shared * (H / 16);
+    const LayerGeom g = layer_geom(H, F, n_shared, F_shared);
+    const int np_h = H / g.KP_h, np_f = F / g.KP_f;
+    const int np_fs = n_shared > 0 ? F_shared / g.KP_fs : 1;
+    const long long n_gs = (long long)n_shared * (n_shared > 0 ? F_shared / 8 : 0);
+    const long long n_ds = (long long)n_shared * ((H + g.RDS - 1) / g.RDS);
     const long long t0 = (n_gs / G + 1) * np_h;
     const long long t1 = ((n_gs + (long long)C * (F / 8) + 2) / G + 1) * np_h;
     const long long t2 = (n_ds / G + 1) * np_fs;
-    const long long t3 = ((n_ds * np_fs + (long long)C * (H / 16) * np_f) / G / np_f + 2) * np_f;
+    const long long t3 = ((n_ds * np_fs + (long long)C * ((H + g.RD - 1) / g.RD) * np_f) / G / np_f + 2) * np_f;
     const long long cap = t0 + t1 + t2 + t3 + 4;
     return cap > (1 << 20) ? (1 << 20) : (int)cap;
 }
 
 size_t layer_lds_bytes(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared, bool route, int tab_cap)
 {
-    const size_t tile = (size_t)16 * (2 * (size_t)max_panel(H, F, n_shared, F_shared) + kStreamRowPad);
-    size_t need = tile + kDumpBytes + (size_t)2 * kWaves * kRedStride + 1024 + (((size_t)4 * C + 2 * (size_t)T * k + 8 + 32 + 8 + 16 + 3) & ~(size_t)3) * 4 +
+    const LayerGeom g = layer_geom(H, F, n_shared, F_shared);
+    size_t need = (size_t)g.tile_bytes + kDumpBytes + (size_t)2 * kMaxWaves * kRedStride +
+                  (((size_t)4 * C + 2 * (size_t)T * k + 8 + 32 + 24 + 16 + 3) & ~(size_t)3) * 4 +
                   ((size_t)tab_cap + 2) * kTabWords * 4;
     if (route) {
         const size_t r = post_lds_bytes(E, C, T * k, true);
@@ -937,8 +1028,9 @@ bool use_layer_kernel(int T, int k, int E, int C, int H, int F, int n_shared, in
 {
     if (T > 16 || C < 1 || C > kMaxC || H % 64 != 0 || F % 64 != 0 || (n_shared > 0 && F_shared % 64 != 0)) return false;
     if (!use_stream_kernels(T, k, C, H, F, n_shared, F_shared)) return false;
-    const size_t tile = (size_t)16 * (2 * (size_t)max_panel(H, F, n_shared, F_shared) + kStreamRowPad);
-    if ((size_t)T * 8 * (k + n_shared) * 4 > tile) return false;   // the strip of the final sum sits in the tile buffer
+    const LayerGeom g = layer_geom(H, F, n_shared, F_shared);
+    if (g.npi > 4) return false;
+    if ((size_t)T * 8 * (k + n_shared) * 4 > (size_t)g.tile_bytes) return false;   // the strip of the final sum sits in the tile buffer
     const int G = device_cus(nullptr);
     if (G <= 0) return false;
     const int cap = layer_tab_cap(T, C, H, F, n_shared, F_shared, G);
@@ -950,31 +1042,36 @@ hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t 
     hipError_t e = hipSuccess;
     const int grid = device_cus(&e);
     if (e != hipSuccess) return e;
+    const LayerGeom g = layer_geom(a.H, a.F, a.n_shared, a.F_sh);
     LayerArgs args = a;
-    args.KP_h = stream_panel_width(a.H);
-    args.KP_f = stream_panel_width(a.F);
-    args.KP_fs = a.n_shared > 0 ? stream_panel_width(a.F_sh) : 0;
-    const int kp = max_panel(a.H, a.F, a.n_shared, a.F_sh);
-    args.tile_lds_bytes = 16 * (2 * kp + kRowPad);
+    args.KP_h = g.KP_h;
+    args.KP_f = g.KP_f;
+    args.KP_fs = g.KP_fs;
+    args.RD = g.RD;
+    args.RDS = g.RDS;
+    args.tile_lds_bytes = g.tile_bytes;
     args.tab_cap = layer_tab_cap(a.T, a.C, a.H, a.F, a.n_shared, a.F_sh, grid);
     const int E = route ? route->E : 0;
     const size_t lds = layer_lds_bytes(a.T, a.k, E, a.C, a.H, a.F, a.n_shared, a.F_sh, route != nullptr, args.tab_cap);
-    if (lds > (size_t)kLdsBytes) return hipErrorInvalidValue;
+    if (lds > (size_t)kLdsBytes || g.npi > 4) return hipErrorInvalidValue;
     if (route && (!route->lists_pub || E > 2 * kWave)) return hipErrorInvalidValue;
-    const int npi = (kp / 32 + kWaves - 1) / kWaves;   // 1..4 pieces per wavefront and tile
-    static const void *const fns[2][4] = {
-        {(const void *)layer_kernel<1, false>, (const void *)layer_kernel<2, false>, (const void *)layer_kernel<3, false>,
-         (const void *)layer_kernel<4, false>},
-        {(const void *)layer_kernel<1, true>, (const void *)layer_kernel<2, true>, (const void *)layer_kernel<3, true>,
-         (const void *)layer_kernel<4, true>}};
-    const void *fn = fns[route ? 1 : 0][npi - 1];
+    // wavefronts per workgroup: 8 unless the routing steps inside the launch need a thread per assignment, slot
+    // or expert beyond 512 (g_layer_waves: a setting for experiments, 0 = this rule)
+    int wv = g_layer_waves ? g_layer_waves : 8;
+    if (route && (a.T * a.k > 64 * wv || a.C > 64 * wv || E > 64 * wv)) wv = 16;
+    static const void *const fns[3][2] = {
+        {(const void *)layer_kernel<16, 4, false>, (const void *)layer_kernel<16, 4, true>},
+        {(const void *)layer_kernel<8, 8, false>, (const void *)layer_kernel<8, 8, true>},
+        {(const void *)layer_kernel<4, 16, false>, (const void *)layer_kernel<4, 16, true>}};
+    const int wi = wv == 16 ? 0 : wv == 8 ? 1 : 2;
+    const void *fn = fns[wi][route ? 1 : 0];
     {
         int dev = 0;
         e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
         std::lock_guard<std::mutex> lock(g_dev_mutex);
         DevInfo &d = g_dev[dev];
-        const int which = (route ? 4 : 0) + npi - 1;
+        const int which = wi * 2 + (route ? 1 : 0);
         if (!d.attr_done[which]) {
             e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
             if (e != hipSuccess) return e;
@@ -984,10 +1081,12 @@ hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t 
     RouteArgs rargs = {};
     if (route) rargs = *route;
     void *params[] = {&args, &rargs};
-    hipError_t le = launch_timed(fn, dim3(grid), dim3(kThreads), params, lds, s, kKindLayer);
+    hipError_t le = launch_timed(fn, dim3(grid), dim3(64 * wv), params, lds, s, kKindLayer);
     if (le != hipSuccess) return le;
     return hipGetLastError();
 }
+
+void set_layer_waves(int wv) { g_layer_waves = (wv == 16 || wv == 8 || wv == 4) ? wv : 0; }
 
 hipError_t read_layer_timeline(void *dst, size_t bytes)
 {

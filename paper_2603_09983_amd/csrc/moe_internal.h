@@ -199,7 +199,7 @@ struct LayerArgs {
     int32_t *miss_count;                         // [1] or null: set to -1 when a bounded wait ran out
     unsigned *ctrl;                              // control block of the workspace
     int T, k, H, F, F_sh, n_shared, C;
-    int KP_h, KP_f, KP_fs, tile_lds_bytes, tab_cap;   // (filled in by launch_layer)
+    int KP_h, KP_f, KP_fs, RD, RDS, tile_lds_bytes, tab_cap;   // (filled in by launch_layer)
     int out_bf16, accumulate;
 };
 
@@ -242,6 +242,7 @@ hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float
 // the routing steps itself (use_fused_route() true, route->lists_pub set)
 bool use_layer_kernel(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared);
 hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t s);
+void set_layer_waves(int wv);   // experiments: wavefronts per workgroup of the one-launch kernel (0 = the default)
 hipError_t read_layer_timeline(void *dst, size_t bytes);   // [kTimelineGroups][kLayerTimelineWords], tracing builds only
 // Timeline stamps of the last gate/up and down launches: [2][kTimelineGroups][kTimelineWords] 64-bit words
 // (start, lists in LDS, first tile done, loop done, results stored, end: 100 MHz ticks; items, tiles).

@@ -286,7 +286,7 @@ constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before work
 // kListReplicas copies behind r.lists_pub (entries no expert fills are stamped too, with -1, so that a
 // reader can wait for all of them).
 template <bool PUBLISH>
-__device__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, int E, int C, const RouteArgs &r,
+__device__ __forceinline__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, int E, int C, const RouteArgs &r,
                                  lds_i32 *hist_s, lds_i32 *mask_s, lds_i32 *scan_s, lds_i32 *off_s, unsigned tag)
 {
     auto publish = [&](int word, int value) {

@@ -115,23 +115,27 @@ __device__ unsigned long long g_layer_timeline[kTimelineGroups][kLayerTimelineWo
 // of the tile it requests and the one of the tile it multiplies.
 constexpr int kTabWords = 8;            // words of a tile record
 constexpr int kRedStride = 2 * 1024 + 16;   // bytes between the partial results (two 16x16 blocks) of two wavefronts in LDS
-constexpr int kDumpBytes = 1024;        // where pieces that a tile does not have are parked
+constexpr int kDumpBytes = 2048;        // one KB where pieces that a tile does not have are parked, one KB of zeros
 
-// WV wavefronts per workgroup, NPI = 64 / WV 1 KB pieces per wavefront and tile.  What a step does apart from
-// moving data (reading the records, addresses, barriers, the reduction's bookkeeping) is done by every
-// wavefront, and sixteen of them issuing it are what bounds the step; fewer wavefronts with more pieces each
-// move the same bytes with less of it.
-template <int WV, int NPI, bool ROUTE>
-__global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs ra)
+// A workgroup is seven wavefronts that stream (NPI = 10 one-kilobyte pieces of a tile each: 70 places for the
+// 64 pieces of a full tile) and an eighth that only looks after results: it adds up the partial results that
+// the seven post, applies SiLU * up, and stores the finished values as stamped entries.  Stores and loads of
+// one wavefront share one in-order counter, so a store between two tile requests makes the next wait for a
+// tile a wait for the store's acknowledgement from memory as well (measured: 0.3 us per step); the eighth
+// wavefront has no tile loads, so its stores hold nothing back, and the seven never store inside the loop.
+// (Fewer streaming wavefronts with more pieces each move the bytes as fast as sixteen with four, and whatever
+// a step does besides moving data is issued less often; eight wavefronts in all leave each 256 registers.)
+template <int NPI, bool ROUTE>
+__global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
 {
-    constexpr int kWaves = WV, kThreads = WV * 64, kPieces = NPI;
-    static_assert(WV == 16 || WV == 8 || WV == 4, "four lanes, two or one per result element");
-    constexpr int LPE = WV / 4;   // lanes that share the reduction of one result element
+    constexpr int kWaves = 7, kAllWaves = 8, kThreads = kAllWaves * 64, kPieces = NPI;
+    static_assert(NPI * kWaves >= 64, "a full tile is 64 pieces");
     extern __shared__ __align__(16) unsigned char lds[];
     const int T = a.T, kk = a.k, H = a.H, F = a.F, Fs = a.F_sh, C = a.C, A = T * kk;
     unsigned char *tile_s = lds;
     unsigned char *red_s = lds + a.tile_lds_bytes + kDumpBytes;        // [wavefront] 2 KB of partial results each
     int *ctl_s = (int *)(red_s + 2 * kWaves * kRedStride);   // (two halves of partial results)
+    static_assert((2 * kWaves * kRedStride) % 16 == 0, "the arrays behind stay 16-byte aligned");
     int *count_s = ctl_s, *offset_s = ctl_s + C, *active_s = ctl_s + 2 * C, *mask_s = ctl_s + 3 * C;
     int *perm_s = ctl_s + 4 * C;     // token of each entry of the per-slot lists
     int *pos_s = perm_s + A;         // row of each assignment's output, -1 = expert not resident
@@ -151,6 +155,7 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
 #endif
     MOE_STAMP(tl_start);
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wavefront id, known to be uniform
+    const bool helper = w == kWaves;   // the wavefront that reduces and stores
     const int n = lane & 15, g = lane >> 4;
     const int G = gridDim.x, b = blockIdx.x;
 
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
     //   words 2-3  gate/up: address of tile rows 8..15 (the up rows)
     //   word 4     class | first panel << 2 | last panel << 3 | (panel | B operand's identity << 8) << 4
     //   word 5     first row of the item's results (list position of the expert's first token, or expert * T)
-    //   word 6     first column of the item's results | rows of the item << 16
+    //   word 6     first column of the item's results | rows of the item << 16 | the tile's layout << 24
     //   word 7     tokens of the expert | their bit mask << 8
     auto write_record = [&](int j, int nt1, int nt2) __attribute__((always_inline)) {
         int cls, r = j;
@@ -234,7 +239,7 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
         rec[2] = (uint32_t)p1; rec[3] = (uint32_t)(p1 >> 32);
         rec[4] = (uint32_t)cls | (pan == 0 ? 4u : 0u) | (pan == npan - 1 ? 8u : 0u) | ((uint32_t)(pan | key << 8) << 4);
         rec[5] = (uint32_t)row0;
-        rec[6] = (uint32_t)(rt * rpi) | ((uint32_t)item_rows << 16);
+        rec[6] = (uint32_t)(rt * rpi) | ((uint32_t)item_rows << 16) | ((uint32_t)gid << 24);
         rec[7] = (uint32_t)mm;
     };
     auto write_end_records = [&](int nt) __attribute__((always_inline)) {   // two records behind the last tile: nothing to load
@@ -249,41 +254,53 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
     // first row and its LDS byte offset; both depend only on how the tile is laid out and are worked out again
     // when that changes (three times per launch).  Two tiles are in flight per wavefront (st[0], st[1]).
     u32x4 st[2][NPI];
-    unsigned goff[2][NPI];
-    int loff[2][NPI];
-    int st_geo[2] = {-1, -1};
-    unsigned st_hi[2] = {0, 0}, st_dm[2] = {0, 0};   // bit i: piece i lies in tile rows 8..15 | is no piece of the tile
-    auto set_geo = [&](int s, int gid) __attribute__((always_inline)) {
-        st_geo[s] = gid;
+    unsigned goff[NPI];   // layout of the tile being requested
+    int loff[NPI];        // layout of the tile being parked
+    int p_geo = -1, k_geo = -1;
+    unsigned p_hi = 0, p_dm = 0;   // bit i: piece i lies in tile rows 8..15 | is no piece of the tile
+    // row << 16 | column of this lane's 16 bytes of piece i in a tile of layout gid; -1: the tile has no such
+    // piece; -2: the piece straddles the tile's end and this lane lies beyond it
+    auto piece_rc = [&](int i, int rs, int end) __attribute__((always_inline)) {
+        const int pc = i * kWaves + w;
+        if ((pc << 10) >= end) return -1;
+        const int off = (pc << 10) + (lane << 4);
+        if (off >= end) return -2;
+        const int row = (int)(((float)off + 8.0f) * (1.0f / (float)rs));   // (off + 8 is never within 4 of a multiple of rs)
+        return row << 16 | (off - row * rs);
+    };
+    auto set_pgeo = [&](int gid) __attribute__((always_inline)) {
+        p_geo = gid;
         const int rs = __builtin_amdgcn_readfirstlane(geo_s[gid * 4]);
         const int K2 = __builtin_amdgcn_readfirstlane(geo_s[gid * 4 + 1]);
         const int end = __builtin_amdgcn_readfirstlane(geo_s[gid * 4 + 2]) * rs;   // bytes of the tile
-        const int np = (end + 1023) >> 10;
-        const float inv_rs = rs ? 1.0f / (float)rs : 0.f;
         unsigned hi = 0, dm = 0;
 #pragma unroll
         for (int i = 0; i < NPI; ++i) {
-            const int pc = i * kWaves + w;
-            if (pc < np) {
-                const int off = (pc << 10) + (lane << 4);
-                if (off < end) {
-                    int row = (int)(((float)off + 8.0f) * inv_rs);   // (off + 8 is never within 4 of a multiple of rs)
-                    const int col = off - row * rs;
-                    goff[s][i] = (unsigned)((gid == 0 ? row & 7 : row) * K2 + col);
-                    loff[s][i] = row * (rs + kRowPad) + col;
-                } else {   // a piece that straddles the tile's end: these lanes read the tile's last 16 bytes again
-                    goff[s][i] = (unsigned)((end / rs - 1) * K2 + rs - 16);
-                    loff[s][i] = a.tile_lds_bytes + (lane << 4);
-                }
-                if (gid == 0 && (pc << 10) >= 8 * rs) hi |= 1u << i;
+            const int rc = piece_rc(i, rs, end);
+            if (rc >= 0) {
+                const int row = rc >> 16, col = rc & 0xffff;
+                goff[i] = (unsigned)((gid == 0 ? row & 7 : row) * K2 + col);
+            } else if (rc == -2) {   // these lanes read the tile's last 16 bytes again
+                goff[i] = (unsigned)((end / rs - 1) * K2 + rs - 16);
             } else {
-                goff[s][i] = (unsigned)(lane << 4);
-                loff[s][i] = a.tile_lds_bytes + (lane << 4);
-                dm |= 1u << i;
+                goff[i] = (unsigned)(lane << 4);
             }
+            const int pc = i * kWaves + w;
+            if ((pc << 10) >= end) dm |= 1u << i;
+            else if (gid == 0 && (pc << 10) >= 8 * rs) hi |= 1u << i;
         }
-        st_hi[s] = hi;
-        st_dm[s] = dm;
+        p_hi = hi;
+        p_dm = dm;
+    };
+    auto set_kgeo = [&](int gid) __attribute__((always_inline)) {
+        k_geo = gid;
+        const int rs = __builtin_amdgcn_readfirstlane(geo_s[gid * 4]);
+        const int end = __builtin_amdgcn_readfirstlane(geo_s[gid * 4 + 2]) * rs;
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) {
+            const int rc = piece_rc(i, rs, end);
+            loff[i] = rc >= 0 ? (rc >> 16) * (rs + kRowPad) + (rc & 0xffff) : a.tile_lds_bytes + (lane << 4);
+        }
     };
     auto issue = [&](int s, int ti) __attribute__((always_inline)) {
         const u32x4 r = *(const u32x4 *)(tab_s + (size_t)ti * kTabWords);
@@ -293,18 +310,19 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
         const unsigned p1h = (unsigned)__builtin_amdgcn_readfirstlane((int)r.w);
         const int gid = (int)(p0l & 15u);
         p0l &= ~15u;
-        if (gid != st_geo[s]) set_geo(s, gid);
+        if (gid != p_geo) set_pgeo(gid);
         g_bytes *p0 = (g_bytes *)(uintptr_t)((u64)p0h << 32 | p0l);
         g_bytes *p1 = (g_bytes *)(uintptr_t)((u64)p1h << 32 | p1l);
 #pragma unroll
         for (int i = 0; i < NPI; ++i) {
-            g_bytes *base = (st_dm[s] >> i) & 1u ? dummy : (st_hi[s] >> i) & 1u ? p1 : p0;   // uniform
-            st[s][i] = ld_stream(base + goff[s][i]);
+            g_bytes *base = (p_dm >> i) & 1u ? dummy : (p_hi >> i) & 1u ? p1 : p0;   // uniform
+            st[s][i] = ld_stream(base + goff[i]);
         }
     };
-    auto park = [&](int s) __attribute__((always_inline)) {
+    auto park = [&](int s, int gid) __attribute__((always_inline)) {   // gid: layout of the tile in register set s
+        if (gid != k_geo) set_kgeo(gid);
 #pragma unroll
-        for (int i = 0; i < NPI; ++i) *(u32x4 *)(tile_s + loff[s][i]) = st[s][i];
+        for (int i = 0; i < NPI; ++i) *(u32x4 *)(tile_s + loff[i]) = st[s][i];
     };
 
     if (ROUTE) {
@@ -320,7 +338,7 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
         int tab_v = -1;
         if (b == 0 && tid < E) tab_v = ra.slot_table[tid];
         const uint16_t *x = (const uint16_t *)ra.hidden;
-        for (int q = b + w * G; q < TE; q += G * kWaves) {
+        for (int q = b + w * G; q < TE; q += G * kAllWaves) {
             const int t = q / E, e = q - t * E;
             const float *wrow = ra.router_w + (size_t)e * H;
             const uint16_t *xr = x + (size_t)t * H;
@@ -350,7 +368,7 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
             }
             for (int i = tid; i < C * ((T + 31) >> 5); i += kThreads) L.cnt_s[i] = 0;
             lds_f32 *lg = L.lg_s + w * lg_stride(E);
-            for (int t = w; t < T; t += kWaves) {
+            for (int t = w; t < T; t += kAllWaves) {
                 const u64 *src = ra.tagged_logits + (size_t)t * E;
                 for (int e0 = 0; e0 < E; e0 += kWave) {
                     const int e = e0 + lane;
@@ -394,6 +412,7 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
         }
     }
     if (tid == 0) misc_s[1] = 0;   // (a barrier follows before anything can set it)
+    if (tid < 256) ((uint32_t *)(lds + a.tile_lds_bytes + 1024))[tid] = 0u;   // the kilobyte of zeros
     if (tid == 0) {
         int *c0 = cls_s, *c1 = cls_s + 8, *c2 = cls_s + 16, *c3 = cls_s + 24;
         c0[0] = np_h; c0[1] = tiles_gs; c0[2] = sg_start0; c0[3] = H; c0[4] = a.KP_h; c0[5] = Fs;
@@ -431,7 +450,9 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
         for (int j = 0; j < kPieces; ++j) {
             const int kb = w + kWaves * j;
             if (kb < nkb) avalid |= 1u << j;
-            aoff[j] = n * (c_rs + kRowPad) + kb * 64 + g * 16;
+            // (a column block that the tile does not have: zeros from the kilobyte kept for that, so that the
+            // multiplication needs no branch and all its LDS reads go out together)
+            aoff[j] = kb < nkb ? n * (c_rs + kRowPad) + kb * 64 + g * 16 : a.tile_lds_bytes + 1024 + (lane << 4);
         }
     };
     // B operand of this wavefront's column blocks.  Gate/up part: the hidden states of tokens 0..T-1, token n
@@ -497,11 +518,13 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
         for (int j = tid; j < nt0; j += kThreads) write_record(j, 0, 0);
         write_end_records(nt0);
         __syncthreads();
-        issue(0, 0);
+        if (!helper) issue(0, 0);
         issued = 1;
         if (nt0 >= 2) {
-            load_bx_of(0);
-            issue(1, 1);
+            if (!helper) {
+                load_bx_of(0);
+                issue(1, 1);
+            }
             issued = 2;
         }
     }
@@ -713,127 +736,99 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
         finish();
         return;
     }
-    if (issued == 0) {
-        issue(0, 0);
-        issued = 1;
-    }
-    if (issued == 1) {
-        // (the first B operand between the first two requests: its wait then covers the first tile only)
-        load_bx_of(0);
-        issue(1, 1);
+    if (!helper) {
+        if (issued == 0) {
+            issue(0, 0);
+            issued = 1;
+        }
+        if (issued == 1) {
+            // (the first B operand between the first two requests: its wait then covers the first tile only)
+            load_bx_of(0);
+            issue(1, 1);
+        }
     }
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // tile rows 0..15 and 16..31
 
     auto multiply = [&]() __attribute__((always_inline)) {
+        u32x4 av[kPieces];
 #pragma unroll
-        for (int j = 0; j < kPieces; ++j) {
-            if ((avalid >> j) & 1u) {
-                u32x4 av = *(const u32x4 *)(tile_s + aoff[j]);
-                acc = mfma(av, bx[j], acc);
-                if (c_two) {
-                    // (rows beyond the item's last one hold whatever the buffer held: their results are not stored)
-                    u32x4 av1 = *(const u32x4 *)(tile_s + aoff[j] + 16 * (c_rs + kRowPad));
-                    acc1 = mfma(av1, bx[j], acc1);
-                }
-            }
-        }
-    };
-    // Results leave in three stages, one step apart, so that nothing of it sits between the parking of a tile and
-    // the request for the next one except one store instruction:
-    //   post    (step t, behind the multiplication) every wavefront puts its partial 16x16 result into red_s;
-    //   reduce  (step t+1, behind the multiplication) all wavefronts add the sixteen partial results: element
-    //           q = lane*4 + j of the MFMA result layout is column (q/4)%16, tile row 4*(q/64) + q%4; wavefront r
-    //           takes elements 16r..16r+15, four lanes per element, each lane four partial results, then the four
-    //           lanes add up (fixed order: the result does not depend on scheduling).  Gate rows are tile rows
-    //           0..7 (elements 0..127) and the up row of the same activation sits 128 elements further on.  The
-    //           lane that holds a finished value (SiLU(gate) * up, or the down projection's sum) also works out
-    //           where it goes and keeps address and value in registers;
-    //   store   (step t+2, between the parking and the request) that lane sends it to memory as a stamped entry.
-    //           A store placed there is older than every load that a later wait must leave in flight, so
-    //           whether a wavefront stored or not, no wait for a tile ever covers a younger tile (the memory
-    //           counter counts loads and stores in order); and it delays the request by one instruction only.
-    // red_s has two halves used in turn, because a reduction reads one while the next item is posted.
-    int post_half = 0;
-    bool red_pending = false, st_pending = false;
-    int rd_cls = 0, rd_row0 = 0, rd_col = 0, rd_mm = 0, rd_half = 0;   // the item posted last
-    bool rd_two = false;
-    u64 *sv_dst = nullptr;   // where this lane's finished value goes (null: it has none)
-    unsigned sv_val = 0, sv_val1 = 0;   // ... and the one 16 rows further on
-    bool sv_one = false, sv_two = false;
-    auto lanes_sum = [&](float v) __attribute__((always_inline)) {   // over the LPE neighbouring lanes of an element
-        // (data-parallel-primitive control quad_perm: each lane reads lane 1,0,3,2, then 2,3,0,1, of its group of four)
-        if (LPE >= 2) v += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0xb1, 0xf, 0xf, false));
-        if (LPE >= 4) v += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0x4e, 0xf, 0xf, false));
-        return v;
-    };
-    auto partial4 = [&](const unsigned char *half, int q, int pg) __attribute__((always_inline)) {   // partial results 4pg..4pg+3 of element q
-        const unsigned char *p = half + (4 * pg) * kRedStride + q * 4;
-        const float x0 = *(const float *)p, x1 = *(const float *)(p + kRedStride);
-        const float x2 = *(const float *)(p + 2 * kRedStride), x3 = *(const float *)(p + 3 * kRedStride);
-        return (x0 + x1) + (x2 + x3);
-    };
-    auto reduce = [&]() __attribute__((always_inline)) {
-        const int pg = lane % LPE;
-        const int q = w * (kWave / LPE) + lane / LPE;   // (the wavefronts cover the 256 elements of a 16x16 block)
-        const unsigned char *half = red_s + rd_half * (kWaves * kRedStride);
-        const int m = rd_mm & 0xff, mask = rd_mm >> 8;
-        const int col = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3);   // (gate/up: q < 128, rows 0..7)
-        const int first_col = rd_col & 0xffff, item_rows = rd_col >> 16;
-        sv_one = sv_two = false;
-        if (rd_cls < 2) {
-            if (q < 128) {   // (uniform over the wavefront)
-                const float s0 = lanes_sum(partial4(half, q, pg)), s1 = lanes_sum(partial4(half, q + 128, pg));
-                // SiLU(s0) * s1 = s0 / (1 + 2^(-s0 log2 e)) * s1 (hardware exponential and reciprocal: the result is
-                // rounded to bf16 anyway)
-                const float v = s0 * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * s0)) * s1;
-                const float vn = __shfl_down(v, LPE, kWave);   // activation row + 1 of the same token (element q + 1)
-                // one 64-bit entry per (token, pair of activations); column `col` is token `col`, and the entry
-                // of the expert's list that this token is = the number of the expert's tokens below it
-                if (pg == 0 && (q & 1) == 0 && ((mask >> col) & 1)) {
-                    const int li = __popc((unsigned)mask & ((1u << col) - 1u));
-                    sv_dst = (rd_cls == 0 ? a.act_sh : a.act) +
-                             (size_t)(rd_row0 + li) * ((rd_cls == 0 ? Fs : F) / 2) + ((first_col + row) >> 1);
-                    sv_val = f32_to_bf16_rne(v) | (f32_to_bf16_rne(vn) << 16);
-                    sv_one = true;
-                }
-            }
-        } else {
-            const float s0 = lanes_sum(partial4(half, q, pg));
-            float s1 = 0.f;
-            if (rd_two) s1 = lanes_sum(partial4(half + 1024, q, pg));
-            if (pg == 0 && col < m) {   // (column `col` is entry `col` of the expert's list)
-                sv_dst = (rd_cls == 2 ? a.o_sh : a.o) + (size_t)(rd_row0 + col) * H + (first_col + row);
-                sv_val = __float_as_uint(s0);
-                sv_val1 = __float_as_uint(s1);
-                sv_one = row < item_rows;
-                sv_two = rd_two && row + 16 < item_rows;
-            }
-        }
-        st_pending = true;
-        red_pending = false;
-    };
-    auto store_results = [&]() __attribute__((always_inline)) {
-#if !(MOE_EXP & 8)
-        if (sv_one) store_entry(sv_dst, wtag, sv_val);
-        if (sv_two) store_entry(sv_dst + 16, wtag, sv_val1);
-#else
-        asm volatile("" :: "v"(sv_dst), "v"(sv_val), "v"(sv_val1), "v"(sv_one), "v"(sv_two));
-#endif
-        st_pending = false;
-    };
-    // everything this workgroup still holds back, out to memory (all wavefronts together: rare paths only)
-    auto drain_results = [&]() __attribute__((always_inline)) {
-        if (st_pending) store_results();
-        if (red_pending) {
-            reduce();
-            store_results();
+        for (int j = 0; j < kPieces; ++j) av[j] = *(const u32x4 *)(tile_s + aoff[j]);
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) acc = mfma(av[j], bx[j], acc);
+        if (c_two) {
+            // (rows beyond the item's last one hold whatever the buffer held: their results are not stored)
+            const int blk1 = 16 * (c_rs + kRowPad);
+#pragma unroll
+            for (int j = 0; j < kPieces; ++j) av[j] = *(const u32x4 *)(tile_s + aoff[j] + ((avalid >> j) & 1u ? blk1 : 0));
+#pragma unroll
+            for (int j = 0; j < kPieces; ++j) acc1 = mfma(av[j], bx[j], acc1);
         }
     };
 
-    // one tile: park it, send out the results reduced in the last step, refresh the B operand if the expert
-    // changed, put the tile two steps ahead in flight, multiply, reduce the item posted in the last step, and on
-    // the item's last panel post the partial result
+    // What the eighth wavefront does with the item that the eight multiplied in the last step (their partial
+    // 16x16 results are in red_s, one or two blocks each; the barrier at the step's end has been passed).
+    // Element q = lane*4 + j of the MFMA result layout is column (q/4)%16, tile row 4*(q/64) + q%4 (+ 16 in the
+    // second block); gate rows are tile rows 0..7 (elements 0..127) and the up row of the same activation sits
+    // 128 elements further on.  Partial results are added in wavefront order: the result does not depend on
+    // scheduling.  red_s has two halves used in turn, because this reads one while the next item is posted.
+    int h_half = 0;
+    auto helper_item = [&](int ti) __attribute__((always_inline)) {
+        const uint32_t *rec = tab_s + (size_t)ti * kTabWords;
+        const unsigned fl = (unsigned)__builtin_amdgcn_readfirstlane((int)rec[4]);
+        if (!(fl & 8u)) return;   // (not the last panel of an item: nothing was posted)
+        const int cls = (int)(fl & 3u);
+        const int row0 = __builtin_amdgcn_readfirstlane((int)rec[5]);
+        const int cr = __builtin_amdgcn_readfirstlane((int)rec[6]);
+        const int mm = __builtin_amdgcn_readfirstlane((int)rec[7]);
+        const int first_col = cr & 0xffff, item_rows = (cr >> 16) & 0xff, m = mm & 0xff, mask = mm >> 8;
+        const unsigned char *half = red_s + h_half * (kWaves * kRedStride);
+        h_half ^= 1;
+        if (cls < 2) {
+            // one 64-bit entry per (token, pair of activations): elements q0, q0 + 1 are rows r, r + 1 of one token
+            const int q0 = 2 * lane;
+            float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
+#pragma unroll
+            for (int v = 0; v < kWaves; ++v) {
+                const float2 gv = *(const float2 *)(half + v * kRedStride + q0 * 4);
+                const float2 uv = *(const float2 *)(half + v * kRedStride + (q0 + 128) * 4);
+                g0 += gv.x; g1 += gv.y; u0 += uv.x; u1 += uv.y;
+            }
+            // SiLU(g) * u = g / (1 + 2^(-g log2 e)) * u (hardware exponential and reciprocal: the result is rounded
+            // to bf16 anyway)
+            const float v0 = g0 * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * g0)) * u0;
+            const float v1 = g1 * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * g1)) * u1;
+            const int col = (q0 >> 2) & 15, row = 4 * (q0 >> 6) + (q0 & 3);
+            // column `col` is token `col`; the entry of the expert's list that this token is = the number of the
+            // expert's tokens below it
+            if ((mask >> col) & 1) {
+                const int li = __popc((unsigned)mask & ((1u << col) - 1u));
+                u64 *dst = (cls == 0 ? a.act_sh : a.act) + (size_t)(row0 + li) * ((cls == 0 ? Fs : F) / 2) +
+                           ((first_col + row) >> 1);
+                store_entry(dst, wtag, f32_to_bf16_rne(v0) | (f32_to_bf16_rne(v1) << 16));
+            }
+        } else {
+            const bool two = __builtin_amdgcn_readfirstlane(geo_s[(cls - 1) * 4 + 2]) > 16;
+            u64 *const obase = cls == 2 ? a.o_sh : a.o;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i >= 4 && !two) break;
+                const int q = lane + 64 * (i & 3);
+                const unsigned char *p = half + (i >> 2) * 1024 + q * 4;
+                float sum = 0.f;
+#pragma unroll
+                for (int v = 0; v < kWaves; ++v) sum += *(const float *)(p + v * kRedStride);
+                const int col = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3) + 16 * (i >> 2);
+                // (column `col` is entry `col` of the expert's list)
+                if (col < m && row < item_rows)
+                    store_entry(obase + (size_t)(row0 + col) * H + (first_col + row), wtag, __float_as_uint(sum));
+            }
+        }
+    };
+
+    // one tile, streaming wavefronts: park it, refresh the B operand if the expert changed, put the tile two
+    // steps ahead in flight, multiply, and on the item's last panel post the partial result
+    int post_half = 0;
     auto step = [&](int s, int ti) __attribute__((always_inline)) {
         MOE_CYC_BEGIN();
         const u32x4 d = *(const u32x4 *)(tab_s + (size_t)ti * kTabWords + 4);
@@ -845,19 +840,15 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
 #endif
         MOE_CYC(0);
 #if !(MOE_EXP & 4)
-        park(s);
+        park(s, (__builtin_amdgcn_readfirstlane((int)d.z) >> 24) & 15);
 #else
 #pragma unroll
         for (int i = 0; i < NPI; ++i) asm volatile("" :: "v"(st[s][i]));   // (the loads stay; nothing is written to LDS)
 #endif
         MOE_CYC(1);
-#if !(MOE_EXP & 1)
-        if (st_pending) store_results();
-#endif
         if ((fl >> 4) != bx_sig) {
-            // (first everything out that this workgroup still holds back: it may be what it, or a workgroup
-            // that it waits for, waits for)
-            drain_results();
+            // (whatever this workgroup still holds back of what it, or a workgroup that it waits for, waits for
+            // here is on its way: the ninth wavefront stores the last item while this one polls)
             const int row0 = __builtin_amdgcn_readfirstlane((int)d.y);
             const int m = __builtin_amdgcn_readfirstlane((int)d.w) & 0xff;
             load_bx((int)(fl & 3u), (int)((fl >> 4) & 0xffu), row0, m);
@@ -875,20 +866,10 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
 #if !(MOE_EXP & 2)
         multiply();
 #endif
-#if !(MOE_EXP & 1)
-        if (red_pending) reduce();   // (the item posted in the last step, or earlier)
-#endif
         if (fl & 8u) {
             *(f32x4 *)(red_s + post_half * (kWaves * kRedStride) + w * kRedStride + lane * 16) = acc;
             if (c_two) *(f32x4 *)(red_s + post_half * (kWaves * kRedStride) + w * kRedStride + 1024 + lane * 16) = acc1;
-            rd_two = c_two;
-            red_pending = true;
-            rd_half = post_half;
             post_half ^= 1;
-            rd_cls = (int)(fl & 3u);
-            rd_row0 = __builtin_amdgcn_readfirstlane((int)d.y);
-            rd_col = __builtin_amdgcn_readfirstlane((int)d.z);
-            rd_mm = __builtin_amdgcn_readfirstlane((int)d.w);
         }
         MOE_CYC(5);
         __syncthreads();   // every wavefront is done with the tile in LDS (and its partial result is posted)
@@ -899,17 +880,30 @@ __global__ __launch_bounds__(WV * 64) void layer_kernel(LayerArgs a, RouteArgs r
 #endif
     };
 
-    // (tiles alternate between the two register sets, so the loop body is two steps; the first tile is peeled
-    // off so that the loop is always entered in the same state: the compiler then counts the loads in flight
-    // exactly and each park waits for its own tile only)
-    step(0, 0);
-    int t = 1;
-    for (; t + 1 < ntiles; t += 2) {
-        step(1, t);
-        step(0, t + 1);
+    if (!helper) {
+        // (tiles alternate between the two register sets, so the loop body is two steps; the first tile is
+        // peeled off so that the loop is always entered in the same state: the compiler then counts the loads
+        // in flight exactly and each park waits for its own tile only)
+        step(0, 0);
+        int t = 1;
+        for (; t + 1 < ntiles; t += 2) {
+            step(1, t);
+            step(0, t + 1);
+        }
+        if (t < ntiles) step(1, t);
+    } else {
+        // the same two barriers per step; between the steps, the item of the step before
+        for (int t = 0; t < ntiles; ++t) {
+#if !(MOE_EXP & 1)
+            if (t > 0) helper_item(t - 1);
+#endif
+            __syncthreads();
+            __syncthreads();
+        }
+#if !(MOE_EXP & 1)
+        helper_item(ntiles - 1);
+#endif
     }
-    if (t < ntiles) step(1, t);
-    drain_results();
     MOE_STAMP(tl_loop);
     __syncthreads();   // (the last reduction has read red_s, which the join reuses)
     finish();
@@ -933,7 +927,7 @@ struct DevInfo {
 };
 DevInfo g_dev[kMaxDevices];
 std::mutex g_dev_mutex;
-int g_layer_waves = 0;
+
 
 }  // namespace
 
@@ -1055,23 +1049,17 @@ hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t 
     const size_t lds = layer_lds_bytes(a.T, a.k, E, a.C, a.H, a.F, a.n_shared, a.F_sh, route != nullptr, args.tab_cap);
     if (lds > (size_t)kLdsBytes || g.npi > 4) return hipErrorInvalidValue;
     if (route && (!route->lists_pub || E > 2 * kWave)) return hipErrorInvalidValue;
-    // wavefronts per workgroup: 8 unless the routing steps inside the launch need a thread per assignment, slot
-    // or expert beyond 512 (g_layer_waves: a setting for experiments, 0 = this rule)
-    int wv = g_layer_waves ? g_layer_waves : 8;
-    if (route && (a.T * a.k > 64 * wv || a.C > 64 * wv || E > 64 * wv)) wv = 16;
-    static const void *const fns[3][2] = {
-        {(const void *)layer_kernel<16, 4, false>, (const void *)layer_kernel<16, 4, true>},
-        {(const void *)layer_kernel<8, 8, false>, (const void *)layer_kernel<8, 8, true>},
-        {(const void *)layer_kernel<4, 16, false>, (const void *)layer_kernel<4, 16, true>}};
-    const int wi = wv == 16 ? 0 : wv == 8 ? 1 : 2;
-    const void *fn = fns[wi][route ? 1 : 0];
+    // (the routing steps inside the launch use a thread per assignment, slot and expert)
+    if (route && (a.T * a.k > 512 || a.C > 512 || E > 512)) return hipErrorInvalidValue;
+    static const void *const fns[2] = {(const void *)layer_kernel<10, false>, (const void *)layer_kernel<10, true>};
+    const void *fn = fns[route ? 1 : 0];
     {
         int dev = 0;
         e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
         std::lock_guard<std::mutex> lock(g_dev_mutex);
         DevInfo &d = g_dev[dev];
-        const int which = wi * 2 + (route ? 1 : 0);
+        const int which = route ? 1 : 0;
         if (!d.attr_done[which]) {
             e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
             if (e != hipSuccess) return e;
@@ -1081,12 +1069,12 @@ hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t 
     RouteArgs rargs = {};
     if (route) rargs = *route;
     void *params[] = {&args, &rargs};
-    hipError_t le = launch_timed(fn, dim3(grid), dim3(64 * wv), params, lds, s, kKindLayer);
+    hipError_t le = launch_timed(fn, dim3(grid), dim3(512), params, lds, s, kKindLayer);
     if (le != hipSuccess) return le;
     return hipGetLastError();
 }
 
-void set_layer_waves(int wv) { g_layer_waves = (wv == 16 || wv == 8 || wv == 4) ? wv : 0; }
+void set_layer_waves(int) {}
 
 hipError_t read_layer_timeline(void *dst, size_t bytes)
 {

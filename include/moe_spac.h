@@ -96,15 +96,28 @@ int moe_workspace_bytes(const moe_shape_t *shape, size_t *bytes_out);
 int moe_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Synchronous health check: waits for `stream`, then reads the control block.
- * Inside the routing launch one workgroup waits for the logits that the others
- * write to device memory, and at the end of the down launch every workgroup
- * waits for the per-assignment outputs of the others; each wait polls a
- * bounded number of times and, should that bound ever run out, sets a flag in
- * the control block and finishes with unspecified results instead of waiting
- * for ever.  Returns MOE_OK when no such flag is set, MOE_ERR_LAUNCH when one
- * is (the flag is cleared, the workspace stays usable) or when the copy
- * fails.  workspace: device pointer. */
+ * Inside a launch workgroups hand results to one another through stamped
+ * entries of the workspace (the logits and the lists of the routing steps,
+ * the per-assignment outputs before the final sum); each wait polls a bounded
+ * number of times and, should that bound ever run out, sets a flag in the
+ * control block and finishes instead of waiting for ever.  The call that it
+ * happened in marks its results: every element of `out` that is written after
+ * the flag was set is NaN, and *miss_count is -1.  Returns MOE_OK when no
+ * flag is set; MOE_ERR_LAUNCH when one is, or when the copy fails.  The flag
+ * is then cleared and the call counter stepped past every number the failed
+ * call may have used, so the workspace stays usable; no call on this
+ * workspace may be in flight meanwhile.  workspace: device pointer. */
 int moe_workspace_status(void *workspace, size_t workspace_bytes, void *stream);
+
+/* Test hook for the failure path above: makes the bounded waits of later
+ * calls on this workspace poll at most `poll_limit` times (0 = the built-in
+ * bound) and adds `stamp_skew` to the call number that producers stamp their
+ * entries with (0 = none), so that with a small limit and a skew of 1 no wait
+ * ever finds its entry, every one runs out quickly, and every kernel still
+ * ends by itself.  moe_workspace_init clears both.  Synchronous.
+ * workspace: device pointer. */
+int moe_workspace_wait_test(void *workspace, size_t workspace_bytes, unsigned poll_limit,
+                            unsigned stamp_skew, void *stream);
 
 /* Step 1 -- Sec. 2.2, lines one to three of the MoE equation.
  *   s = W_g h (+ bias), the k largest logits per token (listed by descending
@@ -147,11 +160,14 @@ int moe_grouped_ffn(const void *hidden, const float *topk_w, const int32_t *slot
                     const void *w_up, const void *w_down, int T, int H, int F, int k, int C, void *out,
                     int out_bf16, int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Steps 1-4 for one verification batch in three launches on `stream` (four
- * for batches above 32 tokens; two for batches of up to 16 tokens and 128
- * experts when the environment variable MOE_SPAC_FUSED_ROUTING is set to
- * something other than 0 at the time of the call: the routing steps then run
- * at the head of the first FFN kernel, same outputs).
+/* Steps 1-4 for one verification batch on `stream`, in the launch form that
+ * shape->launch_form names (MOE_LAUNCH_AUTO: two launches, the routing steps
+ * at the head of the gate/up kernel, for batches of up to 16 tokens and 128
+ * experts with a non-empty pool; else three launches; four above 32 tokens).
+ * Every form computes the same outputs to the same bar.
+ * The workspace carries state from call to call (see moe_workspace_init): it
+ * must have been initialised once, be used by one call at a time, and be
+ * initialised again before it serves another shape.
  * shape: host pointer.  shared_gate/up [n_shared,F_shared,H] and shared_down
  * [n_shared,H,F_shared] bf16 (NULL when n_shared = 0) are added with weight 1
  * for every token.  All step outputs are produced: topk_idx, topk_w [T,k];

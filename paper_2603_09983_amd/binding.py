@@ -39,6 +39,7 @@ _lib.moe_status_string.argtypes = [_i]
 _lib.moe_workspace_bytes.argtypes = [ctypes.POINTER(MoeShape), ctypes.POINTER(_sz)]
 _lib.moe_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.moe_workspace_status.argtypes = [_vp, _sz, _vp]
+_lib.moe_workspace_wait_test.argtypes = [_vp, _sz, ctypes.c_uint, ctypes.c_uint, _vp]
 _lib.moe_route_topk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moe_expert_histogram.argtypes = [_vp, _i, _i, _i, _vp, _vp]
 _lib.moe_slot_resolve.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -60,7 +61,7 @@ _lib.moe_pool_load.argtypes = [_vp] * 9 + [_i] * 3 + [_vp]
 _lib.moe_pool_load.restype = _i
 _lib.moe_utility_init.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]
 _lib.moe_utility_update.argtypes = [_vp] * 7 + [_i] * 5 + [_vp]
-for _f in ("moe_utility_init", "moe_utility_update", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk", "moe_expert_histogram",
+for _f in ("moe_utility_init", "moe_utility_update", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_workspace_wait_test", "moe_route_topk", "moe_expert_histogram",
            "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer"):
     getattr(_lib, _f).restype = _i
 
@@ -76,7 +77,7 @@ _lib.moe_profile_kernel_name.argtypes = [_i]
 _lib.moe_profile_kernel_name.restype = ctypes.c_char_p
 KERNEL_ROUTE, KERNEL_LISTS, KERNEL_FFN, KERNEL_COMBINE, KERNEL_DOWN, KERNEL_ESTIMATOR, KERNEL_BALANCER, KERNEL_CACHE_PLAN, KERNEL_POOL_LOAD, KERNEL_LAYER, KERNEL_KINDS = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10
 
-EXPORTS = ("moe_profile_stream_timeline", "moe_cache_plan", "moe_pool_load", "moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_route_topk",
+EXPORTS = ("moe_profile_stream_timeline", "moe_cache_plan", "moe_pool_load", "moe_balance_threshold", "moe_utility_init", "moe_utility_update", "moe_profile_event_overhead", "moe_profile_enable", "moe_profile_read", "moe_profile_kernel_name", "moe_status_string", "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_workspace_wait_test", "moe_route_topk",
            "moe_expert_histogram", "moe_slot_resolve", "moe_grouped_ffn", "moe_verify_layer", "moe_verify_layer_static")
 
 
@@ -178,6 +179,11 @@ def moe_workspace_init(workspace: torch.Tensor, stream=None, check=True) -> int:
 def moe_workspace_status(workspace: torch.Tensor, stream=None, check=True) -> int:
     return _check(_lib.moe_workspace_status(_ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _stream(stream)), "moe_workspace_status", check)
+
+
+def moe_workspace_wait_test(workspace: torch.Tensor, poll_limit: int, stamp_skew: int, stream=None, check=True) -> int:
+    return _check(_lib.moe_workspace_wait_test(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                               poll_limit, stamp_skew, _stream(stream)), "moe_workspace_wait_test", check)
 
 
 def new_workspace(shape: MoeShape, device="cuda") -> torch.Tensor:

@@ -130,12 +130,6 @@ extern "C" int moe_profile_stream_timeline(unsigned long long *words, size_t n_w
     return e == hipSuccess ? MOE_OK : launch_failed(e);
 }
 
-extern "C" int moe_debug_layer_waves(int wv)
-{
-    set_layer_waves(wv);
-    return MOE_OK;
-}
-
 extern "C" const char *moe_profile_kernel_name(int kind)
 {
     switch (kind) {
@@ -196,13 +190,30 @@ extern "C" int moe_workspace_status(void *workspace, size_t workspace_bytes, voi
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return launch_failed(e);
     if (ctrl[kCtrlError] == 0u) return MOE_OK;
-    // a wait ran out part-way through a call: clear the flag (the call counter keeps counting)
-    ctrl[kCtrlError] = 0u;
-    e = hipMemcpyAsync(workspace, ctrl, sizeof ctrl, hipMemcpyHostToDevice, s);
+    // a wait ran out part-way through a call: clear the flag, and step the call counter by two, so that no
+    // entry which a workgroup of the failed call stamped late (with that call's number, or the next one when the
+    // counter had not been stepped yet) can pass for an entry of a later call
+    const unsigned cleared = 0u, epoch = ctrl[kCtrlEpoch] + 2u;
+    e = hipMemcpyAsync((unsigned *)workspace + kCtrlError, &cleared, sizeof cleared, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync((unsigned *)workspace + kCtrlEpoch, &epoch, sizeof epoch, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return launch_failed(e);
     snprintf(g_launch_msg, sizeof g_launch_msg, "a bounded wait inside a kernel ran out (results of that call are invalid)");
     return MOE_ERR_LAUNCH;
+}
+
+extern "C" int moe_workspace_wait_test(void *workspace, size_t workspace_bytes, unsigned poll_limit,
+                                       unsigned stamp_skew, void *stream)
+{
+    if (!workspace) return MOE_ERR_NULL;
+    if (workspace_bytes < (size_t)kCtrlBytes) return MOE_ERR_WORKSPACE;
+    static_assert(kCtrlSkew == kCtrlSpin + 1, "the two words are written with one copy");
+    hipStream_t s = (hipStream_t)stream;
+    const unsigned words[2] = {poll_limit, stamp_skew};
+    hipError_t e = hipMemcpyAsync((unsigned *)workspace + kCtrlSpin, words, sizeof words, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    return e == hipSuccess ? MOE_OK : launch_failed(e);
 }
 
 extern "C" int moe_route_topk(const void *hidden, const float *router_w, const float *router_bias, int T,
@@ -272,6 +283,7 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
     c.topk_w = topk_w; c.pos = pos; c.out = out;
     c.T = T; c.H = H; c.F = F; c.k = k; c.n_shared = n_shared; c.F_shared = F_shared;
     c.out_bf16 = out_bf16; c.accumulate = accumulate;
+    c.error_flag = (const unsigned *)(ws + w.ctrl) + kCtrlError;
     hipError_t e;
     if (one_launch) {
         // small batch: gate/up, down and the final sum as one weight stream (routing != null: the routing steps too)
@@ -319,6 +331,7 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
             j.topk_w = topk_w; j.pos = pos; j.out = out;
             j.epoch = (const unsigned *)(ws + w.ctrl) + kCtrlEpoch;
             j.error_flag = (unsigned *)(ws + w.ctrl) + kCtrlError;
+            j.miss_count = miss_count;
             j.out_bf16 = out_bf16; j.accumulate = accumulate;
             e = launch_stream(d, false, &j, s);
             return e == hipSuccess ? MOE_OK : launch_failed(e);
@@ -425,7 +438,8 @@ int run_layer(const moe_shape_t *sh, const void *hidden, const float *router_w, 
     const bool can_layer = use_layer_kernel(sh->T, sh->k, sh->E, sh->C, sh->H, sh->F, n_sh, F_sh);
     const bool can_route_inside = w.lists_pub != 0;
     int form = sh->launch_form;
-    if (form == MOE_LAUNCH_AUTO) form = MOE_LAUNCH_THREE;
+    // (the library's choice: routing inside the gate/up launch where the shape allows, one launch less per layer)
+    if (form == MOE_LAUNCH_AUTO) form = can_route_inside ? MOE_LAUNCH_TWO : MOE_LAUNCH_THREE;
     if (form == MOE_LAUNCH_ONE && !(can_layer && can_route_inside)) return MOE_ERR_SHAPE;
     if (form == MOE_LAUNCH_ROUTE_PLUS_ONE && !can_layer) return MOE_ERR_SHAPE;
     if (form == MOE_LAUNCH_TWO && !can_route_inside) return MOE_ERR_SHAPE;

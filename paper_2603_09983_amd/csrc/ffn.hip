@@ -268,6 +268,11 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nsl, in
     for (int i = 0; i < a.n_shared; ++i)
         for (int sl = 0; sl < nsl_sh; ++sl)
             acc += *(const f32x4 *)(a.part_sh + ((size_t)(i * nsl_sh + sl) * a.T + t) * a.H + h);
+    // a bounded wait of an earlier kernel of this call ran out: what would be written is not a result
+    if (a.error_flag && *a.error_flag != 0u) {
+        const float qnan = __uint_as_float(0x7fc00000u);
+        acc = (f32x4){qnan, qnan, qnan, qnan};
+    }
     if (a.out_bf16) {
         u32x2 v = {f32_to_bf16_rne(acc[0]) | (f32_to_bf16_rne(acc[1]) << 16),
                    f32_to_bf16_rne(acc[2]) | (f32_to_bf16_rne(acc[3]) << 16)};

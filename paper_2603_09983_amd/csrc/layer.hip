@@ -78,11 +78,7 @@ __device__ inline u64 load_entry(const u64 *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-#ifndef MOE_EXP
-#define MOE_EXP 0
-#endif
-// (timing experiments produce no results, so they take every entry as this call's)
-#define TAG_IS(x) (MOE_EXP ? true : (unsigned)((x) >> 32) == tag)
+#define TAG_IS(x) ((unsigned)((x) >> 32) == tag)   // an entry that carries this call's number
 #ifdef MOE_STREAM_TRACE
 __device__ unsigned long long g_layer_timeline[kTimelineGroups][kLayerTimelineWords];
 #define MOE_STAMP(var) var = wall_clock64()
@@ -115,27 +111,28 @@ __device__ unsigned long long g_layer_timeline[kTimelineGroups][kLayerTimelineWo
 // of the tile it requests and the one of the tile it multiplies.
 constexpr int kTabWords = 8;            // words of a tile record
 constexpr int kRedStride = 2 * 1024 + 16;   // bytes between the partial results (two 16x16 blocks) of two wavefronts in LDS
+constexpr int kOutBytes = 16 * 1024;    // finished values waiting in LDS (a gate/up item: 512 bytes, a down item: 1 or 2 KB)
+constexpr int kOutRecs = 32;            // ... of at most this many items
 constexpr int kDumpBytes = 2048;        // one KB where pieces that a tile does not have are parked, one KB of zeros
 
-// A workgroup is seven wavefronts that stream (NPI = 10 one-kilobyte pieces of a tile each: 70 places for the
-// 64 pieces of a full tile) and an eighth that only looks after results: it adds up the partial results that
-// the seven post, applies SiLU * up, and stores the finished values as stamped entries.  Stores and loads of
-// one wavefront share one in-order counter, so a store between two tile requests makes the next wait for a
-// tile a wait for the store's acknowledgement from memory as well (measured: 0.3 us per step); the eighth
-// wavefront has no tile loads, so its stores hold nothing back, and the seven never store inside the loop.
-// (Fewer streaming wavefronts with more pieces each move the bytes as fast as sixteen with four, and whatever
-// a step does besides moving data is issued less often; eight wavefronts in all leave each 256 registers.)
+// A workgroup is sixteen wavefronts, each with NPI = 4 one-kilobyte pieces of the tile in flight twice over.
+// Nothing is stored to memory inside the loop: stores and loads of a wavefront share one in-order counter, so
+// a store between two tile requests makes the next wait for a tile a wait for the store's acknowledgement from
+// memory as well (measured: 0.3 us per step, whichever wavefronts store).  Finished values wait in LDS and
+// leave in one go when the workgroup passes from its gate/up tiles to its down tiles (the activations, which
+// other workgroups wait for), when the buffer is full, and at the end.
 template <int NPI, bool ROUTE>
-__global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
+__global__ __launch_bounds__(1024) void layer_kernel(LayerArgs a, RouteArgs ra)
 {
-    constexpr int kWaves = 7, kAllWaves = 8, kThreads = kAllWaves * 64, kPieces = NPI;
+    constexpr int kWaves = 16, kThreads = kWaves * 64, kPieces = NPI;
     static_assert(NPI * kWaves >= 64, "a full tile is 64 pieces");
     extern __shared__ __align__(16) unsigned char lds[];
     const int T = a.T, kk = a.k, H = a.H, F = a.F, Fs = a.F_sh, C = a.C, A = T * kk;
     unsigned char *tile_s = lds;
     unsigned char *red_s = lds + a.tile_lds_bytes + kDumpBytes;        // [wavefront] 2 KB of partial results each
-    int *ctl_s = (int *)(red_s + 2 * kWaves * kRedStride);   // (two halves of partial results)
-    static_assert((2 * kWaves * kRedStride) % 16 == 0, "the arrays behind stay 16-byte aligned");
+    float *out_s = (float *)(red_s + kWaves * kRedStride);   // [kOutBytes / 4] finished values waiting to be stored
+    int *ctl_s = (int *)((unsigned char *)out_s + kOutBytes);
+    static_assert((kWaves * kRedStride) % 16 == 0, "the arrays behind stay 16-byte aligned");
     int *count_s = ctl_s, *offset_s = ctl_s + C, *active_s = ctl_s + 2 * C, *mask_s = ctl_s + 3 * C;
     int *perm_s = ctl_s + 4 * C;     // token of each entry of the per-slot lists
     int *pos_s = perm_s + A;         // row of each assignment's output, -1 = expert not resident
@@ -143,10 +140,11 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
     // per class: panels per item, items per expert, first item of this workgroup's share, contraction length,
     // panel width, rows per expert (constants of the launch, looked up on the rare paths)
     // ... rows per item)
-    int *cls_s = misc_s + 8;         // [4][8]
+    int *orec_s = misc_s + 8;        // [kOutRecs][2]: tile whose item's results wait in out_s, and where
+    int *cls_s = orec_s + 2 * kOutRecs;   // [4][8]
     int *geo_s = cls_s + 32;         // [6][4]: tile row bytes, weight row bytes, rows of the six tile layouts
     u64 *clsp_s = (u64 *)(geo_s + 24);   // [4][2]: where the class's weights start (rows 0..7 and 8..15 of a gate/up tile)
-    uint32_t *tab_s = (uint32_t *)(ctl_s + ((4 * C + 2 * A + 8 + 32 + 24 + 16 + 3) & ~3));   // [tiles + 2][kTabWords]
+    uint32_t *tab_s = (uint32_t *)(ctl_s + ((4 * C + 2 * A + 8 + 2 * kOutRecs + 32 + 24 + 16 + 3) & ~3));   // [tiles + 2][kTabWords]
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
 #ifdef MOE_STREAM_TRACE
@@ -155,7 +153,6 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
 #endif
     MOE_STAMP(tl_start);
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wavefront id, known to be uniform
-    const bool helper = w == kWaves;   // the wavefront that reduces and stores
     const int n = lane & 15, g = lane >> 4;
     const int G = gridDim.x, b = blockIdx.x;
 
@@ -338,7 +335,7 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
         int tab_v = -1;
         if (b == 0 && tid < E) tab_v = ra.slot_table[tid];
         const uint16_t *x = (const uint16_t *)ra.hidden;
-        for (int q = b + w * G; q < TE; q += G * kAllWaves) {
+        for (int q = b + w * G; q < TE; q += G * kWaves) {
             const int t = q / E, e = q - t * E;
             const float *wrow = ra.router_w + (size_t)e * H;
             const uint16_t *xr = x + (size_t)t * H;
@@ -368,7 +365,7 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
             }
             for (int i = tid; i < C * ((T + 31) >> 5); i += kThreads) L.cnt_s[i] = 0;
             lds_f32 *lg = L.lg_s + w * lg_stride(E);
-            for (int t = w; t < T; t += kAllWaves) {
+            for (int t = w; t < T; t += kWaves) {
                 const u64 *src = ra.tagged_logits + (size_t)t * E;
                 for (int e0 = 0; e0 < E; e0 += kWave) {
                     const int e = e0 + lane;
@@ -518,13 +515,11 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
         for (int j = tid; j < nt0; j += kThreads) write_record(j, 0, 0);
         write_end_records(nt0);
         __syncthreads();
-        if (!helper) issue(0, 0);
+        issue(0, 0);
         issued = 1;
         if (nt0 >= 2) {
-            if (!helper) {
-                load_bx_of(0);
-                issue(1, 1);
-            }
+            load_bx_of(0);
+            issue(1, 1);
             issued = 2;
         }
     }
@@ -736,16 +731,14 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
         finish();
         return;
     }
-    if (!helper) {
-        if (issued == 0) {
-            issue(0, 0);
-            issued = 1;
-        }
-        if (issued == 1) {
-            // (the first B operand between the first two requests: its wait then covers the first tile only)
-            load_bx_of(0);
-            issue(1, 1);
-        }
+    if (issued == 0) {
+        issue(0, 0);
+        issued = 1;
+    }
+    if (issued == 1) {
+        // (the first B operand between the first two requests: its wait then covers the first tile only)
+        load_bx_of(0);
+        issue(1, 1);
     }
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // tile rows 0..15 and 16..31
@@ -766,69 +759,93 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
         }
     };
 
-    // What the eighth wavefront does with the item that the eight multiplied in the last step (their partial
-    // 16x16 results are in red_s, one or two blocks each; the barrier at the step's end has been passed).
-    // Element q = lane*4 + j of the MFMA result layout is column (q/4)%16, tile row 4*(q/64) + q%4 (+ 16 in the
-    // second block); gate rows are tile rows 0..7 (elements 0..127) and the up row of the same activation sits
-    // 128 elements further on.  Partial results are added in wavefront order: the result does not depend on
-    // scheduling.  red_s has two halves used in turn, because this reads one while the next item is posted.
-    int h_half = 0;
-    auto helper_item = [&](int ti) __attribute__((always_inline)) {
-        const uint32_t *rec = tab_s + (size_t)ti * kTabWords;
-        const unsigned fl = (unsigned)__builtin_amdgcn_readfirstlane((int)rec[4]);
-        if (!(fl & 8u)) return;   // (not the last panel of an item: nothing was posted)
+    // The sixteen partial results of an item (posted in red_s, barrier passed) are added by wavefronts 0..3 (one
+    // per SIMD unit; the others go on to the next tile), in wavefront order: the result does not depend on
+    // scheduling.  Element q = lane*4 + j of the MFMA result layout is column (q/4)%16, tile row 4*(q/64) + q%4
+    // (+ 16 in the second block); gate rows are tile rows 0..7 (elements 0..127) and the up row of the same
+    // activation sits 128 elements further on.  The finished values (SiLU(gate) * up, or the down projection's
+    // sums) go to out_s; where they go in memory is worked out when they leave.
+    int o_recs = 0, o_used = 0;   // items waiting in out_s, floats used
+    auto reduce_item = [&](int ti, unsigned fl) __attribute__((always_inline)) {
         const int cls = (int)(fl & 3u);
-        const int row0 = __builtin_amdgcn_readfirstlane((int)rec[5]);
-        const int cr = __builtin_amdgcn_readfirstlane((int)rec[6]);
-        const int mm = __builtin_amdgcn_readfirstlane((int)rec[7]);
-        const int first_col = cr & 0xffff, item_rows = (cr >> 16) & 0xff, m = mm & 0xff, mask = mm >> 8;
-        const unsigned char *half = red_s + h_half * (kWaves * kRedStride);
-        h_half ^= 1;
-        if (cls < 2) {
-            // one 64-bit entry per (token, pair of activations): elements q0, q0 + 1 are rows r, r + 1 of one token
-            const int q0 = 2 * lane;
-            float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
+        const int n_out = cls < 2 ? 128 : c_two ? 512 : 256;
+        if (tid < 256) {
+            const unsigned char *p = red_s + tid * 4;
+            if (cls < 2) {
+                if (tid < 128) {
+                    float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-            for (int v = 0; v < kWaves; ++v) {
-                const float2 gv = *(const float2 *)(half + v * kRedStride + q0 * 4);
-                const float2 uv = *(const float2 *)(half + v * kRedStride + (q0 + 128) * 4);
-                g0 += gv.x; g1 += gv.y; u0 += uv.x; u1 += uv.y;
-            }
-            // SiLU(g) * u = g / (1 + 2^(-g log2 e)) * u (hardware exponential and reciprocal: the result is rounded
-            // to bf16 anyway)
-            const float v0 = g0 * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * g0)) * u0;
-            const float v1 = g1 * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * g1)) * u1;
-            const int col = (q0 >> 2) & 15, row = 4 * (q0 >> 6) + (q0 & 3);
-            // column `col` is token `col`; the entry of the expert's list that this token is = the number of the
-            // expert's tokens below it
-            if ((mask >> col) & 1) {
-                const int li = __popc((unsigned)mask & ((1u << col) - 1u));
-                u64 *dst = (cls == 0 ? a.act_sh : a.act) + (size_t)(row0 + li) * ((cls == 0 ? Fs : F) / 2) +
-                           ((first_col + row) >> 1);
-                store_entry(dst, wtag, f32_to_bf16_rne(v0) | (f32_to_bf16_rne(v1) << 16));
-            }
-        } else {
-            const bool two = __builtin_amdgcn_readfirstlane(geo_s[(cls - 1) * 4 + 2]) > 16;
-            u64 *const obase = cls == 2 ? a.o_sh : a.o;
+                    for (int v = 0; v < kWaves; ++v) {
+                        s0 += *(const float *)(p + v * kRedStride);
+                        s1 += *(const float *)(p + v * kRedStride + 512);
+                    }
+                    // SiLU(s0) * s1 = s0 / (1 + 2^(-s0 log2 e)) * s1 (hardware exponential and reciprocal: the
+                    // result is rounded to bf16 anyway)
+                    out_s[o_used + tid] = s0 * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * s0)) * s1;
+                }
+            } else {
+                float s0 = 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (i >= 4 && !two) break;
-                const int q = lane + 64 * (i & 3);
-                const unsigned char *p = half + (i >> 2) * 1024 + q * 4;
-                float sum = 0.f;
+                for (int v = 0; v < kWaves; ++v) s0 += *(const float *)(p + v * kRedStride);
+                out_s[o_used + tid] = s0;
+                if (c_two) {
+                    float s1 = 0.f;
 #pragma unroll
-                for (int v = 0; v < kWaves; ++v) sum += *(const float *)(p + v * kRedStride);
-                const int col = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3) + 16 * (i >> 2);
-                // (column `col` is entry `col` of the expert's list)
-                if (col < m && row < item_rows)
-                    store_entry(obase + (size_t)(row0 + col) * H + (first_col + row), wtag, __float_as_uint(sum));
+                    for (int v = 0; v < kWaves; ++v) s1 += *(const float *)(p + v * kRedStride + 1024);
+                    out_s[o_used + 256 + tid] = s1;
+                }
             }
         }
+        if (tid == 0) {
+            orec_s[2 * o_recs] = ti;
+            orec_s[2 * o_recs + 1] = o_used;
+        }
+        ++o_recs;
+        o_used += n_out;
+    };
+    // Everything that waits in out_s goes to memory as stamped entries, one wavefront per item at a time.
+    auto flush = [&]() __attribute__((always_inline)) {
+        __syncthreads();   // (the last reduction's values, by wavefronts 0..3)
+        for (int r = w; r < o_recs; r += kWaves) {
+            const int ti = __builtin_amdgcn_readfirstlane(orec_s[2 * r]);
+            const float *vals = out_s + __builtin_amdgcn_readfirstlane(orec_s[2 * r + 1]);
+            const uint32_t *rec = tab_s + (size_t)ti * kTabWords;
+            const int cls = __builtin_amdgcn_readfirstlane((int)rec[4]) & 3;
+            const int row0 = __builtin_amdgcn_readfirstlane((int)rec[5]);
+            const int cr = __builtin_amdgcn_readfirstlane((int)rec[6]);
+            const int mm = __builtin_amdgcn_readfirstlane((int)rec[7]);
+            const int first_col = cr & 0xffff, item_rows = (cr >> 16) & 0xff, m = mm & 0xff, mask = mm >> 8;
+            if (cls < 2) {
+                // one 64-bit entry per (token, pair of activations): elements q0, q0 + 1 are rows r, r + 1 of one
+                // token; column `col` is token `col`, and the entry of the expert's list that this token is =
+                // the number of the expert's tokens below it
+                const int q0 = 2 * lane;
+                const int col = (q0 >> 2) & 15, row = 4 * (q0 >> 6) + (q0 & 3);
+                if ((mask >> col) & 1) {
+                    const int li = __popc((unsigned)mask & ((1u << col) - 1u));
+                    u64 *dst = (cls == 0 ? a.act_sh : a.act) + (size_t)(row0 + li) * ((cls == 0 ? Fs : F) / 2) +
+                               ((first_col + row) >> 1);
+                    store_entry(dst, wtag, f32_to_bf16_rne(vals[q0]) | (f32_to_bf16_rne(vals[q0 + 1]) << 16));
+                }
+            } else {
+                u64 *const obase = cls == 2 ? a.o_sh : a.o;
+                const int nblk = item_rows > 16 ? 2 : 1;
+                for (int i = 0; i < 4 * nblk; ++i) {
+                    const int q = lane + 64 * (i & 3);
+                    const int col = (q >> 2) & 15, row = 4 * (q >> 6) + (q & 3) + 16 * (i >> 2);
+                    // (column `col` is entry `col` of the expert's list)
+                    if (col < m && row < item_rows)
+                        store_entry(obase + (size_t)(row0 + col) * H + (first_col + row), wtag,
+                                    __float_as_uint(vals[(i >> 2) * 256 + q]));
+                }
+            }
+        }
+        o_recs = 0;
+        o_used = 0;
     };
 
-    // one tile, streaming wavefronts: park it, refresh the B operand if the expert changed, put the tile two
-    // steps ahead in flight, multiply, and on the item's last panel post the partial result
-    int post_half = 0;
+    // one tile: park it, refresh the B operand if the expert changed, put the tile two steps ahead in flight,
+    // multiply, and on the item's last panel add the partial results up
     auto step = [&](int s, int ti) __attribute__((always_inline)) {
         MOE_CYC_BEGIN();
         const u32x4 d = *(const u32x4 *)(tab_s + (size_t)ti * kTabWords + 4);
@@ -839,16 +856,11 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
         asm volatile("" :: "v"(st[s][NPI - 1]));
 #endif
         MOE_CYC(0);
-#if !(MOE_EXP & 4)
         park(s, (__builtin_amdgcn_readfirstlane((int)d.z) >> 24) & 15);
-#else
-#pragma unroll
-        for (int i = 0; i < NPI; ++i) asm volatile("" :: "v"(st[s][i]));   // (the loads stay; nothing is written to LDS)
-#endif
         MOE_CYC(1);
         if ((fl >> 4) != bx_sig) {
-            // (whatever this workgroup still holds back of what it, or a workgroup that it waits for, waits for
-            // here is on its way: the ninth wavefront stores the last item while this one polls)
+            // (what this workgroup computed of the activations that it, or a workgroup that it waits for, waits
+            // for here has left: the gate/up results are flushed before the first down tile's step)
             const int row0 = __builtin_amdgcn_readfirstlane((int)d.y);
             const int m = __builtin_amdgcn_readfirstlane((int)d.w) & 0xff;
             load_bx((int)(fl & 3u), (int)((fl >> 4) & 0xffu), row0, m);
@@ -863,47 +875,41 @@ __global__ __launch_bounds__(512) void layer_kernel(LayerArgs a, RouteArgs ra)
             acc = (f32x4){0.f, 0.f, 0.f, 0.f};
             acc1 = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
-#if !(MOE_EXP & 2)
         multiply();
-#endif
         if (fl & 8u) {
-            *(f32x4 *)(red_s + post_half * (kWaves * kRedStride) + w * kRedStride + lane * 16) = acc;
-            if (c_two) *(f32x4 *)(red_s + post_half * (kWaves * kRedStride) + w * kRedStride + 1024 + lane * 16) = acc1;
-            post_half ^= 1;
+            *(f32x4 *)(red_s + w * kRedStride + lane * 16) = acc;
+            if (c_two) *(f32x4 *)(red_s + w * kRedStride + 1024 + lane * 16) = acc1;
         }
         MOE_CYC(5);
         __syncthreads();   // every wavefront is done with the tile in LDS (and its partial result is posted)
         MOE_CYC(6);
+        if (fl & 8u) {
+            reduce_item(ti, fl);
+            // out they go: before the first down tile (whose B operand may be what waits here), and when the
+            // next item might not fit
+            const unsigned nfl = (unsigned)__builtin_amdgcn_readfirstlane((int)tab_s[(size_t)(ti + 1) * kTabWords + 4]);
+            const bool leaving_gate_up = (fl & 3u) < 2u && ((nfl & 3u) >= 2u || ti + 1 >= ntiles);
+            if (leaving_gate_up || o_recs == kOutRecs || o_used + 512 > kOutBytes / 4) flush();
+        }
 #ifdef MOE_STREAM_TRACE
         if ((fl & 3u) < 2u) MOE_STAMP(tl_phase);   // (the last gate/up tile leaves the stamp)
         if (ti == 0) MOE_STAMP(tl_first);
 #endif
     };
 
-    if (!helper) {
-        // (tiles alternate between the two register sets, so the loop body is two steps; the first tile is
-        // peeled off so that the loop is always entered in the same state: the compiler then counts the loads
-        // in flight exactly and each park waits for its own tile only)
-        step(0, 0);
+    // (tiles alternate between the two register sets, so the loop body is two steps; the first tile is peeled
+    // off so that the loop is always entered in the same state: the compiler then counts the loads in flight
+    // exactly and each park waits for its own tile only)
+    step(0, 0);
+    {
         int t = 1;
         for (; t + 1 < ntiles; t += 2) {
             step(1, t);
             step(0, t + 1);
         }
         if (t < ntiles) step(1, t);
-    } else {
-        // the same two barriers per step; between the steps, the item of the step before
-        for (int t = 0; t < ntiles; ++t) {
-#if !(MOE_EXP & 1)
-            if (t > 0) helper_item(t - 1);
-#endif
-            __syncthreads();
-            __syncthreads();
-        }
-#if !(MOE_EXP & 1)
-        helper_item(ntiles - 1);
-#endif
     }
+    flush();
     MOE_STAMP(tl_loop);
     __syncthreads();   // (the last reduction has read red_s, which the join reuses)
     finish();
@@ -1006,8 +1012,8 @@ int layer_tab_cap(int T, int C, int H, int F, int n_shared, int F_shared, int G)
 size_t layer_lds_bytes(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared, bool route, int tab_cap)
 {
     const LayerGeom g = layer_geom(H, F, n_shared, F_shared);
-    size_t need = (size_t)g.tile_bytes + kDumpBytes + (size_t)2 * kMaxWaves * kRedStride +
-                  (((size_t)4 * C + 2 * (size_t)T * k + 8 + 32 + 24 + 16 + 3) & ~(size_t)3) * 4 +
+    size_t need = (size_t)g.tile_bytes + kDumpBytes + (size_t)kMaxWaves * kRedStride + kOutBytes +
+                  (((size_t)4 * C + 2 * (size_t)T * k + 8 + 2 * kOutRecs + 32 + 24 + 16 + 3) & ~(size_t)3) * 4 +
                   ((size_t)tab_cap + 2) * kTabWords * 4;
     if (route) {
         const size_t r = post_lds_bytes(E, C, T * k, true);
@@ -1050,8 +1056,8 @@ hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t 
     if (lds > (size_t)kLdsBytes || g.npi > 4) return hipErrorInvalidValue;
     if (route && (!route->lists_pub || E > 2 * kWave)) return hipErrorInvalidValue;
     // (the routing steps inside the launch use a thread per assignment, slot and expert)
-    if (route && (a.T * a.k > 512 || a.C > 512 || E > 512)) return hipErrorInvalidValue;
-    static const void *const fns[2] = {(const void *)layer_kernel<10, false>, (const void *)layer_kernel<10, true>};
+    if (route && (a.T * a.k > 1024 || a.C > 1024 || E > 1024)) return hipErrorInvalidValue;
+    static const void *const fns[2] = {(const void *)layer_kernel<4, false>, (const void *)layer_kernel<4, true>};
     const void *fn = fns[route ? 1 : 0];
     {
         int dev = 0;
@@ -1069,12 +1075,10 @@ hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t 
     RouteArgs rargs = {};
     if (route) rargs = *route;
     void *params[] = {&args, &rargs};
-    hipError_t le = launch_timed(fn, dim3(grid), dim3(512), params, lds, s, kKindLayer);
+    hipError_t le = launch_timed(fn, dim3(grid), dim3(1024), params, lds, s, kKindLayer);
     if (le != hipSuccess) return le;
     return hipGetLastError();
 }
-
-void set_layer_waves(int) {}
 
 hipError_t read_layer_timeline(void *dst, size_t bytes)
 {

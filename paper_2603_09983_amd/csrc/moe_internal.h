@@ -181,6 +181,7 @@ struct JoinArgs {
     void *out;                 // [T,H] fp32 or bf16
     const unsigned *epoch;     // control word: number of this call (stamps the 64-bit entries)
     unsigned *error_flag;      // control word set when a bounded wait ran out
+    int32_t *miss_count;       // [1] or null: set to -1 when a bounded wait ran out
     int out_bf16, accumulate;
 };
 
@@ -218,6 +219,7 @@ struct CombineArgs {
     const int32_t *pos;        // [T*k] row of `part` or -1
     const float *part, *part_sh;
     void *out;
+    const unsigned *error_flag;   // control word set when a bounded wait ran out (then `out` is filled with NaN), or null
     int T, H, F, k, n_shared, F_shared, out_bf16, accumulate;
 };
 
@@ -242,7 +244,6 @@ hipError_t launch_combine_rows(const CombineArgs &a, const float *o, const float
 // the routing steps itself (use_fused_route() true, route->lists_pub set)
 bool use_layer_kernel(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared);
 hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t s);
-void set_layer_waves(int wv);   // experiments: wavefronts per workgroup of the one-launch kernel (0 = the default)
 hipError_t read_layer_timeline(void *dst, size_t bytes);   // [kTimelineGroups][kLayerTimelineWords], tracing builds only
 // Timeline stamps of the last gate/up and down launches: [2][kTimelineGroups][kTimelineWords] 64-bit words
 // (start, lists in LDS, first tile done, loop done, results stored, end: 100 MHz ticks; items, tiles).

@@ -33,7 +33,12 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
     const int b = blockIdx.x, G = gridDim.x;
     const int T = a.T, H = a.H, E = a.E, TE = T * E;
     const int A = T * a.k;
-    const unsigned tag = *a.epoch + 1u;   // stamps this call's logits
+    const unsigned tag = *a.epoch + 1u;   // number of this call
+    // (two words of the control block that only a test sets: the bound of the polls, and a number added to
+    // what producers stamp their entries with, so that the host can make every wait run out)
+    const unsigned *ctrl = a.epoch - kCtrlEpoch;
+    const int spin = ctrl[kCtrlSpin] ? (int)ctrl[kCtrlSpin] : kSpinLimit;
+    const unsigned wtag = tag + ctrl[kCtrlSkew];   // stamps this call's logits
 
     // (workgroup 0) the slot table rides along with the first trip to memory
     int tab_v = -1;
@@ -57,7 +62,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
         for (int m = kWave / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, kWave);
         acc += bias;
         if (lane == 0) {
-            __hip_atomic_store(a.tagged_logits + q, ((unsigned long long)tag << 32) | __float_as_uint(acc),
+            __hip_atomic_store(a.tagged_logits + q, ((unsigned long long)wtag << 32) | __float_as_uint(acc),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (a.logits_opt) a.logits_opt[q] = acc;
         }
@@ -87,7 +92,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
             for (;;) {
                 if (e < E) v = __hip_atomic_load(src + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (__ballot((unsigned)(v >> 32) != tag) == 0ull) break;
-                if (++polls > kSpinLimit) {   // cannot happen on a healthy device; never wait for ever
+                if (++polls > spin) {   // cannot happen on a healthy device; never wait for ever
                     if (lane == 0) atomicOr(a.error_flag, 1u);
                     break;
                 }
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
             __builtin_amdgcn_wave_barrier();
             for (int j = lane; j < a.k; j += kWave)
                 __hip_atomic_store(a.tagged_idx + (size_t)t * a.k + j,
-                                   ((unsigned long long)tag << 32) | (unsigned)L.idx_s[t * a.k + j], __ATOMIC_RELAXED,
+                                   ((unsigned long long)wtag << 32) | (unsigned)L.idx_s[t * a.k + j], __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
     }
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
             for (;;) {
                 v = __hip_atomic_load(a.tagged_idx + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if ((unsigned)(v >> 32) == tag) break;
-                if (++polls > kSpinLimit) {
+                if (++polls > spin) {
                     atomicOr(a.error_flag, 1u);
                     break;
                 }
@@ -150,7 +155,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
     } else if (a.hist) {
         block_histogram(idx, A, E, a.hist, L.hist_s);
     }
-    if (tid == 0) *a.epoch = tag;
+    if (tid == 0) {
+        *a.epoch = tag;
+        // a wait ran out somewhere in this call: what it wrote is not a result, and says so
+        if (a.miss_count && __hip_atomic_load(a.error_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) *a.miss_count = -1;
+    }
 }
 
 __global__ __launch_bounds__(kRouteThreads) void histogram_kernel(const int32_t *idx, int A, int E,

@@ -293,13 +293,18 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
     // FUSED: the routing steps come first, while nothing of the streaming state is alive yet (they need
     // many registers of their own); workgroups other than 0 then request their shared expert's first tile and
     // wait for the lists with that tile in flight.
-    unsigned rtag = 0;
+    unsigned rtag = 0, rwtag = 0;
+    int rspin = kSpinLimit;
     if (FUSED) {
         // ---- steps 1-3 inside this launch (Sec. 2.2, 2.3, App. D), as in the routing kernel ----
         // every workgroup: its share of the T*E dot products, one per wavefront, each logit stored with the
         // call's number as one 64-bit word
         const int T = ra.T, H = ra.H, E = ra.E, TE = T * E, A = T * ra.k, C = ra.C;
         rtag = *ra.epoch + 1u;
+        // (two words of the control block that only a test sets: the bound of the polls, and a number added to
+        // what producers stamp their entries with, so that the host can make every wait run out)
+        rwtag = rtag + (ra.epoch - kCtrlEpoch)[kCtrlSkew];
+        if ((ra.epoch - kCtrlEpoch)[kCtrlSpin]) rspin = (int)(ra.epoch - kCtrlEpoch)[kCtrlSpin];
         const size_t n_pub = list_pub_entries(T, ra.k, C);
         // (workgroup 0 gives the call its number in the control block only when every workgroup has read the
         // old one: each says so with a stamped word of its own)
@@ -325,7 +330,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
             for (int m = kWave / 2; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, kWave);
             dot += bias;
             if (lane == 0) {
-                __hip_atomic_store(ra.tagged_logits + q, ((unsigned long long)rtag << 32) | __float_as_uint(dot),
+                __hip_atomic_store(ra.tagged_logits + q, ((unsigned long long)rwtag << 32) | __float_as_uint(dot),
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (ra.logits_opt) ra.logits_opt[q] = dot;
             }
@@ -350,7 +355,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                     for (;;) {
                         if (e < E) v = __hip_atomic_load(src + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         if (__ballot((unsigned)(v >> 32) != rtag) == 0ull) break;
-                        if (++polls > kSpinLimit) {   // cannot happen on a healthy device; never wait for ever
+                        if (++polls > rspin) {   // cannot happen on a healthy device; never wait for ever
                             if (lane == 0) atomicOr(ra.error_flag, 1u);
                             break;
                         }
@@ -372,11 +377,11 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                                         ra.topk_w + (size_t)t * ra.k, lg);
             }
             __syncthreads();
-            block_post_small<true>(L.idx_s, L.tab_s, T, ra.k, E, C, ra, L.hist_s, L.cnt_s, L.scan_s, L.off_s, rtag);
+            block_post_small<true>(L.idx_s, L.tab_s, T, ra.k, E, C, ra, L.hist_s, L.cnt_s, L.scan_s, L.off_s, rwtag);
             for (int i = tid; i < G; i += kThreads) {
                 int polls = 0;
                 while ((unsigned)(__hip_atomic_load(seen + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != rtag) {
-                    if (++polls > kSpinLimit) {
+                    if (++polls > rspin) {
                         atomicOr(ra.error_flag, 1u);
                         break;
                     }
@@ -405,7 +410,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         if (tid == 0 && b != 0) {
             int polls = 0;
             while ((unsigned)(__hip_atomic_load(pub, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != rtag) {
-                if (++polls > kSpinLimit) break;   // (the loop below reports it)
+                if (++polls > rspin) break;   // (the loop below reports it)
                 __builtin_amdgcn_s_sleep(16);
             }
         }
@@ -416,7 +421,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
             for (;;) {
                 v = __hip_atomic_load(pub + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if ((unsigned)(v >> 32) == rtag) break;
-                if (++polls > kSpinLimit) {
+                if (++polls > rspin) {
                     atomicOr(ra.error_flag, 1u);
                     v = 0;   // (stay inside every array below)
                     break;
@@ -476,6 +481,10 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
     }
     MOE_STAMP(tl_lists);
     const unsigned tag = JOIN ? *jn.epoch : 0u;   // number of this call (set by the routing / list kernel)
+    // (two words of the control block that only a test sets: the bound of the polls, and a number added to what
+    // producers stamp their entries with, so that the host can make every wait run out)
+    const unsigned wtag = JOIN ? tag + (jn.epoch - kCtrlEpoch)[kCtrlSkew] : 0u;
+    const int jspin = JOIN && (jn.epoch - kCtrlEpoch)[kCtrlSpin] ? (int)(jn.epoch - kCtrlEpoch)[kCtrlSpin] : kSpinLimit;
     auto join = [&]() {
         if (!JOIN) return;
         typedef unsigned long long u64;
@@ -483,6 +492,8 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         float *val_s = (float *)tile_s;   // [token][column of the strip][source]; the tile buffer is free by now
         float *gw_s = red_s;              // gate weights, on their way while the entries are waited for
         for (int i = tid; i < a.T * a.k; i += kThreads) gw_s[i] = jn.topk_w[i];
+        int *gave_up_s = odesc_s;         // (the result descriptors are done with) set by a thread whose wait ran out
+        if (tid == 0) *gave_up_s = 0;
         for (int u = b; u < a.R / 8; u += G) {
             __syncthreads();
             for (int i = tid; i < nent; i += kThreads) {
@@ -501,8 +512,9 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                     for (;;) {
                         x = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         if ((unsigned)(x >> 32) == tag) break;
-                        if (++polls > kSpinLimit) {   // cannot happen with the whole grid resident; never wait for ever
+                        if (++polls > jspin) {   // cannot happen with the whole grid resident; never wait for ever
                             atomicOr(jn.error_flag, 1u);
+                            *gave_up_s = 1;
                             break;
                         }
                         __builtin_amdgcn_s_sleep(1);
@@ -511,7 +523,12 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                 }
                 val_s[i] = v;
             }
+            // a wait ran out, here or (the control block says so) anywhere in this call: what is written is not a result
             __syncthreads();
+            const bool poisoned = *gave_up_s != 0 ||
+                                  __hip_atomic_load(jn.error_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+            if (poisoned && tid == 0 && jn.miss_count)
+                __hip_atomic_store(jn.miss_count, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (tid < a.T * 8) {
                 const int t = tid >> 3, col = u * 8 + (tid & 7);
                 const size_t o = (size_t)t * a.R + col;
@@ -521,6 +538,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                                       : ((const float *)jn.out)[o];
                 for (int jj = 0; jj < a.k; ++jj) acc += gw_s[t * a.k + jj] * val_s[tid * S + jj];
                 for (int i = 0; i < a.n_shared; ++i) acc += val_s[tid * S + a.k + i];
+                if (poisoned) acc = __uint_as_float(0x7fc00000u);
                 if (jn.out_bf16) ((uint16_t *)jn.out)[o] = (uint16_t)f32_to_bf16_rne(acc);
                 else ((float *)jn.out)[o] = acc;
             }
@@ -599,7 +617,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                     // explicit global stores (a generic-pointer store would count as an LDS access too)
                     if (JOIN) {
                         // (call number, value) as one 64-bit entry; d[2] / OB = first column of the item
-                        const unsigned long long e = ((unsigned long long)tag << 32) | __float_as_uint(v);
+                        const unsigned long long e = ((unsigned long long)wtag << 32) | __float_as_uint(v);
                         if (d[0])
                             __hip_atomic_store((unsigned long long *)a.out_sh + (size_t)(d[1] + tok) * a.R_sh +
                                                    (d[2] / OB + row), e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -766,6 +784,11 @@ __global__ __launch_bounds__(128) void combine_rows_kernel(CombineArgs a, const 
         if (p >= 0) acc += a.topk_w[(size_t)t * a.k + j] * *(const f32x4 *)(o + (size_t)p * a.H + h);
     }
     for (int i = 0; i < a.n_shared; ++i) acc += *(const f32x4 *)(o_sh + ((size_t)i * a.T + t) * a.H + h);
+    // a bounded wait of an earlier kernel of this call ran out: what would be written is not a result
+    if (a.error_flag && *a.error_flag != 0u) {
+        const float qnan = __uint_as_float(0x7fc00000u);
+        acc = (f32x4){qnan, qnan, qnan, qnan};
+    }
     if (a.out_bf16) {
         u32x2 v = {f32_to_bf16_rne(acc[0]) | (f32_to_bf16_rne(acc[1]) << 16),
                    f32_to_bf16_rne(acc[2]) | (f32_to_bf16_rne(acc[3]) << 16)};

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import oracle
+from paper_2603_09983_amd import binding as B
 from paper_2603_09983_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -19,10 +20,10 @@ def G():
     return gpu_util
 
 
-def run_and_check(G, li, tag):
+def run_and_check(G, li, tag, form=B.LAUNCH_AUTO):
     print(f"[case] {tag} shape={li.shape}", flush=True)
     d = G.upload(li)
-    buf = G.run_layer(d)
+    buf = G.run_layer(d, form=form)
     ref = oracle.layer_from_inputs(li)
     rel = G.check_against_oracle(li, buf, ref, tag=tag)
     s = li.shape
@@ -42,10 +43,11 @@ def test_cfg2_small_moe(G):
     run_and_check(G, synth.make_layer(synth.RECIPES["cfg2"], experts="resident"), "cfg2")
 
 
-def test_cfg2_small_moe_two_launch_option(G, monkeypatch):
-    """The form bench.py times as `fused_routing_option` (routing steps inside the gate/up launch), at full size."""
-    monkeypatch.setenv("MOE_SPAC_FUSED_ROUTING", "1")
-    run_and_check(G, synth.make_layer(synth.RECIPES["cfg2"], experts="resident"), "cfg2/two launches")
+@pytest.mark.parametrize("form", ["three", "two", "one", "route+one"])
+def test_cfg2_small_moe_every_launch_form(G, form):
+    """Every launch form of the layer at full size (auto picks the two-launch form here; bench.py times them all)."""
+    forms = {"three": B.LAUNCH_THREE, "two": B.LAUNCH_TWO, "one": B.LAUNCH_ONE, "route+one": B.LAUNCH_ROUTE_PLUS_ONE}
+    run_and_check(G, synth.make_layer(synth.RECIPES["cfg2"], experts="resident"), "cfg2/" + form, form=forms[form])
 
 
 def test_cfg3_fine_grained_zipf(G):
@@ -61,7 +63,9 @@ def test_cfg4_large_expert_both_capacities(G):
     run_and_check(G, li, "cfg4_c4")
 
 
-@pytest.mark.parametrize("T,layer", [(9, 0), (9, 23), (1, 11), (5, 11), (17, 11), (33, 11), (64, 11), (128, 11)])
+# the first, a middle and the last layer of the sweep's model (their residency differs) at every batch size
+@pytest.mark.parametrize("layer", [0, 11, 23])
+@pytest.mark.parametrize("T", [1, 5, 9, 17, 33, 64, 128])
 def test_cfg5_sweep_layers(G, T, layer):
     r = synth.sweep_recipe(T, layer)
     li = synth.make_layer(r, hidden_seed=synth.sweep_hidden_seed(T), experts="resident")

@@ -259,7 +259,11 @@ def test_route_topk_random_shapes(G):
 
 
 def test_route_topk_nan_logits_rank_last(G):
-    """A NaN logit (here through the bias) is ranked as minus infinity: it is picked only when the finite ones run
+    """Reading (the paper does not say what Top-k does with a NaN score): a NaN logit ranks as minus infinity, ties
+    among them to the lower id.  The oracle's Top-k compares with `>` and has no rule for NaN, so this test does
+    not ask it: the expected ranking is built here from the reading itself (NaN replaced by -inf, then the
+    oracle's rule for ties).
+    A NaN logit (here through the bias) is ranked as minus infinity: it is picked only when the finite ones run
     out, lower ids first, with gate 0."""
     from paper_2603_09983_amd import binding as B
     T, H, E, k = 4, 64, 70, 8
@@ -354,17 +358,24 @@ def test_runtime_errors_leave_outputs_untouched(G):
 
 
 @pytest.mark.parametrize("name", ["ragged_F", "T1_k1", "k_eq_E", "zipf_E60", "E128_k8", "shared_wide_T9"])
-def test_verify_layer_with_the_routing_inside_the_gate_up_launch(G, name, monkeypatch):
-    """The optional two-launch form of the layer (routing steps in front of the gate/up kernel, lists handed to
-    the other workgroups as stamped words): same outputs, to the same bar; then the default form again on the
-    same workspace."""
+def test_verify_layer_with_the_routing_inside_the_gate_up_launch(G, name):
+    """The two-launch form of the layer (routing steps in front of the gate/up kernel, lists handed to the other
+    workgroups as stamped words): same outputs, to the same bar; then the three-launch form on the same
+    workspace."""
+    from paper_2603_09983_amd import binding as B
     li = layer(100 + sorted(SMALL_CASES).index(name), **dict(SMALL_CASES[name]))
     d = G.upload(li)
-    monkeypatch.setenv("MOE_SPAC_FUSED_ROUTING", "1")
-    buf = G.run_layer(d)
+    try:
+        buf = G.run_layer(d, form=B.LAUNCH_TWO)
+    except B.MoeError as err:
+        # a shape the streaming kernels do not take has no two-launch form: asking for it by name is refused
+        # (nothing launched), and the library's own choice still serves the shape
+        assert err.code == B.ERR_SHAPE and name in ("ragged_F",), (name, err)
+        buf = G.run_layer(d)
+        G.check_against_oracle(li, buf, tag=name + "/auto")
+        return
     G.check_against_oracle(li, buf, tag=name + "/fused")
-    buf = G.run_layer(d, buf)
+    buf = G.run_layer(d, buf, form=B.LAUNCH_TWO)
     G.check_against_oracle(li, buf, tag=name + "/fused again")
-    monkeypatch.delenv("MOE_SPAC_FUSED_ROUTING")
-    buf = G.run_layer(d, buf)
+    buf = G.run_layer(d, buf, form=B.LAUNCH_THREE)
     G.check_against_oracle(li, buf, tag=name + "/separate")

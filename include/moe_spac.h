@@ -24,8 +24,11 @@
  *   - Return value: MOE_OK, or a negative code; on a negative code nothing
  *     was launched.  No exceptions, no abort, nothing printed.
  *   - Supported sizes: 1 <= k <= min(E, 64); E <= 512; T*E <= 65536;
- *     C <= 1024; H and F multiples of 32; H <= 4992; bf16 tensors and `out`
- *     16-byte aligned.
+ *     C <= 1024; H, F and F_shared multiples of 8 (rows of 16 bytes); bf16
+ *     tensors and `out` 16-byte aligned.  Batches of up to 32 tokens with
+ *     H, F and F_shared multiples of 64 run in the weight-streaming kernels
+ *     at any H; every other shape runs in a kernel that keeps a token tile's
+ *     hidden rows in LDS, which limits it to H <= 4992 (MOE_ERR_SHAPE beyond).
  *   - Two calls that share a workspace must not overlap in time.  A
  *     workspace holds state between calls (a call counter and regions whose
  *     entries are stamped with it): initialise it with moe_workspace_init
@@ -56,7 +59,7 @@ enum {
     MOE_OK = 0,
     MOE_ERR_NULL = -1,      /* a required pointer is NULL                              */
     MOE_ERR_SHAPE = -2,     /* a size is out of the supported range                    */
-    MOE_ERR_ALIGN = -3,     /* H or F not a multiple of 32, or a misaligned pointer     */
+    MOE_ERR_ALIGN = -3,     /* H or F not a multiple of 8, or a misaligned pointer      */
     MOE_ERR_WORKSPACE = -4, /* workspace_bytes is smaller than the call needs          */
     MOE_ERR_LAUNCH = -5,    /* the HIP runtime refused a launch or an attribute        */
     MOE_ERR_SCRATCH = -6    /* moe_verify_layer_static: the shape needs more scratch memory
@@ -103,7 +106,10 @@ int moe_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
  * control block and finishes instead of waiting for ever.  The call that it
  * happened in marks its results: every element of `out` that is written after
  * the flag was set is NaN, and *miss_count is -1.  Returns MOE_OK when no
- * flag is set; MOE_ERR_LAUNCH when one is, or when the copy fails.  The flag
+ * flag is set; MOE_ERR_LAUNCH when one is, or when the copy fails;
+ * MOE_ERR_WORKSPACE when a call found that the workspace had served a shape
+ * with another layout since its last moe_workspace_init (that call's results
+ * are marked in the same way; initialise the workspace again).  The flag
  * is then cleared and the call counter stepped past every number the failed
  * call may have used, so the workspace stays usable; no call on this
  * workspace may be in flight meanwhile.  workspace: device pointer. */

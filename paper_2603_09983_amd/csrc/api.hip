@@ -2,6 +2,8 @@
 #include "../../include/moe_spac.h"
 #include "moe_internal.h"
 #include <mutex>
+#include <unordered_map>
+#include <vector>
 
 using namespace moe;
 
@@ -20,7 +22,7 @@ constexpr int kProfMax = 8192;
 struct ProfState {
     bool on = false;
     hipEvent_t ev[MOE_KERNEL_KINDS][kProfMax][2];
-    int created = 0;   // pairs created per kind
+    int created[MOE_KERNEL_KINDS] = {};   // pairs made so far, per kind
     int used[MOE_KERNEL_KINDS] = {};
 } g_prof;
 
@@ -34,15 +36,64 @@ int check_route_shape(int T, int H, int E, int k)
     return MOE_OK;
 }
 
-int check_ffn_shape(int T, int H, int F, int k, int C)
+int check_ffn_shape(int T, int H, int F, int k, int C, int n_shared, int F_shared)
 {
     if (T < 1 || H < 1 || F < 1 || k < 1 || C < 0 || C > kMaxC || T > 65535) return MOE_ERR_SHAPE;
-    if (H % 32 != 0 || F % 32 != 0) return MOE_ERR_ALIGN;
-    if (ffn_token_tiles(T, H) == 0) return MOE_ERR_SHAPE;
+    if (H % 8 != 0 || F % 8 != 0 || (n_shared > 0 && F_shared % 8 != 0)) return MOE_ERR_ALIGN;   // 16-byte rows
+    // the kernel that takes what the streaming kernels do not keeps a token tile's hidden rows in LDS
+    if (!use_stream_kernels(T, k, C, H, F, n_shared, F_shared) && ffn_token_tiles(T, H) == 0) return MOE_ERR_SHAPE;
     return MOE_OK;
 }
 
 }  // namespace
+
+namespace {
+struct DeviceState {
+    int n_cus = 0;
+    std::unordered_map<const void *, int> lds_allowed;   // kernel -> dynamic LDS bytes it has been allowed
+};
+DeviceState g_device[kMaxDevices];
+std::mutex g_device_mutex;
+
+hipError_t current_device(int *dev)
+{
+    hipError_t e = hipGetDevice(dev);
+    if (e == hipSuccess && (*dev < 0 || *dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    return e;
+}
+}  // namespace
+
+int moe::device_cus(hipError_t *err)
+{
+    int dev = 0, n = 0;
+    hipError_t e = current_device(&dev);
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(g_device_mutex);
+        DeviceState &d = g_device[dev];
+        if (d.n_cus == 0) {
+            int nc = 0;
+            e = hipDeviceGetAttribute(&nc, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e == hipSuccess) d.n_cus = nc > 0 ? (nc < kMaxGroups ? nc : kMaxGroups) : 256;
+        }
+        n = d.n_cus;
+    }
+    if (err) *err = e;
+    return n;
+}
+
+hipError_t moe::allow_full_lds(const void *fn, int bytes)
+{
+    int dev = 0;
+    hipError_t e = current_device(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    DeviceState &d = g_device[dev];
+    auto it = d.lds_allowed.find(fn);
+    if (it != d.lds_allowed.end() && it->second >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) d.lds_allowed[fn] = bytes;
+    return e;
+}
 
 // One kernel launch, bracketed by a pair of events on its stream while the measurement aid is on.
 hipError_t moe::launch_timed(const void *fn, dim3 grid, dim3 block, void **params, size_t lds, hipStream_t s,
@@ -56,12 +107,24 @@ hipError_t moe::launch_timed(const void *fn, dim3 grid, dim3 block, void **param
 
 void moe::prof_begin(int kind, hipStream_t s)
 {
-    if (g_prof.on && g_prof.used[kind] < g_prof.created) (void)hipEventRecord(g_prof.ev[kind][g_prof.used[kind]][0], s);
+    if (!g_prof.on || g_prof.used[kind] >= kProfMax) return;
+    // (event pairs are made when first needed: a process that never measures makes none)
+    int &made = g_prof.created[kind];
+    if (g_prof.used[kind] >= made) {
+        hipEvent_t *pair = g_prof.ev[kind][made];
+        if (hipEventCreate(&pair[0]) != hipSuccess) return;
+        if (hipEventCreate(&pair[1]) != hipSuccess) {
+            (void)hipEventDestroy(pair[0]);
+            return;
+        }
+        ++made;
+    }
+    (void)hipEventRecord(g_prof.ev[kind][g_prof.used[kind]][0], s);
 }
 
 void moe::prof_end(int kind, hipStream_t s)
 {
-    if (g_prof.on && g_prof.used[kind] < g_prof.created) {
+    if (g_prof.on && g_prof.used[kind] < g_prof.created[kind]) {
         (void)hipEventRecord(g_prof.ev[kind][g_prof.used[kind]][1], s);
         ++g_prof.used[kind];
     }
@@ -69,13 +132,6 @@ void moe::prof_end(int kind, hipStream_t s)
 
 extern "C" int moe_profile_enable(int on)
 {
-    if (on && g_prof.created == 0) {
-        for (int k = 0; k < MOE_KERNEL_KINDS; ++k)
-            for (int i = 0; i < kProfMax; ++i)
-                for (int j = 0; j < 2; ++j)
-                    if (hipEventCreate(&g_prof.ev[k][i][j]) != hipSuccess) return MOE_ERR_LAUNCH;
-        g_prof.created = kProfMax;
-    }
     if (on)
         for (int k = 0; k < MOE_KERNEL_KINDS; ++k) g_prof.used[k] = 0;
     g_prof.on = on != 0;
@@ -101,22 +157,26 @@ extern "C" int moe_profile_read(int kind, double *total_ms, int *launches)
 extern "C" int moe_profile_event_overhead(void *stream, int pairs, double *avg_ms)
 {
     if (!avg_ms) return MOE_ERR_NULL;
-    if (pairs < 1 || pairs > kProfMax || g_prof.created == 0) return MOE_ERR_SHAPE;
+    if (pairs < 1 || pairs > kProfMax) return MOE_ERR_SHAPE;
     hipStream_t s = (hipStream_t)stream;
-    // the pairs of kind 0 serve as scratch: nothing between the two records of a pair
-    for (int i = 0; i < pairs; ++i) {
-        if (hipEventRecord(g_prof.ev[0][i][0], s) != hipSuccess) return MOE_ERR_LAUNCH;
-        if (hipEventRecord(g_prof.ev[0][i][1], s) != hipSuccess) return MOE_ERR_LAUNCH;
-    }
-    if (hipStreamSynchronize(s) != hipSuccess) return MOE_ERR_LAUNCH;
+    // event pairs of its own, nothing between the two records of a pair
+    std::vector<hipEvent_t> ev((size_t)2 * pairs, nullptr);
+    int rc = MOE_OK;
+    for (auto &e : ev)
+        if (rc == MOE_OK && hipEventCreate(&e) != hipSuccess) rc = MOE_ERR_LAUNCH;
+    for (int i = 0; i < 2 * pairs && rc == MOE_OK; ++i)
+        if (hipEventRecord(ev[i], s) != hipSuccess) rc = MOE_ERR_LAUNCH;
+    if (rc == MOE_OK && hipStreamSynchronize(s) != hipSuccess) rc = MOE_ERR_LAUNCH;
     double sum = 0.0;
-    for (int i = 0; i < pairs; ++i) {
+    for (int i = 0; i < pairs && rc == MOE_OK; ++i) {
         float ms = 0.f;
-        if (hipEventElapsedTime(&ms, g_prof.ev[0][i][0], g_prof.ev[0][i][1]) != hipSuccess) return MOE_ERR_LAUNCH;
+        if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) != hipSuccess) rc = MOE_ERR_LAUNCH;
         sum += ms;
     }
-    *avg_ms = sum / pairs;
-    return MOE_OK;
+    for (auto &e : ev)
+        if (e) (void)hipEventDestroy(e);
+    if (rc == MOE_OK) *avg_ms = sum / pairs;
+    return rc;
 }
 
 extern "C" int moe_profile_stream_timeline(unsigned long long *words, size_t n_words)
@@ -153,8 +213,8 @@ extern "C" const char *moe_status_string(int status)
     case MOE_OK: return "ok";
     case MOE_ERR_NULL: return "a required pointer is NULL";
     case MOE_ERR_SHAPE: return "a size is outside the supported range";
-    case MOE_ERR_ALIGN: return "H or F is not a multiple of 32 (8 for routing), or a pointer is not 16-byte aligned";
-    case MOE_ERR_WORKSPACE: return "workspace is smaller than moe_workspace_bytes() asks for";
+    case MOE_ERR_ALIGN: return "H or F is not a multiple of 8, or a pointer is not 16-byte aligned";
+    case MOE_ERR_WORKSPACE: return "workspace is smaller than moe_workspace_bytes() asks for, or has served another shape since moe_workspace_init";
     case MOE_ERR_LAUNCH: return g_launch_msg;
     case MOE_ERR_SCRATCH: return "the shape needs more scratch memory than the library's static array holds";
     default: return "unknown status";
@@ -199,6 +259,8 @@ extern "C" int moe_workspace_status(void *workspace, size_t workspace_bytes, voi
         e = hipMemcpyAsync((unsigned *)workspace + kCtrlEpoch, &epoch, sizeof epoch, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return launch_failed(e);
+    if (ctrl[kCtrlError] & kErrLayout)   // (the layout word stays: the next call with that other shape says so again)
+        return MOE_ERR_WORKSPACE;
     snprintf(g_launch_msg, sizeof g_launch_msg, "a bounded wait inside a kernel ran out (results of that call are invalid)");
     return MOE_ERR_LAUNCH;
 }
@@ -363,7 +425,7 @@ extern "C" int moe_grouped_ffn(const void *hidden, const float *topk_w, const in
 {
     if (!hidden || !topk_w || !slot_idx || !out || !workspace) return MOE_ERR_NULL;
     if (C > 0 && (!w_gate || !w_up || !w_down)) return MOE_ERR_NULL;
-    int rc = check_ffn_shape(T, H, F, k, C);
+    int rc = check_ffn_shape(T, H, F, k, C, 0, 0);
     if (rc) return rc;
     if (!aligned16(hidden) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) ||
         !aligned16(out) || !aligned16(workspace))
@@ -373,7 +435,7 @@ extern "C" int moe_grouped_ffn(const void *hidden, const float *topk_w, const in
     if (workspace_bytes < w.total) return MOE_ERR_WORKSPACE;
     char *ws = (char *)workspace;
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = launch_lists_from_slots(slot_idx, T * k, C, (int32_t *)(ws + w.slot_count),
+    hipError_t e = launch_lists_from_slots(layout_hash(w), slot_idx, T * k, C, (int32_t *)(ws + w.slot_count),
                                            (int32_t *)(ws + w.slot_offset), (int32_t *)(ws + w.perm),
                                            (int32_t *)(ws + w.pos), (int32_t *)(ws + w.active),
                                            (unsigned *)(ws + w.ctrl) + kCtrlNActive,
@@ -401,9 +463,8 @@ int check_layer_args(const moe_shape_t *sh, const void *hidden, const float *rou
     if (sh->n_shared > 0 && (!shared_gate || !shared_up || !shared_down)) return MOE_ERR_NULL;
     int rc = check_route_shape(sh->T, sh->H, sh->E, sh->k);
     if (rc) return rc;
-    rc = check_ffn_shape(sh->T, sh->H, sh->F, sh->k, sh->C);
+    rc = check_ffn_shape(sh->T, sh->H, sh->F, sh->k, sh->C, sh->n_shared, sh->n_shared ? sh->F_shared : 0);
     if (rc) return rc;
-    if (sh->n_shared > 0 && sh->F_shared % 32 != 0) return MOE_ERR_ALIGN;
     if (!aligned16(hidden) || !aligned16(router_w) || !aligned16(w_gate) || !aligned16(w_up) ||
         !aligned16(w_down) || !aligned16(shared_gate) || !aligned16(shared_up) || !aligned16(shared_down) ||
         !aligned16(out))
@@ -426,6 +487,7 @@ int run_layer(const moe_shape_t *sh, const void *hidden, const float *router_w, 
     r.epoch = (unsigned *)(ws + w.ctrl) + kCtrlEpoch;
     r.error_flag = (unsigned *)(ws + w.ctrl) + kCtrlError;
     r.topk_idx = topk_idx; r.topk_w = topk_w; r.logits_opt = nullptr; r.hist = hist;
+    r.layout = layout_hash(w);
     r.slot_table = slot_table; r.C = sh->C;
     r.slot_idx = slot_idx; r.miss_list = miss_list; r.miss_count = miss_count;
     r.slot_count = (int32_t *)(ws + w.slot_count); r.slot_offset = (int32_t *)(ws + w.slot_offset);

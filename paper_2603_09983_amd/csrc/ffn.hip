@@ -51,8 +51,10 @@ __device__ inline f32x4 mfma(u32x4 a, bf16x8 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16(a), b, c, 0, 0, 0);
 }
 
-// NT = token tiles of 16 processed per pass over the weights.
-template <int NT>
+// NT = token tiles of 16 processed per pass over the weights.  RAGGED: H or an F is a multiple of 8 only;
+// rows and contraction blocks that reach past the end of a matrix are masked lane by lane (loads become
+// zeros, stores are skipped), in plain loops without the deep pipelines.
+template <int NT, bool RAGGED>
 __global__ __launch_bounds__(kFfnThreads) void ffn_kernel(FfnArgs a, int nsl, int nsl_sh, int xs /*bytes per x row in LDS*/)
 {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -95,17 +97,17 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_kernel(FfnArgs a, int nsl, in
         part = a.part + ((size_t)slice * a.T * a.k + base) * H;
     }
     const int f0 = slice * kSliceF;
-    const bool wave_has_rows = f0 + 16 * w < F;      // F is a multiple of 32
-    const int nkb_down = (F - f0) / 32 < 4 ? (F - f0) / 32 : 4;
+    const bool wave_has_rows = f0 + 16 * w < F;      // (not RAGGED: F is a multiple of 32)
+    const int nkb_down = (F - f0 + 31) / 32 < 4 ? (F - f0 + 31) / 32 : 4;
     const uint16_t *xg = (const uint16_t *)a.hidden;
 
     for (int r0 = 0; r0 < m; r0 += NT * 16) {
         // ---- gather the routed tokens' hidden rows into LDS (zero rows beyond m) ----
-        const int chunks_per_row = H / 8;
+        const int chunks_per_row = (H + 31) / 32 * 4;   // (zeros up to the next multiple of 32 columns)
         for (int q = tid; q < NT * 16 * chunks_per_row; q += kFfnThreads) {
             int r = q / chunks_per_row, col = q - r * chunks_per_row;
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (r0 + r < m) {
+            if (r0 + r < m && col * 8 < H) {
                 int t = is_shared ? (r0 + r) : a.perm[base + r0 + r] / a.k;
                 v = *(const u32x4 *)(xg + (size_t)t * H + col * 8);
             }
@@ -117,7 +119,25 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_kernel(FfnArgs a, int nsl, in
         f32x4 accg[NT], accu[NT];
 #pragma unroll
         for (int tl = 0; tl < NT; ++tl) { accg[tl] = (f32x4){0.f, 0.f, 0.f, 0.f}; accu[tl] = accg[tl]; }
-        if (wave_has_rows) {
+        if (RAGGED && wave_has_rows) {
+            const int row = f0 + 16 * w + n;
+            const bool row_ok = row < F;
+            const size_t roff = (size_t)(row_ok ? row : F - 1) * H;
+            const unsigned char *xb = x_s + (size_t)n * xs + g * 16;
+            for (int kb = 0; kb < (H + 31) / 32; ++kb) {
+                const int col = kb * 32 + g * 8;
+                const bool ok = row_ok && col < H;
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                const u32x4 tg = ok ? ld_stream(wg + roff + col) : zero;
+                const u32x4 tu = ok ? ld_stream(wu + roff + col) : zero;
+#pragma unroll
+                for (int tl = 0; tl < NT; ++tl) {
+                    bf16x8 bx = *(const bf16x8 *)(xb + (size_t)tl * 16 * xs + kb * 64);
+                    accg[tl] = mfma(tg, bx, accg[tl]);
+                    accu[tl] = mfma(tu, bx, accu[tl]);
+                }
+            }
+        } else if (wave_has_rows) {
             const uint16_t *pg = wg + (size_t)(f0 + 16 * w + n) * H + g * 8;
             const uint16_t *pu = wu + (size_t)(f0 + 16 * w + n) * H + g * 8;
             const unsigned char *xb = x_s + (size_t)n * xs + g * 16;
@@ -194,7 +214,7 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_kernel(FfnArgs a, int nsl, in
             for (int i = 0; i < 4; ++i)
                 bact[tl][i] = *(const bf16x8 *)(act_s + (size_t)(tl * 16 + n) * kActStride + (i * 32 + g * 8) * 2);
 
-        const int nrt = H / 16;                       // output row tiles, dealt round-robin to wavefronts
+        const int nrt = (H + 15) / 16;                // output row tiles, dealt round-robin to wavefronts
         const int my_tiles = (nrt - w + kWaves - 1) / kWaves;
         const uint16_t *pd = wd + (size_t)(16 * w + n) * F + f0 + g * 8;
         const size_t tile_step = (size_t)16 * kWaves * F;
@@ -215,7 +235,25 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_kernel(FfnArgs a, int nsl, in
             }
             po += 16 * kWaves;
         };
-        if (nkb_down == 4 && my_tiles >= kDownStages && my_tiles % kDownStages == 0) {
+        if (RAGGED) {
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            for (int it = 0; it < my_tiles; ++it) {
+                const int row = 16 * (w + it * kWaves) + n;          // this lane's weight row (an output column)
+                const bool row_ok = row < H;
+                const uint16_t *prow = wd + (size_t)(row_ok ? row : H - 1) * F;
+                const bool store_ok = 16 * (w + it * kWaves) + 4 * g < H;   // the lane's four outputs: all in or all out
+#pragma unroll
+                for (int tl = 0; tl < NT; ++tl) {
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                    for (int i = 0; i < nkb_down; ++i) {
+                        const int col = f0 + i * 32 + g * 8;
+                        acc = mfma(row_ok && col < F ? ld_stream(prow + col) : zero, bact[tl][i], acc);
+                    }
+                    if (store_ok && r0 + tl * 16 + n < m) *(f32x4 *)(po + (size_t)tl * 16 * H) = acc;
+                }
+                po += 16 * kWaves;
+            }
+        } else if (nkb_down == 4 && my_tiles >= kDownStages && my_tiles % kDownStages == 0) {
 #pragma unroll
             for (int s = 0; s < kDownStages; ++s) load_tile(s);
             for (int it = kDownStages; it < my_tiles; it += kDownStages) {
@@ -284,9 +322,12 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nsl, in
 
 }  // namespace
 
+// (x rows in LDS reach the next multiple of 32 columns, zero-filled)
+static int x_row_bytes(int H) { return 2 * ((H + 31) / 32 * 32) + 16; }
+
 size_t ffn_lds_bytes(int H, int nt)
 {
-    return (size_t)nt * 16 * (2 * (size_t)H + 16) + (size_t)nt * 16 * kActStride;
+    return (size_t)nt * 16 * (size_t)x_row_bytes(H) + (size_t)nt * 16 * kActStride;
 }
 
 int ffn_token_tiles(int T, int H)
@@ -302,23 +343,20 @@ hipError_t launch_ffn(const FfnArgs &a, hipStream_t s)
     const int blocks = a.C * nsl + a.n_shared * nsl_sh;
     if (blocks == 0) return hipSuccess;
     const int nt = ffn_token_tiles(a.T, a.H);
+    if (nt == 0) return hipErrorInvalidValue;
     const size_t lds = ffn_lds_bytes(a.H, nt);
-    const int xs = 2 * a.H + 16;
-    static bool attr_done[3] = {false, false, false};
-    if (!attr_done[nt]) {
-        hipError_t e = hipFuncSetAttribute(
-            nt == 2 ? (const void *)ffn_kernel<2> : (const void *)ffn_kernel<1>,
-            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_done[nt] = true;
-    }
-    prof_begin(2, s);
-    if (nt == 2)
-        hipLaunchKernelGGL(ffn_kernel<2>, dim3(blocks), dim3(kFfnThreads), lds, s, a, nsl, nsl_sh, xs);
-    else
-        hipLaunchKernelGGL(ffn_kernel<1>, dim3(blocks), dim3(kFfnThreads), lds, s, a, nsl, nsl_sh, xs);
-    prof_end(2, s);
-    return hipGetLastError();
+    const int xs = x_row_bytes(a.H);
+    const bool ragged = a.H % 32 != 0 || a.F % 32 != 0 || (a.n_shared && a.F_shared % 32 != 0);
+    static const void *const fns[2][2] = {{(const void *)ffn_kernel<1, false>, (const void *)ffn_kernel<1, true>},
+                                          {(const void *)ffn_kernel<2, false>, (const void *)ffn_kernel<2, true>}};
+    const void *fn = fns[nt - 1][ragged ? 1 : 0];
+    hipError_t e = allow_full_lds(fn);
+    if (e != hipSuccess) return e;
+    FfnArgs args = a;
+    int nsl_a = nsl, nsl_sh_a = nsl_sh, xs_a = xs;
+    void *params[] = {&args, &nsl_a, &nsl_sh_a, &xs_a};
+    e = launch_timed(fn, dim3(blocks), dim3(kFfnThreads), params, lds, s, 2);
+    return e != hipSuccess ? e : hipGetLastError();
 }
 
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s)

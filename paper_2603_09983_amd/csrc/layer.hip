@@ -163,6 +163,7 @@ __global__ __launch_bounds__(1024) void layer_kernel(LayerArgs a, RouteArgs ra)
     const int spin = spin_w ? (int)spin_w : kSpinLimit;
     const unsigned tag = ROUTE ? epoch0 + 1u : epoch0;   // number of this call
     const unsigned wtag = tag + skew;                    // what this call's entries are stamped with (skew = 0)
+    if (ROUTE && b == 0 && tid == 0) check_layout(a.ctrl, ra.layout);
     auto give_up = [&]() __attribute__((always_inline)) {   // never wait for ever: say so in the control block and poison what this workgroup writes
         atomicOr(error_flag, 1u);
         misc_s[1] = 1;
@@ -687,7 +688,8 @@ __global__ __launch_bounds__(1024) void layer_kernel(LayerArgs a, RouteArgs ra)
                 val_s[i] = v;
             }
             __syncthreads();
-            const bool poisoned = misc_s[1] != 0;
+            const bool poisoned = misc_s[1] != 0 ||
+                                  __hip_atomic_load(error_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
             if (tid < T * 8) {
                 const int t = tid >> 3, col = u * 8 + (tid & 7);
                 const size_t o = (size_t)t * H + col;
@@ -706,7 +708,9 @@ __global__ __launch_bounds__(1024) void layer_kernel(LayerArgs a, RouteArgs ra)
     auto finish = [&]() __attribute__((always_inline)) {
         join();
         __syncthreads();
-        if (tid == 0 && misc_s[1] != 0 && a.miss_count)
+        // a wait ran out, here or (the control block says so) anywhere in this call: the call says so in miss_count too
+        if (tid == 0 && a.miss_count &&
+            (misc_s[1] != 0 || __hip_atomic_load(error_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u))
             __hip_atomic_store(a.miss_count, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (ROUTE && b == 0) {
             // the call's number goes into the control block once every workgroup has read the old one
@@ -927,38 +931,12 @@ __global__ __launch_bounds__(1024) void layer_kernel(LayerArgs a, RouteArgs ra)
 #endif
 }
 
-struct DevInfo {
-    int n_cus = 0;
-    bool attr_done[8] = {};
-};
-DevInfo g_dev[kMaxDevices];
-std::mutex g_dev_mutex;
 
 
 }  // namespace
 
 namespace {
 
-// number of CUs of the current device = workgroups of the launch (0: the runtime would not say)
-int device_cus(hipError_t *err)
-{
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
-    int n = 0;
-    if (e == hipSuccess) {
-        std::lock_guard<std::mutex> lock(g_dev_mutex);
-        DevInfo &d = g_dev[dev];
-        if (d.n_cus == 0) {
-            int nc = 0;
-            e = hipDeviceGetAttribute(&nc, hipDeviceAttributeMultiprocessorCount, dev);
-            if (e == hipSuccess) d.n_cus = nc > 0 ? (nc < kMaxGroups ? nc : kMaxGroups) : 256;
-        }
-        n = d.n_cus;
-    }
-    if (err) *err = e;
-    return n;
-}
 
 // rows of a down item whose panel is KP columns wide: as many as fit 64 pieces of 1 KB, 16..32
 int down_rows(int KP)
@@ -1059,19 +1037,8 @@ hipError_t launch_layer(const LayerArgs &a, const RouteArgs *route, hipStream_t 
     if (route && (a.T * a.k > 1024 || a.C > 1024 || E > 1024)) return hipErrorInvalidValue;
     static const void *const fns[2] = {(const void *)layer_kernel<4, false>, (const void *)layer_kernel<4, true>};
     const void *fn = fns[route ? 1 : 0];
-    {
-        int dev = 0;
-        e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        std::lock_guard<std::mutex> lock(g_dev_mutex);
-        DevInfo &d = g_dev[dev];
-        const int which = route ? 1 : 0;
-        if (!d.attr_done[which]) {
-            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-            if (e != hipSuccess) return e;
-            d.attr_done[which] = true;
-        }
-    }
+    e = allow_full_lds(fn);
+    if (e != hipSuccess) return e;
     RouteArgs rargs = {};
     if (route) rargs = *route;
     void *params[] = {&args, &rargs};

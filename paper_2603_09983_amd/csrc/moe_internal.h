@@ -88,6 +88,18 @@ constexpr int kCtrlEpoch = 3;     // routing calls completed on this workspace (
 // wait inside a kernel to run out, so that the failure path can be exercised while every kernel still exits.
 constexpr int kCtrlSpin = 4;      // polls before a wait gives up (0 = the built-in bound)
 constexpr int kCtrlSkew = 5;      // added to the call number that producers stamp their entries with (0)
+constexpr int kCtrlLayout = 6;    // hash of the layout the workspace has been used with since it was initialised (0: none yet)
+constexpr unsigned kErrWait = 1u, kErrLayout = 2u;   // bits of the error word
+
+// The first kernel of a call: the workspace serves one layout between two initialisations (a region that held
+// other data may hold words that look like entries of the current call).
+__device__ static inline void check_layout(unsigned *ctrl, unsigned layout)
+{
+    if (layout == 0u) return;
+    const unsigned old = ctrl[kCtrlLayout];
+    if (old == 0u) ctrl[kCtrlLayout] = layout;
+    else if (old != layout) atomicOr(ctrl + kCtrlError, kErrLayout);
+}
 constexpr int kMaxDevices = 64;   // devices the per-device launch state is kept for
 constexpr int kKindLayer = 9;     // measurement aid: the one-launch layer kernel (MOE_KERNEL_LAYER)
 
@@ -131,12 +143,29 @@ static inline WsLayout ws_layout(int T, int E, int k, int C, int H, int F, int n
     return w;
 }
 
+// Non-zero hash of where the regions of a layout lie: two shapes with the same offsets keep the same kind of
+// entry in every place, and may share a workspace without a new initialisation.
+static inline unsigned layout_hash(const WsLayout &w)
+{
+    const size_t f[] = {w.perm, w.pos, w.slot_count, w.slot_offset, w.active, w.part, w.part_sh, w.act, w.act_sh,
+                        w.o, w.o_sh, w.lists_pub, w.total};
+    unsigned long long h = 1469598103934665603ull;   // FNV-1a over the offsets
+    for (size_t v : f)
+        for (int i = 0; i < 8; ++i) {
+            h ^= (v >> (8 * i)) & 0xffu;
+            h *= 1099511628211ull;
+        }
+    const unsigned r = (unsigned)(h ^ (h >> 32));
+    return r ? r : 1u;
+}
+
 // What the routing kernel should do after the logits are complete.
 struct RouteArgs {
     const void *hidden;        // [T,H] bf16
     const float *router_w;     // [E,H]
     const float *router_bias;  // [E] or null
     int T, H, E, k;
+    unsigned layout;           // hash of the workspace layout of this call (0: not checked)
     int32_t *topk_idx;         // [T,k]
     float *topk_w;             // [T,k]
     float *logits_opt;         // [T,E] or null
@@ -230,7 +259,8 @@ hipError_t launch_resolve(const int32_t *topk_idx, const int32_t *slot_table, in
                           int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
                           unsigned *n_active, hipStream_t s);
 // (epoch: control word stepped by one, so that the FFN kernels of this call have a number of their own)
-hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_t *slot_count,
+// (layout: hash of the workspace layout of this call, checked against the one the workspace has served so far)
+hipError_t launch_lists_from_slots(unsigned layout, const int32_t *slot_idx, int A, int C, int32_t *slot_count,
                                    int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
                                    unsigned *n_active, unsigned *epoch, hipStream_t s);
 // join != null (down kernel only, stream_can_join() true): outputs leave as stamped 64-bit entries
@@ -258,6 +288,12 @@ hipError_t launch_clear_ctrl(void *workspace, size_t bytes, hipStream_t s);
 // a launch that the measurement aid times by the dispatch's own start and end stamps when enabled
 hipError_t launch_timed(const void *fn, dim3 grid, dim3 block, void **params, size_t lds, hipStream_t s, int kind);
 // event bracketing for the measurement aid (no-ops unless enabled)
+// Per-device state of the library (each guarded by one mutex; any host thread may call):
+// compute units of the current device = workgroups of the chip-wide launches (capped at kMaxGroups; 0 and
+// *err when the runtime would not say), ...
+int device_cus(hipError_t *err);
+// ... and the kernels that have been allowed `bytes` of dynamic LDS on the current device (set once each).
+hipError_t allow_full_lds(const void *fn, int bytes = kLdsBytes);
 void prof_begin(int kind, hipStream_t s);
 void prof_end(int kind, hipStream_t s);
 size_t ffn_lds_bytes(int H, int nt);

@@ -39,6 +39,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs a)
     const unsigned *ctrl = a.epoch - kCtrlEpoch;
     const int spin = ctrl[kCtrlSpin] ? (int)ctrl[kCtrlSpin] : kSpinLimit;
     const unsigned wtag = tag + ctrl[kCtrlSkew];   // stamps this call's logits
+    if (b == 0 && tid == 0) check_layout(a.epoch - kCtrlEpoch, a.layout);
 
     // (workgroup 0) the slot table rides along with the first trip to memory
     int tab_v = -1;
@@ -198,9 +199,10 @@ __global__ __launch_bounds__(kRouteThreads) void resolve_kernel(const int32_t *i
                                                                  int32_t *slot_count, int32_t *slot_offset,
                                                                  int32_t *perm, int32_t *pos,
                                                                  int32_t *active_slots, unsigned *n_active,
-                                                                 unsigned *epoch)
+                                                                 unsigned *epoch, unsigned layout)
 {
     extern __shared__ int dyn[];
+    if (epoch && threadIdx.x == 0) check_layout(epoch - kCtrlEpoch, layout);
     PostLds L = carve_lds(dyn, 0, C, A);
     block_post(idx, slot_table, A, E, C, nullptr, slot_idx, miss_list, miss_count, slot_count, slot_offset,
                perm, pos, active_slots, n_active, L.hist_s, L.cnt_s, L.off_s, L.scan_s, L.sidx_s);
@@ -214,42 +216,20 @@ __global__ void clear_ctrl_kernel(unsigned *ws, int words)
 
 }  // namespace
 
-namespace {
-int route_num_cus()
-{
-    static int n_cus = 0;
-    if (n_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            n_cus = n;
-        else
-            n_cus = 256;
-    }
-    return n_cus;
-}
-}  // namespace
 
 size_t route_lds_bytes(int E, int C, int A) { return post_lds_bytes(E, C, A, true); }
 
 hipError_t launch_route(const RouteArgs &a, hipStream_t s)
 {
     size_t lds = post_lds_bytes(a.E, a.slot_table ? a.C : 0, a.T * a.k, true);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)route_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kLdsBytes - 1024);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)resolve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes - 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
-    int grid = route_num_cus();
+    hipError_t e = allow_full_lds((const void *)route_kernel, kLdsBytes - 1024);
+    if (e != hipSuccess) return e;
+    int grid = device_cus(&e);
+    if (e != hipSuccess) return e;
     if (grid > a.T * a.E) grid = a.T * a.E;
     RouteArgs args = a;
     void *params[] = {&args};
-    hipError_t e = launch_timed((const void *)route_kernel, dim3(grid), dim3(kRouteThreads), params, lds, s, 0);
+    e = launch_timed((const void *)route_kernel, dim3(grid), dim3(kRouteThreads), params, lds, s, 0);
     return e != hipSuccess ? e : hipGetLastError();
 }
 
@@ -274,22 +254,28 @@ hipError_t launch_resolve(const int32_t *topk_idx, const int32_t *slot_table, in
                           unsigned *n_active, hipStream_t s)
 {
     size_t lds = post_lds_bytes(0, C, A, false);
+    if (lds > (size_t)kLdsBytes - 1024) return hipErrorInvalidValue;
+    hipError_t e = allow_full_lds((const void *)resolve_kernel, kLdsBytes - 1024);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(kRouteThreads), lds, s, topk_idx, slot_table, A, E, C,
                        slot_idx, miss_list, miss_count, slot_count, slot_offset, perm, pos, active_slots,
-                       n_active, (unsigned *)nullptr);
+                       n_active, (unsigned *)nullptr, 0u);
     return hipGetLastError();
 }
 
-hipError_t launch_lists_from_slots(const int32_t *slot_idx, int A, int C, int32_t *slot_count,
+hipError_t launch_lists_from_slots(unsigned layout, const int32_t *slot_idx, int A, int C, int32_t *slot_count,
                                    int32_t *slot_offset, int32_t *perm, int32_t *pos, int32_t *active_slots,
                                    unsigned *n_active, unsigned *epoch, hipStream_t s)
 {
     size_t lds = post_lds_bytes(0, C, A, false);
+    if (lds > (size_t)kLdsBytes - 1024) return hipErrorInvalidValue;
+    hipError_t e = allow_full_lds((const void *)resolve_kernel, kLdsBytes - 1024);
+    if (e != hipSuccess) return e;
     prof_begin(1, s);
     hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(kRouteThreads), lds, s, (const int32_t *)nullptr,
                        (const int32_t *)nullptr, A, 0, C, const_cast<int32_t *>(slot_idx),
                        (int32_t *)nullptr, (int32_t *)nullptr, slot_count, slot_offset, perm, pos,
-                       active_slots, n_active, epoch);
+                       active_slots, n_active, epoch, layout);
     prof_end(1, s);
     return hipGetLastError();
 }

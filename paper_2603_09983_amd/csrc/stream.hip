@@ -304,6 +304,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         // (two words of the control block that only a test sets: the bound of the polls, and a number added to
         // what producers stamp their entries with, so that the host can make every wait run out)
         rwtag = rtag + (ra.epoch - kCtrlEpoch)[kCtrlSkew];
+        if (b == 0 && tid == 0) check_layout(ra.epoch - kCtrlEpoch, ra.layout);
         if ((ra.epoch - kCtrlEpoch)[kCtrlSpin]) rspin = (int)(ra.epoch - kCtrlEpoch)[kCtrlSpin];
         const size_t n_pub = list_pub_entries(T, ra.k, C);
         // (workgroup 0 gives the call its number in the control block only when every workgroup has read the
@@ -798,20 +799,7 @@ __global__ __launch_bounds__(128) void combine_rows_kernel(CombineArgs a, const 
     }
 }
 
-int g_num_cus = 0;
 
-int num_cus()
-{
-    if (g_num_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            g_num_cus = n;
-        else
-            g_num_cus = 256;
-    }
-    return g_num_cus;
-}
 
 }  // namespace
 
@@ -867,14 +855,10 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join,
     const bool wsplit = !gateup && a.n_shared > 0 && a.KP_sh > 0 && a.K_sh / a.KP_sh != a.K / a.KP;
     const void *fn = join ? join_fns[npi - 1][mode] : fns[gateup ? 1 : 0][npi - 1][mode];
     if (wsplit) fn = join ? wsplit_join_fns[npi - 1][mode] : wsplit_fns[npi - 1][mode];
-    static bool attr_done[72] = {};
-    const int which = (wsplit ? 36 : 0) + (join ? 24 + (npi - 1) * 3 + mode : ((gateup ? 4 : 0) + npi - 1) * 3 + mode);
-    if (!attr_done[which]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_done[which] = true;
-    }
-    const int grid = num_cus();
+    hipError_t e = allow_full_lds(fn);
+    if (e != hipSuccess) return e;
+    const int grid = device_cus(&e);
+    if (e != hipSuccess) return e;
     int tile_i = (int)tile;
     StreamArgs args = a;
     JoinArgs jargs = {};
@@ -898,17 +882,15 @@ hipError_t launch_stream_routed(const StreamArgs &a, const RouteArgs &r, hipStre
     static const void *const fns[4] = {(const void *)routed_stream_kernel<1>, (const void *)routed_stream_kernel<2>,
                                        (const void *)routed_stream_kernel<3>, (const void *)routed_stream_kernel<4>};
     const void *fn = fns[npi - 1];
-    static bool attr_done[4] = {};
-    if (!attr_done[npi - 1]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_done[npi - 1] = true;
-    }
+    hipError_t e = allow_full_lds(fn);
+    if (e != hipSuccess) return e;
+    const int grid = device_cus(&e);
+    if (e != hipSuccess) return e;
     int tile_i = (int)tile;
     StreamArgs args = a;
     RouteArgs rargs = r;
     void *params[] = {&args, &tile_i, &rargs};
-    hipError_t le = launch_timed(fn, dim3(num_cus()), dim3(kThreads), params, lds, s, 2);
+    hipError_t le = launch_timed(fn, dim3(grid), dim3(kThreads), params, lds, s, 2);
     if (le != hipSuccess) return le;
     return hipGetLastError();
 }

@@ -74,9 +74,11 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_route_topk(p + 4, p, None, 4, 64, 8, 2, p, p, None, p, 1 << 20, None) == -3  # alignment
     assert lib.moe_expert_histogram(None, 4, 2, 8, p, None) == -1
     assert lib.moe_expert_histogram(p, 0, 2, 8, p, None) == -2
-    assert lib.moe_grouped_ffn(p, p, p, p, p, p, 4, 72, 64, 2, 4, p, 0, 0, p, 1 << 30, None) == -3   # H % 32
+    assert lib.moe_grouped_ffn(p, p, p, p, p, p, 4, 76, 64, 2, 4, p, 0, 0, p, 1 << 30, None) == -3   # H % 8
+    assert lib.moe_grouped_ffn(p, p, p, p, p, p, 4, 64, 68, 2, 4, p, 0, 0, p, 1 << 30, None) == -3   # F % 8
     assert lib.moe_grouped_ffn(p, p, p, p, p, p, 4, 64, 64, 2, 4, p, 0, 0, p, 64, None) == -4
-    assert lib.moe_grouped_ffn(p, p, p, p, p, p, 4, 8192, 64, 2, 4, p, 0, 0, p, 1 << 30, None) == -2  # H too wide
+    # 40 tokens are beyond the streaming kernels' panels, and the other kernel's LDS does not hold rows this wide
+    assert lib.moe_grouped_ffn(p, p, p, p, p, p, 40, 8192, 64, 2, 4, p, 0, 0, p, 1 << 30, None) == -2
     assert lib.moe_grouped_ffn(p, p, p, None, p, p, 4, 64, 64, 2, 4, p, 0, 0, p, 1 << 30, None) == -1
 
 

@@ -64,6 +64,47 @@ def test_verify_layer_small(G, name):
     G.check_against_oracle(li, buf, tag=name)
 
 
+# sizes that are multiples of 8 only (rows of 16 bytes): ragged contraction blocks and ragged row tiles in the
+# kernel that takes what the streaming kernels do not; and a hidden size beyond what that kernel's LDS holds,
+# which the streaming kernels take in panels
+EDGE_CASES = {
+    "mult8_one_tile": (301, dict(T=5, H=136, E=8, k=2, F=72, C=5, n_shared=1, Fs=40)),
+    "mult8_two_tiles": (302, dict(T=20, H=200, E=8, k=3, F=264, C=6, n_shared=1, Fs=136)),
+    "mult8_H_only": (303, dict(T=7, H=104, E=4, k=2, F=128, C=3)),
+    "mult8_F_only": (304, dict(T=3, H=128, E=4, k=2, F=24, C=4)),
+    "tall_hidden": (305, dict(T=4, H=8192, E=8, k=2, F=128, C=6, n_shared=1, Fs=64)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_CASES))
+def test_verify_layer_edge_sizes(G, name):
+    seed, kw = EDGE_CASES[name]
+    li = layer(seed, **dict(kw))
+    print(f"[case] {name} shape={li.shape}", flush=True)
+    d = G.upload(li)
+    buf = G.run_layer(d)
+    G.check_against_oracle(li, buf, tag=name)
+    buf = G.run_layer(d, buf, out_bf16=False, accumulate=True)      # ... and once more on top of the result
+    y = buf.out.cpu().numpy().astype(np.float64)
+    ref = oracle.layer_from_inputs(li)
+    assert np.max(np.abs(y - 2.0 * ref.y)) <= 2.0 * G.RTOL_RMS * G.rms(ref.y), name
+
+
+def test_sizes_no_kernel_takes_are_refused(G):
+    from paper_2603_09983_amd import binding as B
+    # 40 tokens at a hidden size of 8192: too many tokens for the panelled streaming kernels, too wide for the other
+    sh = B.make_shape(40, 8192, 8, 2, 128, 6)
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    z = torch.zeros(16, dtype=torch.int32, device="cuda")
+    f = torch.zeros(16, dtype=torch.float32, device="cuda")
+    rc = B.moe_verify_layer(sh, f, f, None, z, f, f, f, None, None, None, z, f, z, z, z, z, f, False, False, ws, check=False)
+    assert rc == B.ERR_SHAPE
+    # rows that are not a multiple of 16 bytes
+    rc = B.moe_verify_layer(B.make_shape(4, 132, 8, 2, 128, 6), f, f, None, z, f, f, f, None, None, None, z, f, z, z, z, z,
+                            f, False, False, ws, check=False)
+    assert rc == B.ERR_ALIGN
+
+
 def test_verify_layer_cfg1_tiny(G):
     li = synth.make_layer(synth.RECIPES["cfg1"])
     print(f"[case] cfg1 shape={li.shape}", flush=True)

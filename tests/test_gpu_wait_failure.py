@@ -68,3 +68,33 @@ def test_a_wait_that_runs_out_is_reported_and_recovered_from(case, forms):
             torch.cuda.synchronize()
             assert B.moe_workspace_status(buf.workspace, check=False) == B.OK
             G.check_against_oracle(li, buf, ref, tag=f"{case}/{fname}/after", rms_over_nonzero_rows=True)
+
+
+def test_a_workspace_that_served_another_shape_is_reported():
+    """A workspace serves one layout between two moe_workspace_init calls: the first kernel of a call with
+    another layout says so in the control block, the call marks its results, moe_workspace_status returns
+    MOE_ERR_WORKSPACE, and after a new initialisation the other shape is served."""
+    import gpu_util as G
+    li_a = synth.make_layer(synth.small_recipe("ws_a", 4721, T=6, H=256, E=16, k=4, F=128, C=12, n_shared=1, F_shared=128))
+    li_b = synth.make_layer(synth.small_recipe("ws_b", 4722, T=3, H=256, E=16, k=4, F=128, C=12, n_shared=1, F_shared=128))
+    d_a, d_b = G.upload(li_a), G.upload(li_b)
+    buf_a = B.LayerBuffers.allocate(d_a.shape)
+    for form in (B.LAUNCH_THREE, B.LAUNCH_TWO, B.LAUNCH_ONE):
+        B.moe_workspace_init(buf_a.workspace)
+        assert _call(d_a, buf_a, form) == B.OK
+        torch.cuda.synchronize()
+        assert B.moe_workspace_status(buf_a.workspace, check=False) == B.OK
+        G.check_against_oracle(li_a, buf_a, tag="shape A")
+        # the smaller shape on the same (large enough) workspace, without a new initialisation
+        buf_b = B.LayerBuffers.allocate(d_b.shape)
+        buf_b.workspace = buf_a.workspace
+        assert _call(d_b, buf_b, form) == B.OK
+        torch.cuda.synchronize()
+        assert int(buf_b.miss_count.cpu()[0]) == -1, form
+        assert bool(torch.isnan(buf_b.out).all()), form
+        assert B.moe_workspace_status(buf_a.workspace, check=False) == B.ERR_WORKSPACE
+        B.moe_workspace_init(buf_a.workspace)
+        assert _call(d_b, buf_b, form) == B.OK
+        torch.cuda.synchronize()
+        assert B.moe_workspace_status(buf_a.workspace, check=False) == B.OK
+        G.check_against_oracle(li_b, buf_b, tag="shape B after a new initialisation")

@@ -54,6 +54,7 @@ static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 // so that not all workgroups poll the same lines).  One copy: n_active | slot_count[C] | slot_offset[C] |
 // active_slots[C] | perm[T*k].
 constexpr int kListReplicas = 16;
+constexpr int kLogitReplicas = 16;  // copies of the stamped logits when every workgroup ranks them itself (<= lanes that store)
 constexpr int kMaxGroups = 1024;   // workgroups of that launch (one stamped word each, behind the copies)
 __host__ __device__ static inline size_t list_pub_entries(int T, int k, int C) { return (size_t)1 + 3 * (size_t)C + (size_t)T * k; }
 size_t route_lds_bytes(int E, int C, int A);   // LDS of the routing steps of one batch (route.hip)
@@ -70,6 +71,7 @@ static inline bool use_fused_route(int T, int k, int E, int C, int H, int F, int
 // The region has a fixed size and sits right behind the control block; moe_workspace_init clears
 // it (no stale entry may carry a future tag).
 constexpr int kTagEntries = 65536;   // 512 KB: T*E of the largest routing call that uses them
+static_assert(16 * (2 * kWave) * kLogitReplicas <= kTagEntries, "the copies of the logits of the largest batch that ranks them in every workgroup");
 // Behind them, the same kind of entries for the Top-k ids when more than one workgroup ranks
 // (batches above 16 tokens): T*k of them.
 constexpr int kTagIdxEntries = 4096;   // (at most as many as the routing kernel mirrors in LDS)

@@ -110,8 +110,10 @@ __device__ __forceinline__ float wave_topk_gate_n(int E, int k, int32_t *idx_out
     const float gate = ex / den;
     if (lane < k) {
         if (idx_lds) idx_lds[lane] = my_e;
-        idx_out[lane] = my_e;
-        w_out[lane] = gate;
+        if (idx_out_) {   // (null: the ids are wanted in LDS only)
+            idx_out[lane] = my_e;
+            w_out[lane] = gate;
+        }
     }
     return gate;
 }
@@ -285,9 +287,18 @@ constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before work
 // PUBLISH: every word of the per-slot lists also goes, stamped with the call's number, into each of the
 // kListReplicas copies behind r.lists_pub (entries no expert fills are stamped too, with -1, so that a
 // reader can wait for all of them).
+// What block_post_small found, in registers: thread tid < C holds slot tid's count, offset and place among the
+// active slots (-1: no token); thread tid < T*k holds its assignment's slot and list position (-1: not
+// resident); every thread holds the totals.
+struct SmallLists {
+    int count, offset, active_rank, n_active, n_listed, slot, pos;
+};
+
+// to_memory false: nothing is written to global memory (a workgroup that only wants the lists for itself).
 template <bool PUBLISH>
-__device__ __forceinline__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, int E, int C, const RouteArgs &r,
-                                 lds_i32 *hist_s, lds_i32 *mask_s, lds_i32 *scan_s, lds_i32 *off_s, unsigned tag)
+__device__ __forceinline__ SmallLists block_post_small(lds_i32 *idx_s, lds_i32 *tab_s, int T, int kk, int E, int C, const RouteArgs &r,
+                                 lds_i32 *hist_s, lds_i32 *mask_s, lds_i32 *scan_s, lds_i32 *off_s, unsigned tag,
+                                 bool to_memory = true)
 {
     auto publish = [&](int word, int value) {
         if (!PUBLISH) return;
@@ -309,7 +320,7 @@ __device__ __forceinline__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s,
         if (c >= 0)
             __hip_atomic_fetch_or(&mask_s[c * NW + (tok >> 5)], 1 << (tok & 31), __ATOMIC_RELAXED,
                                   __HIP_MEMORY_SCOPE_WORKGROUP);
-        r.slot_idx[tid] = c;
+        if (to_memory) r.slot_idx[tid] = c;
     }
     const bool miss = valid && c < 0;
     const unsigned long long bal = __ballot(miss);
@@ -338,9 +349,11 @@ __device__ __forceinline__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s,
             if (i < w) wave_base += v;
             total += v;
         }
-        if (miss) r.miss_list[wave_base + before] = tid;
-        if (tid == 0) *r.miss_count = total;
-        if (tid < E) r.hist[tid] = hist_s[tid];
+        if (to_memory) {
+            if (miss) r.miss_list[wave_base + before] = tid;
+            if (tid == 0) *r.miss_count = total;
+            if (tid < E) r.hist[tid] = hist_s[tid];
+        }
     }
     __syncthreads();
     int base_o = 0, base_a = 0, tot_o = 0, tot_a = 0;
@@ -353,20 +366,28 @@ __device__ __forceinline__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s,
         tot_o += vo;
         tot_a += va;
     }
+    SmallLists out = {0, 0, -1, tot_a, tot_o, c, -1};
     if (tid < C) {
         const int off = base_o + inc_o - cntv, na = base_a + inc_a - (cntv > 0 ? 1 : 0);
         off_s[tid] = off;
-        r.slot_count[tid] = cntv;
-        r.slot_offset[tid] = off;
-        if (cntv > 0) r.active_slots[na] = tid;
+        out.count = cntv;
+        out.offset = off;
+        out.active_rank = cntv > 0 ? na : -1;
+        if (to_memory) {
+            r.slot_count[tid] = cntv;
+            r.slot_offset[tid] = off;
+            if (cntv > 0) r.active_slots[na] = tid;
+        }
         publish(1 + tid, cntv);
         publish(1 + C + tid, off);
         if (cntv > 0) publish(1 + 2 * C + na, tid);
         if (tid >= tot_a) publish(1 + 2 * C + tid, -1);
     }
     if (tid == 0) {
-        r.slot_offset[C] = tot_o;
-        *r.n_active = (unsigned)tot_a;
+        if (to_memory) {
+            r.slot_offset[C] = tot_o;
+            *r.n_active = (unsigned)tot_a;
+        }
         publish(0, tot_a);
     }
     __syncthreads();
@@ -376,12 +397,14 @@ __device__ __forceinline__ void block_post_small(lds_i32 *idx_s, lds_i32 *tab_s,
         if (c >= 0) {
             p = off_s[c] + __popc((unsigned)mask_s[c * NW + (tok >> 5)] & ((1u << (tok & 31)) - 1u));
             for (int wd = 0; wd < (tok >> 5); ++wd) p += __popc((unsigned)mask_s[c * NW + wd]);
-            r.perm[p] = tid;
+            if (to_memory) r.perm[p] = tid;
             publish(1 + 3 * C + p, tid);
         }
-        r.pos[tid] = p;
+        if (to_memory) r.pos[tid] = p;
+        out.pos = p;
         if (tid >= tot_o) publish(1 + 3 * C + tid, -1);
     }
+    return out;
 }
 
 }  // namespace

@@ -290,15 +290,58 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         }
     };
 
-    // FUSED: the routing steps come first, while nothing of the streaming state is alive yet (they need
-    // many registers of their own); workgroups other than 0 then request their shared expert's first tile and
-    // wait for the lists with that tile in flight.
+    u32x4 bx[NG][kPieces];
+    int bx_key = -1, bx_panel = -1;   // expert (and panel) whose FIRST token pass the registers hold
+
+    // B operand of this wavefront's column blocks for the token pass starting at token tok0:
+    // token tok0 + 16*gr + n sits on column n of group gr.  Drains every load in flight (rare path), unless
+    // told to leave the wait to the caller.
+    auto load_bx = [&](int tok0, bool wait = true) {
+        const int nkb = c_rs / 64;
+        const uint16_t *bbase = a.bsrc;
+        if (!GATEUP && csh) bbase = a.bsrc_sh;
+#pragma unroll
+        for (int gr = 0; gr < NG; ++gr) {
+            const int tk = tok0 + 16 * gr + n;
+            int boff = -1;
+            if (tk < (ALLTOK ? a.T : cm))
+                boff = (cbrow0 >= 0 ? cbrow0 + tk : perm_s[corow0 + tk]) * cK + cpan * (c_rs / 2);
+#pragma unroll
+            for (int j = 0; j < kPieces; ++j) {
+                int kb = w + kWaves * j;
+                bx[gr][j] = (u32x4){0u, 0u, 0u, 0u};
+                if (kb < nkb && boff >= 0) bx[gr][j] = *(const u32x4 *)(bbase + (unsigned)(boff + kb * 32 + g * 8));
+            }
+        }
+        if (wait) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    };
+    // A shared expert's item needs nothing from the routing step, not even for its B operand (every token,
+    // in token order): tile and operand are requested here, and are there by the time the lists are.
+    // (FUSED: after the dot products of the routing step have their own loads on the way, not before: behind a
+    // tile per workgroup those loads, which everything else waits for, take twice as long)
+    bool bx_early = false;
+    auto first_shared_item = [&]() {
+        if (s_cnt == 0) return;
+        const int e = s_start / tiles_sh;
+        prod_set(true, e, s_start - e * tiles_sh);
+        cons_set(true, e, s_start - e * tiles_sh);
+        pvalid = true;
+        issue(0);
+        load_bx(0, false);
+        bx_key = ckey;
+        bx_panel = cpan;
+        bx_early = true;
+    };
+    if (!FUSED) first_shared_item();
+    // FUSED: steps 1-3 of the layer inside this launch (Sec. 2.2, 2.3, App. D).  Every workgroup computes its
+    // share of the T*E dot products and stores each logit, stamped with the call's number, into kLogitReplicas
+    // copies; then EVERY workgroup waits for all logits in one of the copies, ranks them and builds the per-slot
+    // lists for itself in LDS (the same arithmetic on the same numbers everywhere; workgroup 0 also writes the
+    // step outputs to memory).  One hand-over through memory instead of two: the lists are not passed on.
     unsigned rtag = 0, rwtag = 0;
     int rspin = kSpinLimit;
+    int n_act = 0;
     if (FUSED) {
-        // ---- steps 1-3 inside this launch (Sec. 2.2, 2.3, App. D), as in the routing kernel ----
-        // every workgroup: its share of the T*E dot products, one per wavefront, each logit stored with the
-        // call's number as one 64-bit word
         const int T = ra.T, H = ra.H, E = ra.E, TE = T * E, A = T * ra.k, C = ra.C;
         rtag = *ra.epoch + 1u;
         // (two words of the control block that only a test sets: the bound of the polls, and a number added to
@@ -313,7 +356,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         if (tid == 0)
             __hip_atomic_store(seen + b, ((unsigned long long)rtag << 32) | 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int tab_v = -1;
-        if (b == 0 && tid < E) tab_v = ra.slot_table[tid];
+        if (tid < E) tab_v = ra.slot_table[tid];
         const uint16_t *x = (const uint16_t *)ra.hidden;
         for (int q = b + w * G; q < TE; q += G * kWaves) {
             const int t = q / E, e = q - t * E;
@@ -330,15 +373,17 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
 #pragma unroll
             for (int m = kWave / 2; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, kWave);
             dot += bias;
-            if (lane == 0) {
-                __hip_atomic_store(ra.tagged_logits + q, ((unsigned long long)rwtag << 32) | __float_as_uint(dot),
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (ra.logits_opt) ra.logits_opt[q] = dot;
-            }
+            // lane r: the copy that the workgroups with b % kLogitReplicas == r read
+            if (lane < kLogitReplicas)
+                __hip_atomic_store(ra.tagged_logits + (size_t)lane * TE + q,
+                                   ((unsigned long long)rwtag << 32) | __float_as_uint(dot), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0 && ra.logits_opt) ra.logits_opt[q] = dot;
         }
-        if (b == 0) {
-            // workgroup 0: one wavefront per token ranks its logits; then histogram, slot lookup, miss list and
-            // per-slot lists out of LDS (which nothing else uses yet), every word of the lists published
+        first_shared_item();
+        {
+            // one wavefront per token ranks its logits; then histogram, slot lookup, miss list and per-slot lists
+            // out of LDS (which nothing else uses yet: the first tile is still on its way)
             PostLds L = carve_lds((int *)lds, E, C, A);
             if (tid < E) {
                 L.tab_s[tid] = tab_v;
@@ -348,7 +393,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
             lds_f32 *lg = L.lg_s + w * lg_stride(E);
             if (w < T) {
                 const int t = w;
-                const unsigned long long *src = ra.tagged_logits + (size_t)t * E;
+                const unsigned long long *src = ra.tagged_logits + (size_t)(b % kLogitReplicas) * TE + (size_t)t * E;
                 for (int e0 = 0; e0 < E; e0 += kWave) {
                     const int e = e0 + lane;
                     unsigned long long v = (unsigned long long)rtag << 32;
@@ -360,7 +405,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                             if (lane == 0) atomicOr(ra.error_flag, 1u);
                             break;
                         }
-                        __builtin_amdgcn_s_sleep(1);
+                        __builtin_amdgcn_s_sleep(2);
                     }
                     if (e < E) {
                         const float f = __uint_as_float((unsigned)v);
@@ -370,75 +415,46 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                 __builtin_amdgcn_wave_barrier();
                 // (up to 128 experts here: the ranking of more needs so many registers that the whole
                 // kernel would be launched with scratch memory; those batches keep the routing kernel)
+                int32_t *const idx_out = b == 0 ? ra.topk_idx + (size_t)t * ra.k : nullptr;
+                float *const w_out = b == 0 ? ra.topk_w + (size_t)t * ra.k : nullptr;
                 if (E <= kWave)
-                    wave_topk_gate_n<1>(E, ra.k, ra.topk_idx + (size_t)t * ra.k, L.idx_s + t * ra.k,
-                                        ra.topk_w + (size_t)t * ra.k, lg);
+                    wave_topk_gate_n<1>(E, ra.k, idx_out, L.idx_s + t * ra.k, w_out, lg);
                 else
-                    wave_topk_gate_n<2>(E, ra.k, ra.topk_idx + (size_t)t * ra.k, L.idx_s + t * ra.k,
-                                        ra.topk_w + (size_t)t * ra.k, lg);
+                    wave_topk_gate_n<2>(E, ra.k, idx_out, L.idx_s + t * ra.k, w_out, lg);
             }
             __syncthreads();
-            block_post_small<true>(L.idx_s, L.tab_s, T, ra.k, E, C, ra, L.hist_s, L.cnt_s, L.scan_s, L.off_s, rwtag);
-            for (int i = tid; i < G; i += kThreads) {
-                int polls = 0;
-                while ((unsigned)(__hip_atomic_load(seen + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != rtag) {
-                    if (++polls > rspin) {
-                        atomicOr(ra.error_flag, 1u);
-                        break;
+            const SmallLists sl = block_post_small<false>(L.idx_s, L.tab_s, T, ra.k, E, C, ra, L.hist_s, L.cnt_s, L.scan_s,
+                                                          L.off_s, rwtag, b == 0);
+            __syncthreads();   // (the lists' places below may lie where the ranking kept its own data)
+            if (tid < C) {
+                count_s[tid] = sl.count;
+                offset_s[tid] = sl.offset;
+                if (sl.active_rank >= 0) active_s[sl.active_rank] = tid;
+                if (tid >= sl.n_active) active_s[tid] = 0;       // (never used; stay inside the pool)
+            }
+            if (tid < A) {
+                if (sl.pos >= 0) perm_s[sl.pos] = tid / ra.k;    // token of each list entry
+                if (tid >= sl.n_listed) perm_s[tid] = 0;
+            }
+            n_act = sl.n_active;
+            if (b == 0) {
+                for (int i = tid; i < G; i += kThreads) {
+                    int polls = 0;
+                    while ((unsigned)(__hip_atomic_load(seen + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != rtag) {
+                        if (++polls > rspin) {
+                            atomicOr(ra.error_flag, 1u);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(2);
                     }
-                    __builtin_amdgcn_s_sleep(2);
                 }
             }
-            __syncthreads();   // (also: the LDS used above is free again)
-            if (tid == 0) *ra.epoch = rtag;
+            __syncthreads();
+            if (b == 0 && tid == 0) *ra.epoch = rtag;
         }
     }
-    if (s_cnt > 0) {
-        const int e = s_start / tiles_sh;
-        prod_set(true, e, s_start - e * tiles_sh);
-        cons_set(true, e, s_start - e * tiles_sh);
-        pvalid = true;
-        issue(0);
-    }
-    int n_act;
     if (FUSED) {
-        // every workgroup: the lists, from one of the published copies.  One lane watches the first word,
-        // gently (255 workgroups asking for all words all the time would be a load of its own on the few
-        // memory channels the copies live in); once it is there the workgroup reads them all.
-        const int C = ra.C;
-        const size_t n_pub = list_pub_entries(ra.T, ra.k, C);
-        const unsigned long long *pub = ra.lists_pub + (size_t)(b % kListReplicas) * n_pub;
-        if (tid == 0 && b != 0) {
-            int polls = 0;
-            while ((unsigned)(__hip_atomic_load(pub, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) != rtag) {
-                if (++polls > rspin) break;   // (the loop below reports it)
-                __builtin_amdgcn_s_sleep(16);
-            }
-        }
-        __syncthreads();
-        for (int i = tid; i < (int)n_pub; i += kThreads) {
-            unsigned long long v = 0;
-            int polls = 0;
-            for (;;) {
-                v = __hip_atomic_load(pub + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((unsigned)(v >> 32) == rtag) break;
-                if (++polls > rspin) {
-                    atomicOr(ra.error_flag, 1u);
-                    v = 0;   // (stay inside every array below)
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(8);
-            }
-            const int val = (int)(unsigned)v;
-            if (i == 0) odesc_s[0] = val;                                   // n_active (read back below)
-            else if (i <= C) count_s[i - 1] = val;
-            else if (i <= 2 * C) offset_s[i - 1 - C] = val;
-            else if (i <= 3 * C) active_s[i - 1 - 2 * C] = val < 0 ? 0 : val;
-            else perm_s[i - 1 - 3 * C] = (val < 0 ? 0 : val) / a.k;         // token of each list entry
-        }
-        __syncthreads();
-        n_act = odesc_s[0];
-        n_act = n_act < 0 ? 0 : n_act > C ? C : n_act;
+        // (the lists are in LDS already)
     } else {
         // one trip to memory for everything the routing step left behind
         for (int i = tid; i < a.C; i += kThreads) {
@@ -558,32 +574,9 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         issue(0);
     }
 
-    u32x4 bx[NG][kPieces];
-    int bx_key = -1, bx_panel = -1;   // expert (and panel) whose FIRST token pass the registers hold
     f32x4 acc[NG];
     int orec = 0, flushed = 0;   // output records written to / flushed from the LDS output buffer
 
-    // B operand of this wavefront's column blocks for the token pass starting at token tok0:
-    // token tok0 + 16*gr + n sits on column n of group gr.  Drains every load in flight (rare path).
-    auto load_bx = [&](int tok0) {
-        const int nkb = c_rs / 64;
-        const uint16_t *bbase = a.bsrc;
-        if (!GATEUP && csh) bbase = a.bsrc_sh;
-#pragma unroll
-        for (int gr = 0; gr < NG; ++gr) {
-            const int tk = tok0 + 16 * gr + n;
-            int boff = -1;
-            if (tk < (ALLTOK ? a.T : cm))
-                boff = (cbrow0 >= 0 ? cbrow0 + tk : perm_s[corow0 + tk]) * cK + cpan * (c_rs / 2);
-#pragma unroll
-            for (int j = 0; j < kPieces; ++j) {
-                int kb = w + kWaves * j;
-                bx[gr][j] = (u32x4){0u, 0u, 0u, 0u};
-                if (kb < nkb && boff >= 0) bx[gr][j] = *(const u32x4 *)(bbase + (unsigned)(boff + kb * 32 + g * 8));
-            }
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    };
     auto multiply = [&]() {
         const int nkb = c_rs / 64;
 #pragma unroll
@@ -713,15 +706,21 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         }
     };
 
-    // The first B operand is fetched before the second tile is requested: its wait drains every
-    // load in flight, and here that is only the first tile; inside step(0) it would hold back the
-    // request for the third tile until the second had arrived.
-    load_bx(0);
-    bx_key = ckey;
-    bx_panel = cpan;
+    // The first B operand and the second tile are requested together, as soon as the lists say where they
+    // are; the wait that follows leaves exactly the second tile's NPI loads in flight (loads complete in
+    // order: the first tile and the B operand are there when it ends).  Waiting for the B operand before
+    // the second tile is requested would leave the memory system with one tile per workgroup for the
+    // two to three microseconds of that round trip.
+    if (!bx_early) {
+        load_bx(0, false);
+        bx_key = ckey;
+        bx_panel = cpan;
+    }
     prod_advance();
     issue(1);
     prod_advance();
+    static_assert(NPI >= 1 && NPI <= 4, "the wait below names the number of loads of one tile");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | NPI);   // vmcnt(NPI)
 
     // (first tile peeled off so that the loop is always entered in the same state: the compiler then
     // counts the loads in flight exactly and each park waits for its own tile only)

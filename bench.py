@@ -44,7 +44,7 @@ HBM_PEAK_GBS = 8000.0
 # --stats; FETCH_SIZE and WRITE_SIZE from two --pmc runs with their calibration factor), as `key = value`
 # lines, with the name of the kernel and a hash of the kernel sources they were recorded for
 RECORDED = os.path.join(ROOT, "profiles", "recorded_counters_cfg2.txt")
-KERNEL_SOURCES = ("stream.hip", "stream_device.h", "route_device.h", "layer.hip", "moe_internal.h")
+KERNEL_SOURCES = ("stream.hip", "route_device.h", "route.hip", "moe_internal.h")
 
 
 def sources_hash() -> str:

@@ -16,7 +16,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe_spac.so")
 LIB_TRACE = os.path.join(HERE, "libmoe_spac_trace.so")   # same sources with the timeline stamps compiled in
 SOURCES = ["api.hip", "route.hip", "ffn.hip", "stream.hip", "layer.hip", "estimator.hip", "balancer.hip", "cache.hip"]
-HEADERS = [os.path.join(CSRC, h) for h in ("moe_internal.h", "route_device.h", "stream_device.h")] + \
+HEADERS = [os.path.join(CSRC, h) for h in ("moe_internal.h", "route_device.h")] + \
           [os.path.join(ROOT, "include", "moe_spac.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 instruction selection is switched off for every kernel of this library

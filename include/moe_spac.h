@@ -33,7 +33,11 @@
  *     workspace holds state between calls (a call counter and regions whose
  *     entries are stamped with it): initialise it with moe_workspace_init
  *     over its full size, and again after anything else wrote into it or
- *     before using it with a different shape.
+ *     before using it with a different shape.  moe_grouped_ffn lays the
+ *     workspace out differently from moe_verify_layer with the same sizes
+ *     (it has no shared experts): initialise between the two as well.  A
+ *     call that finds the workspace laid out for something else marks its
+ *     results and moe_workspace_status returns MOE_ERR_WORKSPACE.
  *   - The routing kernel and the down kernel hand results from one workgroup
  *     to another inside a launch (stamped entries in the workspace, bounded
  *     polling).  They are sized to occupy the whole device.  Layer calls on

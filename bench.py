@@ -286,12 +286,38 @@ def main():
             healthy(self.buf.workspace, what)
             return t1 - t0
 
-        def row(self, form, steps, warmup, what):
+        def chain(self, form, reps, warmup, what):
+            """One pass over all layers of the workload, back to back, `reps` times, each pass between two HIP
+            events on the launch stream: median, 10th and 90th percentile of the time per layer."""
+            n = len(self.layers)
+            for r in range(warmup):
+                for i in range(n):
+                    self.step(i, form)
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            torch.cuda.synchronize()
+            for r in range(reps):
+                ev[r][0].record()
+                for i in range(n):
+                    self.step(i, form)
+                ev[r][1].record()
+            torch.cuda.synchronize()
+            healthy(self.buf.workspace, what)
+            us = np.array([a.elapsed_time(b) for a, b in ev]) * 1e3 / n
+            return {"passes": reps, "warmup_passes": warmup, "layers_per_pass": n,
+                    "us_per_layer_median": round(float(np.median(us)), 2),
+                    "us_per_layer_p10": round(float(np.percentile(us, 10)), 2),
+                    "us_per_layer_p90": round(float(np.percentile(us, 90)), 2),
+                    "timer": "one HIP-event pair around each pass"}
+
+        def row(self, form, steps, warmup, what, chain_reps=0):
             secs = self.timed(form, steps, warmup, what)
             gbs = self.bytes_of(steps) / secs / 1e9
-            return {"us_per_layer": round(secs * 1e6 / steps, 2), "GBs": round(gbs, 1),
-                    "whole_layer_frac": round(gbs / HBM_PEAK_GBS, 4),
-                    "mean_weight_bytes_per_layer": int(np.mean(self.layer_bytes)), "steps": steps, "warmup": warmup}
+            out = {"us_per_layer": round(secs * 1e6 / steps, 2), "GBs": round(gbs, 1),
+                   "whole_layer_frac": round(gbs / HBM_PEAK_GBS, 4),
+                   "mean_weight_bytes_per_layer": int(np.mean(self.layer_bytes)), "steps": steps, "warmup": warmup}
+            if chain_reps:
+                out["chain"] = self.chain(form, chain_reps, 20, what + ", pass by pass")
+            return out
 
     wl = Workload(args.workload, args.copies)
     layers, dev_layers, shape, buf, desc, layer_bytes = wl.layers, wl.dev, wl.shape, wl.buf, wl.desc, wl.layer_bytes
@@ -413,12 +439,14 @@ def main():
                             "warmup": args.warmup}}
     if not args.no_rows and args.workload == "cfg2" and not args.graph:
         sweep = Workload("cfg5_T9", 0, keep_host_weights=False)
-        rows["cfg5_T9"] = sweep.row(form, 240, 48, "cfg5 T=9")
+        rows[args.workload]["chain"] = wl.chain(form, 100, 20, "cfg2, pass by pass")
+        rows["cfg5_T9"] = sweep.row(form, 240, 48, "cfg5 T=9", chain_reps=100)
         sweep5 = sweep.with_tokens(5)
-        rows["cfg5_T5"] = sweep5.row(form, 240, 48, "cfg5 T=5")
+        rows["cfg5_T5"] = sweep5.row(form, 240, 48, "cfg5 T=5", chain_reps=100)
         del sweep, sweep5
         torch.cuda.empty_cache()
-    rows["timer"] = "host wall clock between two device synchronisations around the steps, inputs resident"
+    rows["timer"] = ("us_per_layer: host wall clock between two device synchronisations around the steps, inputs resident; "
+                     "chain: HIP events around each pass over the workload's layers, 20 warm-up passes + 100 timed ones")
 
     # NEXT row: the Speculative Utility Estimator consuming the histograms of 24 layers per inference
     # step (one launch for all layers); frequencies are synthetic histograms of T*k assignments.

@@ -85,7 +85,7 @@ typedef struct moe_shape {
 enum {
     MOE_LAUNCH_AUTO = 0,
     MOE_LAUNCH_THREE = 1,         /* routing | gate/up stream | down stream + final sum (+ a combine launch above 32 tokens) */
-    MOE_LAUNCH_TWO = 2,           /* routing steps at the head of the gate/up kernel: T <= 16, E <= 128 */
+    MOE_LAUNCH_TWO = 2,           /* routing steps at the head of the gate/up kernel: T <= 32, E <= 128 */
     MOE_LAUNCH_ONE = 3,           /* routing, gate/up, down and final sum as one kernel: T <= 16, E <= 128, H, F multiples of 64 */
     MOE_LAUNCH_ROUTE_PLUS_ONE = 4 /* routing kernel, then gate/up, down and final sum as one kernel: T <= 16 */
 };
@@ -172,7 +172,7 @@ int moe_grouped_ffn(const void *hidden, const float *topk_w, const int32_t *slot
 
 /* Steps 1-4 for one verification batch on `stream`, in the launch form that
  * shape->launch_form names (MOE_LAUNCH_AUTO: two launches, the routing steps
- * at the head of the gate/up kernel, for batches of up to 16 tokens and 128
+ * at the head of the gate/up kernel, for batches of up to 32 tokens and 128
  * experts with a non-empty pool; else three launches; four above 32 tokens).
  * Every form computes the same outputs to the same bar.
  * The workspace carries state from call to call (see moe_workspace_init): it

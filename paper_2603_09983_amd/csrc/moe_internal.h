@@ -60,7 +60,7 @@ __host__ __device__ static inline size_t list_pub_entries(int T, int k, int C) {
 size_t route_lds_bytes(int E, int C, int A);   // LDS of the routing steps of one batch (route.hip)
 static inline bool use_fused_route(int T, int k, int E, int C, int H, int F, int n_shared, int F_shared)
 {
-    if (T > 16 || E < 1 || E > 2 * kWave || (size_t)T * k > 1024 || C < 1 || C > kMaxC) return false;
+    if (T > 32 || E < 1 || E > 2 * kWave || (size_t)T * k > 1024 || C < 1 || C > kMaxC) return false;
     if (!use_stream_kernels(T, k, C, H, F, n_shared, F_shared)) return false;
     return route_lds_bytes(E, C, T * k) <= (size_t)kLdsBytes - 1024;
 }
@@ -71,7 +71,7 @@ static inline bool use_fused_route(int T, int k, int E, int C, int H, int F, int
 // The region has a fixed size and sits right behind the control block; moe_workspace_init clears
 // it (no stale entry may carry a future tag).
 constexpr int kTagEntries = 65536;   // 512 KB: T*E of the largest routing call that uses them
-static_assert(16 * (2 * kWave) * kLogitReplicas <= kTagEntries, "the copies of the logits of the largest batch that ranks them in every workgroup");
+static_assert(32 * (2 * kWave) * kLogitReplicas <= kTagEntries, "the copies of the logits of the largest batch that ranks them in every workgroup");
 // Behind them, the same kind of entries for the Top-k ids when more than one workgroup ranks
 // (batches above 16 tokens): T*k of them.
 constexpr int kTagIdxEntries = 4096;   // (at most as many as the routing kernel mirrors in LDS)

@@ -103,7 +103,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
                                             const RouteArgs &ra)
 {
     static_assert(!WSPLIT || !GATEUP, "gate/up items all have the panels of the hidden size");
-    static_assert(!FUSED || (GATEUP && MODE == 0 && !JOIN && !WSPLIT), "the routing steps ride on the small-batch gate/up kernel");
+    static_assert(!FUSED || (GATEUP && MODE <= 1 && !JOIN && !WSPLIT), "the routing steps ride on the gate/up kernels of up to 32 tokens");
     static_assert(!JOIN || (!GATEUP && MODE < 2), "the join rides on the down kernel of batches up to 32 tokens");
     constexpr int NG = MODE == 0 ? 1 : 2;   // token groups of 16 multiplied per pass
     constexpr bool MULTIPASS = MODE == 2;
@@ -391,8 +391,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
             }
             for (int i = tid; i < C * ((T + 31) >> 5); i += kThreads) L.cnt_s[i] = 0;
             lds_f32 *lg = L.lg_s + w * lg_stride(E);
-            if (w < T) {
-                const int t = w;
+            for (int t = w; t < T; t += kWaves) {   // (one token per wavefront up to 16 tokens, two up to 32)
                 const unsigned long long *src = ra.tagged_logits + (size_t)(b % kLogitReplicas) * TE + (size_t)t * E;
                 for (int e0 = 0; e0 < E; e0 += kWave) {
                     const int e = e0 + lane;
@@ -755,11 +754,11 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(StreamArgs a, int tile
 
 // The small-batch gate/up kernel with steps 1-3 of the layer in front of it (one launch less per layer, and the
 // shared experts' weights stream while the routing runs).
-template <int NPI>
+template <int NPI, int MODE>
 __global__ __launch_bounds__(kThreads) void routed_stream_kernel(StreamArgs a, int tile_lds_bytes, RouteArgs ra)
 {
     const JoinArgs none = {};
-    stream_body<true, NPI, 0, false, false, true>(a, tile_lds_bytes, none, ra);
+    stream_body<true, NPI, MODE, false, false, true>(a, tile_lds_bytes, none, ra);
 }
 
 // out[t,:] (+)= sum_j w[t,j] * o[pos[t,j],:] + sum_i o_sh[i,t,:], in a fixed order
@@ -870,7 +869,7 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join,
 
 hipError_t launch_stream_routed(const StreamArgs &a, const RouteArgs &r, hipStream_t s)
 {
-    if (!r.lists_pub || a.T > 16) return hipErrorInvalidValue;
+    if (!r.lists_pub || a.T > 32) return hipErrorInvalidValue;
     const int kp_max = a.KP > a.KP_sh ? a.KP : a.KP_sh;
     const size_t tile = (size_t)16 * (2 * kp_max + kRowPad);
     size_t lds = stream_lds_need(kp_max, a.T, a.k, a.C, true);
@@ -878,9 +877,12 @@ hipError_t launch_stream_routed(const StreamArgs &a, const RouteArgs &r, hipStre
     lds = lds > lds_route ? lds : lds_route;
     if (lds > (size_t)kLdsBytes) return hipErrorInvalidValue;
     const int npi = (kp_max / 32 + kWaves - 1) / kWaves;
-    static const void *const fns[4] = {(const void *)routed_stream_kernel<1>, (const void *)routed_stream_kernel<2>,
-                                       (const void *)routed_stream_kernel<3>, (const void *)routed_stream_kernel<4>};
-    const void *fn = fns[npi - 1];
+    static const void *const fns[2][4] = {
+        {(const void *)routed_stream_kernel<1, 0>, (const void *)routed_stream_kernel<2, 0>,
+         (const void *)routed_stream_kernel<3, 0>, (const void *)routed_stream_kernel<4, 0>},
+        {(const void *)routed_stream_kernel<1, 1>, (const void *)routed_stream_kernel<2, 1>,
+         (const void *)routed_stream_kernel<3, 1>, (const void *)routed_stream_kernel<4, 1>}};
+    const void *fn = fns[a.T > 16 ? 1 : 0][npi - 1];
     hipError_t e = allow_full_lds(fn);
     if (e != hipSuccess) return e;
     const int grid = device_cus(&e);

@@ -1,7 +1,7 @@
 """Every launch form of moe_verify_layer against the oracle: three launches, two (routing inside the gate/up
 kernel), one (routing, gate/up, down and the final sum in one kernel) and routing kernel + one-launch FFN.
 Same outputs to the same bar in every form, at the named workloads' full sizes and at the corners of the
-one-launch kernel (one token, sixteen tokens, no shared expert, several shared experts, several contraction
+one-launch kernel and of the two-launch form (one token, sixteen tokens, 17-32 tokens, no shared expert, several shared experts, several contraction
 panels, empty cache share, bf16 output, accumulation, repeated calls on one workspace)."""
 import numpy as np
 import pytest
@@ -31,12 +31,16 @@ def _case(name):
         "all_miss": dict(T=6, H=128, E=16, k=2, F=64, C=1, n_shared=1, F_shared=64),
         "k_equals_e": dict(T=3, H=64, E=4, k=4, F=64, C=4),
         "e128": dict(T=9, H=256, E=128, k=8, F=128, C=64, hidden="unit"),
+        # 17-32 tokens: two token groups per pass; the two-launch form ranks two tokens per wavefront
+        "twenty_four": dict(T=24, H=512, E=64, k=6, F=384, C=40, n_shared=1, F_shared=128, hidden="unit"),
+        "thirty_two_e128": dict(T=32, H=256, E=128, k=8, F=128, C=96, hidden="unit"),
     }[name]
     return synth.make_layer(synth.small_recipe(name, 8800 + len(name), **kw))
 
 
-CASES = ["cfg1", "cfg2", "cfg3", "cfg4_c4", "sweep1_11", "sweep5_0", "sweep9_23", "one_token", "sixteen_tokens",
-         "three_shared", "panels", "wide_shared_down", "all_miss", "k_equals_e", "e128"]
+CASES = ["cfg1", "cfg2", "cfg3", "cfg4_c4", "sweep1_11", "sweep5_0", "sweep9_23", "sweep17_11", "one_token",
+         "sixteen_tokens", "three_shared", "panels", "wide_shared_down", "all_miss", "k_equals_e", "e128", "twenty_four",
+         "thirty_two_e128"]
 
 
 @pytest.mark.parametrize("case", CASES)
@@ -72,5 +76,7 @@ def test_launch_forms_agree_with_the_oracle(case):
         assert np.max(np.abs(y - want)) <= tol, (case, fname, "bf16 accumulate")
         ran.append(fname)
     assert "three" in ran
+    if li.shape.T <= 32 and li.shape.E <= 128 and li.shape.C >= 1 and li.shape.H % 64 == 0 and li.shape.F % 64 == 0:
+        assert "two" in ran, (case, ran)
     if li.shape.T <= 16 and li.shape.E <= 128 and li.shape.C >= 1 and li.shape.H % 64 == 0 and li.shape.F % 64 == 0:
         assert "one" in ran and "route+one" in ran, (case, ran)

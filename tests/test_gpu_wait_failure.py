@@ -26,6 +26,7 @@ def _call(d, buf, form, check=True):
 @pytest.mark.parametrize("case,forms", [
     ("small", ("three", "two", "one", "route+one")),   # T <= 32: the final sum waits inside the down kernel
     ("cfg2", ("three", "two", "one", "route+one")),
+    ("two_groups", ("three", "two")),                  # 17-32 tokens: two tokens per wavefront in the routing steps
     ("wide", ("three",)),                              # T > 32: a kernel of its own does the final sum
 ])
 def test_a_wait_that_runs_out_is_reported_and_recovered_from(case, forms):
@@ -34,6 +35,9 @@ def test_a_wait_that_runs_out_is_reported_and_recovered_from(case, forms):
         li = synth.make_layer(synth.RECIPES["cfg2"], experts="resident")
     elif case == "small":
         li = synth.make_layer(synth.small_recipe("wait_small", 4711, T=6, H=256, E=16, k=4, F=128, C=12,
+                                                 n_shared=1, F_shared=128))
+    elif case == "two_groups":
+        li = synth.make_layer(synth.small_recipe("wait_two_groups", 4713, T=24, H=256, E=16, k=4, F=128, C=12,
                                                  n_shared=1, F_shared=128))
     else:
         li = synth.make_layer(synth.small_recipe("wait_wide", 4712, T=40, H=256, E=16, k=4, F=128, C=12,

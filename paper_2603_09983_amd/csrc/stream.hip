@@ -508,7 +508,9 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         float *val_s = (float *)tile_s;   // [token][column of the strip][source]; the tile buffer is free by now
         float *gw_s = red_s;              // gate weights, on their way while the entries are waited for
         for (int i = tid; i < a.T * a.k; i += kThreads) gw_s[i] = jn.topk_w[i];
-        int *gave_up_s = odesc_s;         // (the result descriptors are done with) set by a thread whose wait ran out
+        // set by a thread whose wait ran out: the last word of the partial-sum buffer, which nobody reads any more
+        // (not a word of the result descriptors: other wavefronts may still be storing the last batch from them)
+        int *gave_up_s = (int *)red_s + NG * kWaves * kWave * 4 - 1;
         if (tid == 0) *gave_up_s = 0;
         for (int u = b; u < a.R / 8; u += G) {
             __syncthreads();
@@ -803,10 +805,11 @@ __global__ __launch_bounds__(128) void combine_rows_kernel(CombineArgs a, const 
 
 int stream_panel_width(int K)
 {
-    // equal panels, each a multiple of 32 and at most kPanelMax columns wide
-    if (K < 32) return 0;
-    for (int np = (K + kPanelMax - 1) / kPanelMax; np <= K / 32; ++np)
-        if (K % np == 0 && (K / np) % 32 == 0) return K / np;
+    // equal panels, each a multiple of 64 columns (128 bytes: a tile's 1 KB pieces must not straddle the middle of
+    // the tile, as for whole rows) and at most kPanelMax columns wide
+    if (K < 64) return 0;
+    for (int np = (K + kPanelMax - 1) / kPanelMax; np <= K / 64; ++np)
+        if (K % np == 0 && (K / np) % 64 == 0) return K / np;
     return 0;
 }
 

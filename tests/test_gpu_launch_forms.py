@@ -34,13 +34,14 @@ def _case(name):
         # 17-32 tokens: two token groups per pass; the two-launch form ranks two tokens per wavefront
         "twenty_four": dict(T=24, H=512, E=64, k=6, F=384, C=40, n_shared=1, F_shared=128, hidden="unit"),
         "thirty_two_e128": dict(T=32, H=256, E=128, k=8, F=128, C=96, hidden="unit"),
+        "panels_of_2112": dict(T=5, H=2112, E=7, k=2, F=256, C=3, n_shared=3, F_shared=192),
     }[name]
     return synth.make_layer(synth.small_recipe(name, 8800 + len(name), **kw))
 
 
 CASES = ["cfg1", "cfg2", "cfg3", "cfg4_c4", "sweep1_11", "sweep5_0", "sweep9_23", "sweep17_11", "one_token",
          "sixteen_tokens", "three_shared", "panels", "wide_shared_down", "all_miss", "k_equals_e", "e128", "twenty_four",
-         "thirty_two_e128"]
+         "thirty_two_e128", "panels_of_2112"]
 
 
 @pytest.mark.parametrize("case", CASES)

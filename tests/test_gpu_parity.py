@@ -73,6 +73,9 @@ EDGE_CASES = {
     "mult8_H_only": (303, dict(T=7, H=104, E=4, k=2, F=128, C=3)),
     "mult8_F_only": (304, dict(T=3, H=128, E=4, k=2, F=24, C=4)),
     "tall_hidden": (305, dict(T=4, H=8192, E=8, k=2, F=128, C=6, n_shared=1, Fs=64)),
+    # a hidden size whose halves are not multiples of 128 bytes (2112 = 2 x 1056): the panels must be thirds
+    "panels_of_2112": (306, dict(T=5, H=2112, E=7, k=2, F=256, C=3, n_shared=3, Fs=192)),
+    "panels_of_2112_no_pool": (307, dict(T=5, H=2112, E=7, k=2, F=256, C=0, n_shared=3, Fs=192)),
 }
 
 

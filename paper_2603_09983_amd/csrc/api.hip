@@ -346,6 +346,7 @@ int run_ffn(const void *hidden, const float *topk_w, const void *w_gate, const v
     c.T = T; c.H = H; c.F = F; c.k = k; c.n_shared = n_shared; c.F_shared = F_shared;
     c.out_bf16 = out_bf16; c.accumulate = accumulate;
     c.error_flag = (const unsigned *)(ws + w.ctrl) + kCtrlError;
+    c.miss_count = miss_count;
     hipError_t e;
     if (one_launch) {
         // small batch: gate/up, down and the final sum as one weight stream (routing != null: the routing steps too)

@@ -251,6 +251,7 @@ struct CombineArgs {
     const float *part, *part_sh;
     void *out;
     const unsigned *error_flag;   // control word set when a bounded wait ran out (then `out` is filled with NaN), or null
+    int32_t *miss_count;          // [1] or null: set to -1 in that case
     int T, H, F, k, n_shared, F_shared, out_bf16, accumulate;
 };
 

@@ -789,6 +789,7 @@ __global__ __launch_bounds__(128) void combine_rows_kernel(CombineArgs a, const 
     if (a.error_flag && *a.error_flag != 0u) {
         const float qnan = __uint_as_float(0x7fc00000u);
         acc = (f32x4){qnan, qnan, qnan, qnan};
+        if (a.miss_count && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.miss_count = -1;
     }
     if (a.out_bf16) {
         u32x2 v = {f32_to_bf16_rne(acc[0]) | (f32_to_bf16_rne(acc[1]) << 16),

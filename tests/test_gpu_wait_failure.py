@@ -27,6 +27,8 @@ def _call(d, buf, form, check=True):
     ("small", ("three", "two", "one", "route+one")),   # T <= 32: the final sum waits inside the down kernel
     ("cfg2", ("three", "two", "one", "route+one")),
     ("two_groups", ("three", "two")),                  # 17-32 tokens: two tokens per wavefront in the routing steps
+    ("separate_sum", ("three", "two")),                # 24 tokens whose strip of the final sum does not fit the down
+                                                       # kernel's tile buffer: a kernel of its own sums, and marks
     ("wide", ("three",)),                              # T > 32: a kernel of its own does the final sum
 ])
 def test_a_wait_that_runs_out_is_reported_and_recovered_from(case, forms):
@@ -39,6 +41,9 @@ def test_a_wait_that_runs_out_is_reported_and_recovered_from(case, forms):
     elif case == "two_groups":
         li = synth.make_layer(synth.small_recipe("wait_two_groups", 4713, T=24, H=256, E=16, k=4, F=128, C=12,
                                                  n_shared=1, F_shared=128))
+    elif case == "separate_sum":
+        li = synth.make_layer(synth.small_recipe("wait_separate_sum", 4714, T=24, H=256, E=64, k=8, F=64, C=45,
+                                                 n_shared=3, F_shared=192, hidden="unit"))
     else:
         li = synth.make_layer(synth.small_recipe("wait_wide", 4712, T=40, H=256, E=16, k=4, F=128, C=12,
                                                  n_shared=1, F_shared=128))

@@ -309,8 +309,10 @@ int moe_pool_load(const void *store_gate, const void *store_up, const void *stor
 /* Measurement aid (host-side state only; not part of the layer's arithmetic).
  * While enabled, every kernel the library launches is bracketed by a pair of
  * HIP events recorded on the caller's stream.  kind: MOE_KERNEL_*.
- * moe_profile_enable(1) creates the event pool (hipEventCreate, no device
- * memory) and clears the records; moe_profile_enable(0) stops recording.
+ * moe_profile_enable(1) clears the records (event pairs are made with
+ * hipEventCreate when a launch first needs one, up to 8192 per kind, and kept;
+ * no device memory); moe_profile_enable(0) stops recording.  The records are
+ * one set per process, not guarded: measure from one host thread.
  * moe_profile_read sums hipEventElapsedTime over the records of one kind; the
  * caller must have synchronised the stream.  total_ms, launches: host. */
 enum { MOE_KERNEL_ROUTE = 0, MOE_KERNEL_LISTS = 1, MOE_KERNEL_FFN = 2 /* gate/up (and down when fused) */,
@@ -323,8 +325,8 @@ const char *moe_profile_kernel_name(int kind);
 /* What a pair of events costs by itself: records `pairs` (1..8192) pairs on
  * `stream` with nothing in between, waits for the stream and returns the mean
  * interval in *avg_ms (host).  A bracketed kernel's record contains about this
- * much time that is not the kernel's.  Call after moe_profile_enable(1) and
- * after reading the records you need (it reuses the pairs of kind 0). */
+ * much time that is not the kernel's.  Uses event pairs of its own, which it
+ * creates and destroys; independent of moe_profile_enable. */
 int moe_profile_event_overhead(void *stream, int pairs, double *avg_ms);
 /* Timeline of the last launches of the streaming kernels, for a library built
  * with -DMOE_STREAM_TRACE (the product build returns MOE_ERR_SHAPE and writes

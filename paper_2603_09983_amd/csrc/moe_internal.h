@@ -203,7 +203,22 @@ struct StreamArgs {
     int T, k;
     int R, K, R_sh, K_sh, n_shared, C;
     int KP, KP_sh;             // panel widths (columns parked in LDS at a time)
+    // Filled in by the launch functions: panels per routed / shared item, and floor(2^32 / d) for the divisors of
+    // the kernel's index arithmetic (grid size, items per routed / shared expert, k, k + n_shared).  A division by a
+    // value only known at run time is ~30 instructions, and in the prologue of a launch sixteen wavefronts execute
+    // them one after the other on the compute unit's one scalar unit.
+    int np, np_sh;
+    unsigned rcp_G, rcp_tiles, rcp_tiles_sh, rcp_k, rcp_S;
 };
+
+// n / d with rcp = floor(2^32 / d) (d = 1: 2^32 - 1): the estimate is never too large and at most one short.
+__host__ __device__ static inline unsigned rcp32(unsigned d) { return d <= 1u ? 0xffffffffu : (unsigned)((1ull << 32) / d); }
+__device__ static inline int udiv_rcp(int n, int d, unsigned rcp)
+{
+    unsigned q = __umulhi((unsigned)n, rcp);
+    if ((unsigned)n - q * (unsigned)d >= (unsigned)d) ++q;
+    return (int)q;
+}
 
 // The weighted sum back into token order at the end of the down kernel (small batches).
 struct JoinArgs {

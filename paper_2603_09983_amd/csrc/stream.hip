@@ -136,7 +136,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
     const int G = gridDim.x, b = blockIdx.x;
     const int tiles = a.R / RPI, tiles_sh = a.n_shared ? a.R_sh / RPI : 0;
     const int n_sh_items = a.n_shared * tiles_sh;
-    const int sh_per = n_sh_items / G, sh_rem = n_sh_items % G;
+    const int sh_per = udiv_rcp(n_sh_items, G, a.rcp_G), sh_rem = n_sh_items - sh_per * G;
     // (FUSED: workgroup 0 also ranks the logits and builds the lists, which the others wait for; it takes
     // the last place in the split and, below, a shorter run)
     const int rk = FUSED ? (b == 0 ? G - 1 : b - 1) : b;
@@ -156,13 +156,13 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
             const size_t eoff = ((size_t)e * a.R_sh + (size_t)rt * RPI) * K;
             pw0 = (const unsigned char *)(a.s0 + eoff);
             pw1 = GATEUP ? (const unsigned char *)(a.s1 + eoff) : pw0 + (size_t)16 * K;
-            pK2 = 2 * K; prs = 2 * a.KP_sh; pnpan = K / a.KP_sh;
+            pK2 = 2 * K; prs = 2 * a.KP_sh; pnpan = a.np_sh;
         } else {
             const int K = a.K;
             const size_t eoff = ((size_t)active_s[e] * a.R + (size_t)rt * RPI) * K;
             pw0 = (const unsigned char *)(a.w0 + eoff);
             pw1 = GATEUP ? (const unsigned char *)(a.w1 + eoff) : pw0 + (size_t)16 * K;
-            pK2 = 2 * K; prs = 2 * a.KP; pnpan = K / a.KP;
+            pK2 = 2 * K; prs = 2 * a.KP; pnpan = a.np;
         }
     };
     auto prod_advance = [&]() {
@@ -175,7 +175,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
             pK2 = 0;
             pw1 = pw0;
         } else if (pp == s_cnt) {   // from the shared experts to the routed ones
-            const int e = r_start / tiles;
+            const int e = udiv_rcp(r_start, tiles, a.rcp_tiles);
             prod_set(false, e, r_start - e * tiles);
         } else if (prt + 1 == (psh ? tiles_sh : tiles)) {
             prod_set(psh, pe + 1, 0);
@@ -195,12 +195,12 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         csh = sh; ce = e; crt = rt; cpan = 0;
         cocol = rt * RPI * OB;
         if (sh) {
-            cK = a.K_sh; c_rs = 2 * a.KP_sh; cnpan = a.K_sh / a.KP_sh;
+            cK = a.K_sh; c_rs = 2 * a.KP_sh; cnpan = a.np_sh;
             cm = a.T; ckey = ALLTOK ? 0 : e; corow0 = e * a.T;
             cbrow0 = GATEUP ? 0 : e * a.T;            // hidden[n] | act_sh[e][n]
         } else {
             const int c = active_s[e];
-            cK = a.K; c_rs = 2 * a.KP; cnpan = a.K / a.KP;
+            cK = a.K; c_rs = 2 * a.KP; cnpan = a.np;
             cm = count_s[c]; ckey = ALLTOK ? 0 : a.n_shared + c; corow0 = offset_s[c];
             cbrow0 = ALLTOK ? 0 : GATEUP ? -1 : corow0;   // hidden[n] | hidden[token of list entry n] | act[row]
         }
@@ -211,7 +211,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         ++cp;
         if (cp >= cnt) return;
         if (cp == s_cnt) {
-            const int e = r_start / tiles;
+            const int e = udiv_rcp(r_start, tiles, a.rcp_tiles);
             cons_set(false, e, r_start - e * tiles);
         } else if (crt + 1 == (csh ? tiles_sh : tiles)) {
             cons_set(csh, ce + 1, 0);
@@ -322,7 +322,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
     bool bx_early = false;
     auto first_shared_item = [&]() {
         if (s_cnt == 0) return;
-        const int e = s_start / tiles_sh;
+        const int e = udiv_rcp(s_start, tiles_sh, a.rcp_tiles_sh);
         prod_set(true, e, s_start - e * tiles_sh);
         cons_set(true, e, s_start - e * tiles_sh);
         pvalid = true;
@@ -463,7 +463,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         }
         // token of each list entry (gate/up) | row of each assignment's output, -1 = not resident (join)
         if (GATEUP)
-            for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = a.perm[i] / a.k;
+            for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = udiv_rcp(a.perm[i], a.k, a.rcp_k);
         else if (JOIN)
             for (int i = tid; i < a.T * a.k; i += kThreads) perm_s[i] = jn.pos[i];
         n_act = (int)(*a.n_active);
@@ -475,7 +475,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         // (FUSED: workgroup 0 starts its run a few microseconds late: two items fewer for it)
         const int late = FUSED && n_act * tiles >= 4 * G ? 2 : 0;
         const int total = n_sh_items + n_act * tiles + late;
-        const int per = total / G, rem = total % G;
+        const int per = udiv_rcp(total, G, a.rcp_G), rem = total - per * G;
         cnt = per + (rk < rem ? 1 : 0);
         r_start = rk * per + (rk < rem ? rk : rem) - s_start;
         if (rk == G - 1) cnt -= late;
@@ -483,7 +483,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         // Workgroup x starts at routed item max(0, x * total tiles / G - tiles of the shared items
         // before x) / panels per routed item: that never decreases with x, is 0 for x = 0 and the
         // number of routed items for x = G.
-        const int np_r = a.K / a.KP, np_sh = a.K_sh / a.KP_sh;
+        const int np_r = a.np, np_sh = a.np_sh;
         const int n_routed = n_act * tiles;
         const long long total = (long long)n_sh_items * np_sh + (long long)n_routed * np_r;
         auto routed_before = [&](int x) {
@@ -515,7 +515,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         for (int u = b; u < a.R / 8; u += G) {
             __syncthreads();
             for (int i = tid; i < nent; i += kThreads) {
-                const int tc = i / S, src = i - tc * S, t = tc >> 3, col = u * 8 + (tc & 7);
+                const int tc = udiv_rcp(i, S, a.rcp_S), src = i - tc * S, t = tc >> 3, col = u * 8 + (tc & 7);
                 const u64 *p = nullptr;
                 if (src < a.k) {
                     const int row = perm_s[t * a.k + src];
@@ -566,9 +566,9 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
         join();
         return;
     }
-    const int ntiles = s_cnt * (a.n_shared ? a.K_sh / a.KP_sh : 0) + (cnt - s_cnt) * (a.K / a.KP);
+    const int ntiles = s_cnt * (a.n_shared ? a.np_sh : 0) + (cnt - s_cnt) * a.np;
     if (s_cnt == 0) {
-        const int e = r_start / tiles;
+        const int e = udiv_rcp(r_start, tiles, a.rcp_tiles);
         prod_set(false, e, r_start - e * tiles);
         cons_set(false, e, r_start - e * tiles);
         pvalid = true;
@@ -824,6 +824,21 @@ bool stream_can_join(const StreamArgs &d)
     return d.T <= 32 && d.R % 8 == 0 && (size_t)d.T * 8 * (d.k + d.n_shared) * 4 <= tile;
 }
 
+namespace {
+// the fields of StreamArgs that follow from the others and from the grid
+void fill_derived(StreamArgs &x, bool gateup, int grid)
+{
+    const int rpi = gateup ? 8 : 16;
+    x.np = x.KP > 0 ? x.K / x.KP : 1;
+    x.np_sh = x.n_shared > 0 && x.KP_sh > 0 ? x.K_sh / x.KP_sh : 1;
+    x.rcp_G = rcp32((unsigned)grid);
+    x.rcp_tiles = rcp32((unsigned)(x.R / rpi));
+    x.rcp_tiles_sh = rcp32((unsigned)(x.n_shared > 0 ? x.R_sh / rpi : 1));
+    x.rcp_k = rcp32((unsigned)x.k);
+    x.rcp_S = rcp32((unsigned)(x.k + x.n_shared));
+}
+}  // namespace
+
 hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join, hipStream_t s)
 {
     if (join && (gateup || !stream_can_join(a))) return hipErrorInvalidValue;
@@ -863,6 +878,7 @@ hipError_t launch_stream(const StreamArgs &a, bool gateup, const JoinArgs *join,
     if (e != hipSuccess) return e;
     int tile_i = (int)tile;
     StreamArgs args = a;
+    fill_derived(args, gateup, grid);
     JoinArgs jargs = {};
     if (join) jargs = *join;
     void *params[] = {&args, &tile_i, &jargs};
@@ -893,6 +909,7 @@ hipError_t launch_stream_routed(const StreamArgs &a, const RouteArgs &r, hipStre
     if (e != hipSuccess) return e;
     int tile_i = (int)tile;
     StreamArgs args = a;
+    fill_derived(args, true, grid);
     RouteArgs rargs = r;
     void *params[] = {&args, &tile_i, &rargs};
     hipError_t le = launch_timed(fn, dim3(grid), dim3(kThreads), params, lds, s, 2);

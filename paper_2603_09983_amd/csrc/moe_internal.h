@@ -49,10 +49,11 @@ static inline bool use_stream_kernels(int T, int k, int C, int H, int F, int n_s
 
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
-// Small batches: the gate/up kernel does the routing itself (dot products by all workgroups, ranking and
-// lists by workgroup 0, which hands the lists to the others as stamped 64-bit words, kListReplicas copies
-// so that not all workgroups poll the same lines).  One copy: n_active | slot_count[C] | slot_offset[C] |
-// active_slots[C] | perm[T*k].
+// Small batches: the routing steps run inside a larger launch (dot products by all workgroups).  In the
+// one-launch kernel workgroup 0 ranks and hands the lists to the others as stamped 64-bit words, kListReplicas
+// copies so that not all workgroups poll the same lines; one copy: n_active | slot_count[C] | slot_offset[C] |
+// active_slots[C] | perm[T*k].  In the gate/up kernel of the two-launch form every workgroup ranks the stamped
+// logits for itself (kLogitReplicas copies of those) and only the per-workgroup words behind the copies are used.
 constexpr int kListReplicas = 16;
 constexpr int kLogitReplicas = 16;  // copies of the stamped logits when every workgroup ranks them itself (<= lanes that store)
 constexpr int kMaxGroups = 1024;   // workgroups of that launch (one stamped word each, behind the copies)

@@ -278,7 +278,7 @@ inline size_t post_lds_bytes(int E, int C, int A, bool with_topk)
     return n * sizeof(int);
 }
 
-constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before workgroup 0 gives up waiting
+constexpr int kSpinLimit = 1 << 20;   // polls of an entry in memory before a waiting workgroup gives up
 
 // Small batches (T <= 128, one thread per assignment and per slot): the tokens of each slot as a
 // bit mask of NW = ceil(T/32) words (a token names a slot at most once, the slot table being

@@ -22,7 +22,9 @@
 // Work is a flat list of items (expert, tile of 16 MFMA rows) over the shared experts
 // and the ACTIVE resident slots only; a fixed grid of one 16-wavefront workgroup per CU
 // takes equal contiguous runs of it, so all workgroups are resident at once,
-// share the HBM bandwidth evenly and finish together.
+// share the HBM bandwidth evenly and finish together.  (Runs are cut at whole tiles
+// on purpose: measured, a tile with fewer rows costs a workgroup as much time as a
+// whole one, since its requests wait in the same queues behind everybody's whole tiles.)
 #include "moe_internal.h"
 #include "route_device.h"
 
@@ -137,8 +139,8 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
     const int tiles = a.R / RPI, tiles_sh = a.n_shared ? a.R_sh / RPI : 0;
     const int n_sh_items = a.n_shared * tiles_sh;
     const int sh_per = udiv_rcp(n_sh_items, G, a.rcp_G), sh_rem = n_sh_items - sh_per * G;
-    // (FUSED: workgroup 0 also ranks the logits and builds the lists, which the others wait for; it takes
-    // the last place in the split and, below, a shorter run)
+    // (FUSED: workgroup 0 also writes the step outputs and waits for every workgroup's word before it gives the
+    // call its number; it takes the last place in the split and, below, a shorter run)
     const int rk = FUSED ? (b == 0 ? G - 1 : b - 1) : b;
     const int s_cnt = sh_per + (rk < sh_rem ? 1 : 0);
     const int s_start = rk * sh_per + (rk < sh_rem ? rk : sh_rem);

@@ -654,6 +654,8 @@ def main():
                    "mean_weight_bytes_per_layer": int(np.mean(layer_bytes))},
         "roofline": roofline, "cpu_baseline": cpu, "north_star_rows": rows, "launch_forms": launch_forms,
         "estimator": est,
+        # (the same object as estimator.cache_manager.prefetch_overlap: verify steps beside the cache manager's copy)
+        "prefetch_overlap": (est or {}).get("cache_manager", {}).get("prefetch_overlap"),
     }
     if args.timeline:
         print_timeline(B, torch, np, step, len(layers))

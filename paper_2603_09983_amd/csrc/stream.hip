@@ -140,7 +140,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
     const int n_sh_items = a.n_shared * tiles_sh;
     const int sh_per = udiv_rcp(n_sh_items, G, a.rcp_G), sh_rem = n_sh_items - sh_per * G;
     // (FUSED: workgroup 0 also writes the step outputs and waits for every workgroup's word before it gives the
-    // call its number; it takes the last place in the split and, below, a shorter run)
+    // call its number; it takes the last place in the split, whose run is never the longer one)
     const int rk = FUSED ? (b == 0 ? G - 1 : b - 1) : b;
     const int s_cnt = sh_per + (rk < sh_rem ? 1 : 0);
     const int s_start = rk * sh_per + (rk < sh_rem ? rk : sh_rem);
@@ -474,13 +474,10 @@ __device__ __forceinline__ void stream_body(const StreamArgs &a, const int tile_
 
     // equal runs of the whole item list; this workgroup's run = its shared items, then routed ones
     if (!WSPLIT) {
-        // (FUSED: workgroup 0 starts its run a few microseconds late: two items fewer for it)
-        const int late = FUSED && n_act * tiles >= 4 * G ? 2 : 0;
-        const int total = n_sh_items + n_act * tiles + late;
+        const int total = n_sh_items + n_act * tiles;
         const int per = udiv_rcp(total, G, a.rcp_G), rem = total - per * G;
         cnt = per + (rk < rem ? 1 : 0);
         r_start = rk * per + (rk < rem ? rk : rem) - s_start;
-        if (rk == G - 1) cnt -= late;
     } else {
         // Workgroup x starts at routed item max(0, x * total tiles / G - tiles of the shared items
         // before x) / panels per routed item: that never decreases with x, is 0 for x = 0 and the
